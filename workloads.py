@@ -1,0 +1,108 @@
+"""Seeded synthetic inputs and the benchmark layer shapes.
+
+This module serves both the CPU oracle's callers and the HIP library's callers
+and holds none of the method's arithmetic: it only names layer shapes and draws
+random tensors.  The shapes stand in for the paper's benchmark set (Section VI:
+convolutions taken from AlexNet, NiN and GoogLeNetV1 at several batch sizes,
+whose list the paper does not print); every tensor is synthetic.
+"""
+from collections import namedtuple
+
+import numpy as np
+
+# One forward-convolution problem.  dist_in: "u01" uniform[0,1) or "u11"
+# uniform[-1,1); dist_filt: "n001" normal(0, std 0.01) or "u11"; dist_bias:
+# "zero" (a real all-zero array), "u01b" uniform[-0.1,0.1) or "none" (NULL).
+Layer = namedtuple("Layer", "name C H W K R S stride pad dist_in dist_filt dist_bias")
+
+BASE_SEED = 160600094
+
+TOY = Layer("toy3x3", 3, 32, 32, 16, 3, 3, 1, 1, "u11", "u11", "u01b")
+CONV1 = Layer("conv1_11x11s4", 3, 227, 227, 96, 11, 11, 4, 0, "u01", "n001", "zero")
+CONV2 = Layer("conv2_5x5", 96, 27, 27, 256, 5, 5, 1, 2, "u01", "n001", "u01b")
+CONV3 = Layer("conv3_3x3", 256, 13, 13, 384, 3, 3, 1, 1, "u01", "n001", "u01b")
+CONV4 = Layer("conv4_3x3", 384, 13, 13, 384, 3, 3, 1, 1, "u01", "n001", "u01b")
+CONV5 = Layer("conv5_3x3", 384, 13, 13, 256, 3, 3, 1, 1, "u01", "n001", "u01b")
+PW_A = Layer("pw_480x14_192", 480, 14, 14, 192, 1, 1, 1, 0, "u01", "n001", "u01b")
+PW_B = Layer("pw_832x7_384", 832, 7, 7, 384, 1, 1, 1, 0, "u01", "n001", "u01b")
+PW_C = Layer("pw_192x28_64", 192, 28, 28, 64, 1, 1, 1, 0, "u01", "n001", "u01b")
+RED3 = Layer("red3x3_96x28_128", 96, 28, 28, 128, 3, 3, 1, 1, "u01", "n001", "u01b")
+RED5 = Layer("red5x5_16x28_32", 16, 28, 28, 32, 5, 5, 1, 2, "u01", "n001", "u01b")
+
+# The groups follow the five benchmark configurations.
+CONFIG_TOY = [TOY]
+CONFIG_FIRST = [CONV1]
+CONFIG_MIDDLE = [CONV2, CONV3, CONV4, CONV5]
+CONFIG_POINTWISE = [PW_A, PW_B, PW_C, RED3, RED5]
+STACK = [CONV1, CONV2, CONV3, CONV4, CONV5]   # 3x3/s2 max-pool after conv1 and conv2
+STACK_POOL_AFTER = (0, 1)
+ALL_LAYERS = CONFIG_TOY + CONFIG_FIRST + CONFIG_MIDDLE + CONFIG_POINTWISE
+BY_NAME = {l.name: l for l in ALL_LAYERS}
+
+
+def out_hw(layer):
+    """Output height/width of a layer (floor form of the Section II size rule)."""
+    P = (layer.H + 2 * layer.pad - layer.R) // layer.stride + 1
+    Q = (layer.W + 2 * layer.pad - layer.S) // layer.stride + 1
+    return P, Q
+
+
+def _draw(rng, dist, shape):
+    if dist == "u01":
+        return rng.random(shape, dtype=np.float32)
+    if dist == "u11":
+        return (rng.random(shape, dtype=np.float32) * 2.0 - 1.0).astype(np.float32)
+    if dist == "n001":
+        return (rng.standard_normal(shape, dtype=np.float32) * np.float32(0.01)).astype(np.float32)
+    if dist == "u01b":
+        return ((rng.random(shape, dtype=np.float32) * 2.0 - 1.0)
+                * np.float32(0.1)).astype(np.float32)
+    if dist == "zero":
+        return np.zeros(shape, dtype=np.float32)
+    raise ValueError(dist)
+
+
+def layer_seed(layer, N):
+    """Seed of one (layer, batch) problem: base + 1000*index + N."""
+    idx = [l.name for l in ALL_LAYERS].index(layer.name)
+    return BASE_SEED + 1000 * idx + N
+
+
+def make_layer_inputs(layer, N, seed=None):
+    """(in[N,C,H,W], filt[K,C,R,S], bias[K] or None), fp32, drawn in that order."""
+    rng = np.random.default_rng(layer_seed(layer, N) if seed is None else seed)
+    x = _draw(rng, layer.dist_in, (N, layer.C, layer.H, layer.W))
+    f = _draw(rng, layer.dist_filt, (layer.K, layer.C, layer.R, layer.S))
+    b = None if layer.dist_bias == "none" else _draw(rng, layer.dist_bias, (layer.K,))
+    return x, f, b
+
+
+def make_random_problem(seed, N, C, H, W, K, R, S, dist="u11", with_bias=True):
+    """Free-form seeded problem for fuzz / edge-case tests."""
+    rng = np.random.default_rng(seed)
+    x = _draw(rng, dist, (N, C, H, W))
+    f = _draw(rng, dist, (K, C, R, S))
+    b = _draw(rng, "u01b", (K,)) if with_bias else None
+    return x, f, b
+
+
+def make_integer_problem(seed, N, C, H, W, K, R, S, lo=-2, hi=2, with_bias=True):
+    """Small-integer data: every product and partial sum is an integer below
+    2**24, so fp32 arithmetic in any order is exact."""
+    rng = np.random.default_rng(seed)
+    x = rng.integers(lo, hi + 1, size=(N, C, H, W)).astype(np.float32)
+    f = rng.integers(lo, hi + 1, size=(K, C, R, S)).astype(np.float32)
+    b = rng.integers(-3, 4, size=(K,)).astype(np.float32) if with_bias else None
+    return x, f, b
+
+
+def make_stack_inputs(N, seed=None):
+    """Image batch plus (filt, bias) per layer for the five-conv stack."""
+    rng = np.random.default_rng(BASE_SEED + 50000 + N if seed is None else seed)
+    img = _draw(rng, "u01", (N, CONV1.C, CONV1.H, CONV1.W))
+    params = []
+    for l in STACK:
+        f = _draw(rng, l.dist_filt, (l.K, l.C, l.R, l.S))
+        b = _draw(rng, "u01b", (l.K,))
+        params.append((f, b))
+    return img, params
