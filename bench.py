@@ -1,0 +1,253 @@
+"""Benchmark of the forward convolution library on one MI355X.
+
+A step is one pass of the hot path over every benchmark layer shape (first
+layer, the four middle layers, the three pointwise and the two reduce layers)
+at batch 32, each call = variant selection + tiled MFMA kernel (+ split
+reduction) with fused bias + ReLU, inputs already resident in HBM.  `value` is
+the algorithmic GFLOP/s of that pass (2 flops per multiply-accumulate, the
+convention of the paper's SGEMM tables).  The same JSON line carries the
+per-layer table at batch 1 and 32 with both roofline fractions, the five-layer
+stack at batch 1/5/20/32, the roofline of the dominant kernel measured with HIP
+events, and the CPU oracle timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "conv fwd GFLOP/s (fp32) per layer at batch 1 and 32; % of fp32 MFMA/HBM roof"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class LayerProblem:
+    """Device tensors of one (layer, N) problem, `copies` rotating sets."""
+
+    def __init__(self, layer, N, copies=1):
+        import torch
+        import workloads
+        from paper_1606_00094_amd import binding, roofline
+        self.layer, self.N = layer, N
+        dev = torch.device("cuda:0")
+        x, f, b = workloads.make_layer_inputs(layer, N)
+        P, Q = workloads.out_hw(layer)
+        self.dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        self.flops = roofline.conv_flops(*self.dims)
+        self.bytes = roofline.conv_bytes(*self.dims)
+        self.variant = binding.conv_selected_variant(*self.dims)
+        need = binding.conv_fwd_workspace_bytes(*self.dims, self.variant)
+        self.ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
+        self.sets = []
+        for c in range(copies):
+            self.sets.append((xd if c == 0 else xd.clone(), fd if c == 0 else fd.clone(), bd,
+                              torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)))
+        self.k = 0
+
+    def launch(self):
+        from paper_1606_00094_amd import binding
+        x, f, b, o = self.sets[self.k]
+        self.k = (self.k + 1) % len(self.sets)
+        binding.conv_fwd_ex(x, f, b, o, self.layer.stride, self.layer.pad, True,
+                            workspace=self.ws, variant=self.variant)
+
+
+def time_launches(fn, reps, warm=3):
+    """Average milliseconds per call of fn over `reps` back-to-back calls, by HIP
+    events on torch's current stream (the stream the library launches on)."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def layer_row(prob, ms, mode):
+    from paper_1606_00094_amd import binding, roofline
+    t = ms * 1e-3
+    return {
+        "layer": prob.layer.name, "N": prob.N, "mode": mode,
+        "variant": binding.conv_variant_name(prob.variant),
+        "us": round(ms * 1e3, 2),
+        "gflops": round(prob.flops / t / 1e9, 1),
+        "frac_mfma": round(prob.flops / t / 1e12 / roofline.PEAK_FP32_MFMA_TFLOPS, 4),
+        "gbps": round(prob.bytes / t / 1e9, 1),
+        "frac_hbm": round(prob.bytes / t / 1e9 / roofline.PEAK_HBM_GBPS, 4),
+    }
+
+
+def run_stack(N, reps):
+    """Five-layer stack with 3x3/s2 max pooling after the first two layers."""
+    import torch
+    import workloads
+    from paper_1606_00094_amd import binding, roofline
+    dev = torch.device("cuda:0")
+    img, params = workloads.make_stack_inputs(N)
+    cur_shape = img.shape
+    bufs, plan, flops = [torch.from_numpy(img).to(dev)], [], 0
+    for li, (layer, (f, b)) in enumerate(zip(workloads.STACK, params)):
+        n, c, h, w = cur_shape
+        dims = (n, c, h, w, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        P, Q = binding.conv_out_dims(h, w, layer.R, layer.S, layer.stride, layer.pad)
+        v = binding.conv_selected_variant(*dims)
+        need = binding.conv_fwd_workspace_bytes(*dims, v)
+        ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        out = torch.empty((n, layer.K, P, Q), dtype=torch.float32, device=dev)
+        plan.append(("conv", len(bufs) - 1, len(bufs), torch.from_numpy(f).to(dev),
+                     torch.from_numpy(b).to(dev), layer, ws, v))
+        bufs.append(out)
+        flops += roofline.conv_flops(*dims)
+        cur_shape = out.shape
+        if li in workloads.STACK_POOL_AFTER:
+            pooled = torch.empty((n, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1),
+                                 dtype=torch.float32, device=dev)
+            plan.append(("pool", len(bufs) - 1, len(bufs)))
+            bufs.append(pooled)
+            cur_shape = pooled.shape
+
+    def step():
+        for op in plan:
+            if op[0] == "conv":
+                _, i, o, f, b, layer, ws, v = op
+                binding.conv_fwd_ex(bufs[i], f, b, bufs[o], layer.stride, layer.pad, True,
+                                    workspace=ws, variant=v)
+            else:
+                binding.maxpool_fwd(bufs[op[1]], bufs[op[2]], 3, 2)
+
+    ms = time_launches(step, reps)
+    return {"N": N, "ms": round(ms, 4), "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
+            "frac_mfma": round(flops / (ms * 1e-3) / 1e12 / roofline.PEAK_FP32_MFMA_TFLOPS, 4)}
+
+
+def cpu_baseline(layers, N):
+    """The oracle as it stands, timed on this machine's host cores over one pass of
+    the same layer set at batch N (bounded: a single execution per layer)."""
+    import oracle
+    import workloads
+    from paper_1606_00094_amd import roofline
+    oracle.build()
+    flops, secs = 0, 0.0
+    for layer in layers:
+        x, f, b = workloads.make_layer_inputs(layer, N)
+        t0 = time.perf_counter()
+        oracle.conv_fwd(x, f, b, stride=layer.stride, pad=layer.pad, relu=True)
+        secs += time.perf_counter() - t0
+        flops += roofline.conv_flops(N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S,
+                                     layer.stride, layer.pad)
+    return {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(secs, 2),
+            "sample": "one pass of the %d benchmark layers at batch %d (%.1f GFLOP)"
+                      % (len(layers), N, flops / 1e9)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-layer-table", action="store_true")
+    ap.add_argument("--cpu-baseline-batch", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (--gpus %d refused)" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    from paper_1606_00094_amd import binding, roofline
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the library has no CPU path")
+        sys.exit(1)
+    binding.lib()
+    torch.cuda.set_device(0)
+
+    layers = workloads.CONFIG_FIRST + workloads.CONFIG_MIDDLE + workloads.CONFIG_POINTWISE
+    probs = [LayerProblem(l, args.batch) for l in layers]
+    total_flops = sum(p.flops for p in probs)
+
+    def step():
+        for p in probs:
+            p.launch()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = max(e0.elapsed_time(e1) / args.steps, 0.0)
+    # whole-job rate uses the host clock around the synchronised region
+    value = total_flops / (wall_ms * 1e-3) / 1e9
+    log("step: %.3f ms wall, %.3f ms by events, %.1f GFLOP/s" % (wall_ms, ms_per_step, value))
+
+    # ---- per-layer table
+    table = []
+    per_layer_ms = {}
+    for p in probs:
+        ms = time_launches(p.launch, 30)
+        per_layer_ms[p.layer.name] = ms
+        table.append(layer_row(p, ms, "warm"))
+    if not args.no_layer_table:
+        for l in [workloads.TOY] + layers:
+            p1 = LayerProblem(l, 1)
+            table.append(layer_row(p1, time_launches(p1.launch, 200, warm=10), "warm"))
+            # cold: rotate through enough distinct tensor sets that nothing stays in cache
+            copies = int(min(256, max(2, (600 << 20) // max(1, p1.bytes))))
+            pc = LayerProblem(l, 1, copies=copies)
+            table.append(layer_row(pc, time_launches(pc.launch, copies, warm=2), "cold"))
+            del p1, pc
+    for row in table:
+        log(json.dumps(row))
+
+    # ---- roofline of the dominant kernel (largest share of the step)
+    dom = max(probs, key=lambda p: per_layer_ms[p.layer.name])
+    dom_ms = time_launches(dom.launch, 50)
+    achieved = dom.flops / (dom_ms * 1e-3) / 1e12
+    roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": roofline.PEAK_FP32_MFMA_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(achieved / roofline.PEAK_FP32_MFMA_TFLOPS, 4),
+            "traffic": None, "kernel": binding.conv_variant_name(dom.variant),
+            "layer": dom.layer.name, "N": dom.N, "us_per_launch": round(dom_ms * 1e3, 2)}
+
+    stack = [] if args.no_layer_table else [run_stack(n, 20) for n in (1, 5, 20, 32)]
+    for row in stack:
+        log(json.dumps({"stack": row}))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(layers, args.cpu_baseline_batch)
+        log(json.dumps(cpu))
+
+    print(json.dumps({
+        "metric": METRIC, "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "one pass over the 10 benchmark conv layers (first layer, 4 middle, "
+                               "3 pointwise, 2 reduce) at batch %d, bias + ReLU fused" % args.batch,
+                   "batch": args.batch, "gflop_per_step": round(total_flops / 1e9, 2)},
+        "roofline": roof, "cpu_baseline": cpu, "layers": table, "stack": stack,
+    }), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,113 @@
+/*
+ * bconv.h -- C ABI of the MI355X (gfx950) forward convolution library.
+ *
+ * The operation is the convolution layer of the paper's Section II:
+ *   out[n,k,p,q] = act( bias[k] + sum_{c,r,s} in[n,c,p*stride-pad+r,q*stride-pad+s]
+ *                                             * filt[k,c,r,s] )
+ * i.e. for every output point the window of the input starting at
+ * (p*stride, q*stride) (in zero-padded coordinates) over all input channels is
+ * multiplied element-wise with filter k and summed, with no filter flip; images
+ * of a batch are independent; act is the identity or ReLU max(0,x), fused
+ * (Section II: the activation "is often fused into the convolution").  The
+ * per-output-channel bias, which the paper leaves out of its discussion, is
+ * added before the activation.  Output extent (Section II size rule, floor
+ * reading):  P = floor((H + 2*pad - R)/stride) + 1, same for Q with W, S.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *     reads in/filt/bias and writes out, and never frees or keeps them.
+ *   - Layouts are dense row-major fp32: in N*C*H*W, filt K*C*R*S, bias K (or
+ *     NULL = no bias), out N*K*P*Q.  out must not overlap any input.
+ *     4-byte alignment is enough.
+ *   - Calls only enqueue work on a HIP stream and return; they never
+ *     synchronise it.  `hip_stream` is a hipStream_t passed as void* (NULL = the
+ *     null stream).
+ *   - Return value: BCONV_OK (0) or a negative bconv_status; on error nothing
+ *     has been launched.  No C++ exception crosses the boundary.
+ *   - One scalar stride and one scalar pad apply to both axes (Section II:
+ *     kernel size and stride taken as scalars); R and S are independent.
+ *     No groups, no dilation.
+ */
+#ifndef BCONV_H
+#define BCONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BCONV_OK = 0,
+  BCONV_EINVAL = -1,     /* non-positive dimension, stride <= 0, pad < 0, relu not 0/1 */
+  BCONV_ENULL = -2,      /* a required pointer is NULL */
+  BCONV_ESHAPE = -3,     /* no output point: H + 2*pad < R or W + 2*pad < S, or tensor too large */
+  BCONV_EWORKSPACE = -4, /* workspace missing or smaller than conv_fwd_workspace_bytes() */
+  BCONV_ELAUNCH = -5,    /* the HIP runtime refused an allocation or a launch */
+  BCONV_EVARIANT = -6    /* variant id out of range or not applicable to this shape */
+} bconv_status;
+
+/* Section II output-size rule.  Host only.  Writes *P, *Q. */
+int conv_out_dims(int H, int W, int R, int S, int stride, int pad, int* P, int* Q);
+
+/* Forward convolution + bias + optional ReLU on the null stream, variant chosen
+ * by the selection table (the role of the paper's per-operation variant and
+ * blocking choice, Section V "blocking strategy" and Section VI variants).
+ * If the chosen variant splits the reduction, partial sums go to a workspace
+ * the library allocates once per device and keeps until the process ends. */
+int conv_fwd(const float* in, const float* filt, const float* bias, float* out,
+             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+             int relu);
+
+/* Same operation with explicit stream, workspace and variant.
+ *   workspace / workspace_bytes: device scratch of at least
+ *     conv_fwd_workspace_bytes(..., variant_id) bytes, 256-byte aligned; may be
+ *     NULL/0 when that function returns 0.  Contents before and after are
+ *     unspecified.  Two calls that share a workspace must be ordered on one stream.
+ *   variant_id: -1 = selection table; 0 .. conv_num_variants()-1 = forced
+ *     (tests, tuning sweeps); a variant that cannot run the shape gives
+ *     BCONV_EVARIANT. */
+int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* out,
+                int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                int relu, void* workspace, size_t workspace_bytes, void* hip_stream,
+                int variant_id);
+
+/* Bytes of workspace conv_fwd_ex needs for this shape and variant (0 if none;
+ * also 0 for arguments conv_fwd_ex would reject). */
+size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
+                                int stride, int pad, int variant_id);
+
+/* Variant catalogue.  A variant is a kernel family + tile shape + reduction
+ * split; the ids are stable within one build of the library. */
+int conv_num_variants(void);
+/* Writes a NUL-terminated name into buf (truncated to buflen). */
+int conv_variant_name(int variant_id, char* buf, size_t buflen);
+/* The variant conv_fwd would run for this shape, or a negative status. */
+int conv_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride,
+                          int pad);
+/* 1 if the variant can run the shape, 0 if not, negative status on bad arguments. */
+int conv_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int stride,
+                            int pad, int variant_id);
+
+/* Host-only diagnostic: walks every workgroup, thread and reduction chunk of the
+ * launch that (shape, variant) would produce, using the same index functions as
+ * the device code, and counts LDS or global accesses that would fall outside
+ * their buffers.  Returns that count (0 = clean) or a negative status.  Touches
+ * no GPU. */
+long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int stride,
+                            int pad, int variant_id);
+
+/* Max pooling over ksz x ksz windows stepped by `stride`, no padding, floor
+ * extents (the pooling primitive the paper names in Section I-A among the
+ * deployment operations; used to chain the five-layer stack).
+ * in N*C*H*W -> out N*C*P*Q with P = floor((H-ksz)/stride)+1. */
+int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz,
+                int stride, void* hip_stream);
+
+/* Static, human-readable text for a status code. */
+const char* bconv_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCONV_H */

@@ -1,0 +1,162 @@
+"""Thin ctypes binding of libbconv's C ABI (see include/bconv.h).
+
+Argument marshalling only: tensors must already be contiguous fp32 on the GPU;
+every step of the computation runs in the library's HIP kernels.  There is no
+CPU fallback: if libbconv.so is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbconv.so")
+_lib = None
+
+_vp = ctypes.c_void_p
+_i = ctypes.c_int
+_sz = ctypes.c_size_t
+
+EXPORTS = {
+    "conv_out_dims": ([_i] * 6 + [ctypes.POINTER(_i)] * 2, _i),
+    "conv_fwd": ([_vp] * 4 + [_i] * 10, _i),
+    "conv_fwd_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
+    "conv_fwd_workspace_bytes": ([_i] * 10, _sz),
+    "conv_num_variants": ([], _i),
+    "conv_variant_name": ([_i, ctypes.c_char_p, _sz], _i),
+    "conv_selected_variant": ([_i] * 9, _i),
+    "conv_variant_applicable": ([_i] * 10, _i),
+    "bconv_debug_audit": ([_i] * 10, ctypes.c_longlong),
+    "maxpool_fwd": ([_vp] * 2 + [_i] * 6 + [_vp], _i),
+    "bconv_strerror": ([_i], ctypes.c_char_p),
+}
+
+
+class BconvError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, strerror(status)))
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libbconv.so not built: run `python -m paper_1606_00094_amd.build` "
+                               "(there is no CPU fallback)")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (argtypes, restype) in EXPORTS.items():
+            fn = getattr(handle, name)
+            fn.argtypes = argtypes
+            fn.restype = restype
+        _lib = handle
+    return _lib
+
+
+def strerror(status):
+    return lib().bconv_strerror(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise BconvError(status, where)
+
+
+def _dev_ptr(t, name):
+    import torch
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32
+            and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous float32 tensor on the GPU" % name)
+    return t.data_ptr()
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def conv_out_dims(H, W, R, S, stride, pad):
+    P, Q = _i(0), _i(0)
+    _check(lib().conv_out_dims(H, W, R, S, stride, pad, ctypes.byref(P), ctypes.byref(Q)),
+           "conv_out_dims")
+    return P.value, Q.value
+
+
+def _dims(inp, filt):
+    N, C, H, W = inp.shape
+    K, C2, R, S = filt.shape
+    if C != C2:
+        raise ValueError("in has %d channels, filt expects %d" % (C, C2))
+    return N, C, H, W, K, R, S
+
+
+def conv_fwd_ex(inp, filt, bias, out, stride, pad, relu, workspace=None, stream=None, variant=-1):
+    """conv_fwd_ex of the C ABI on torch tensors; enqueues on `stream` (default: torch's
+    current stream) and returns `out`."""
+    N, C, H, W, K, R, S = _dims(inp, filt)
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    if tuple(out.shape) != (N, K, P, Q):
+        raise ValueError("out must have shape %s" % ((N, K, P, Q),))
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib().conv_fwd_ex(_dev_ptr(inp, "in"), _dev_ptr(filt, "filt"), _dev_ptr(bias, "bias"),
+                             _dev_ptr(out, "out"), N, C, H, W, K, R, S, stride, pad,
+                             1 if relu else 0, ws_ptr, ws_bytes, _stream_handle(stream),
+                             int(variant)), "conv_fwd_ex")
+    return out
+
+
+def conv_fwd(inp, filt, bias, out, stride, pad, relu):
+    """conv_fwd of the C ABI (null stream, selection table, internal workspace)."""
+    N, C, H, W, K, R, S = _dims(inp, filt)
+    _check(lib().conv_fwd(_dev_ptr(inp, "in"), _dev_ptr(filt, "filt"), _dev_ptr(bias, "bias"),
+                          _dev_ptr(out, "out"), N, C, H, W, K, R, S, stride, pad,
+                          1 if relu else 0), "conv_fwd")
+    return out
+
+
+def conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant=-1):
+    return int(lib().conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, int(variant)))
+
+
+def conv_num_variants():
+    return int(lib().conv_num_variants())
+
+
+def conv_variant_name(variant):
+    buf = ctypes.create_string_buffer(96)
+    _check(lib().conv_variant_name(int(variant), buf, len(buf)), "conv_variant_name")
+    return buf.value.decode()
+
+
+def conv_selected_variant(N, C, H, W, K, R, S, stride, pad):
+    v = int(lib().conv_selected_variant(N, C, H, W, K, R, S, stride, pad))
+    if v < 0:
+        raise BconvError(v, "conv_selected_variant")
+    return v
+
+
+def conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, variant):
+    v = int(lib().conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, int(variant)))
+    if v < 0:
+        raise BconvError(v, "conv_variant_applicable")
+    return bool(v)
+
+
+def bconv_debug_audit(N, C, H, W, K, R, S, stride, pad, variant):
+    return int(lib().bconv_debug_audit(N, C, H, W, K, R, S, stride, pad, int(variant)))
+
+
+def maxpool_fwd(inp, out, ksz, stride, stream=None):
+    N, C, H, W = inp.shape
+    _check(lib().maxpool_fwd(_dev_ptr(inp, "in"), _dev_ptr(out, "out"), N, C, H, W, ksz, stride,
+                             _stream_handle(stream)), "maxpool_fwd")
+    return out
+
+
+def variant_ids_by_name():
+    return {conv_variant_name(v): v for v in range(conv_num_variants())}

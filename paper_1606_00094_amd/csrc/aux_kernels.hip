@@ -1,0 +1,107 @@
+// Small kernels around the tiled MFMA convolution: the plain direct convolution
+// (always-applicable fallback, variant 0), the split-K reduction with the fused
+// bias + ReLU epilogue, and max pooling.
+#include "bconv_internal.h"
+
+namespace bconv {
+
+// One thread per output point, loops over (c, r, s): the definition of the
+// paper's Section II executed literally, fp32 accumulation, 64-bit indexing.
+__global__ __launch_bounds__(256)
+void direct_conv_kernel(const float* __restrict__ in, const float* __restrict__ filt,
+                        const float* __restrict__ bias, float* __restrict__ out, Shape s,
+                        int relu, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    int q = (int)(idx % s.Q);
+    long long t = idx / s.Q;
+    int p = (int)(t % s.P);
+    t /= s.P;
+    int k = (int)(t % s.K);
+    int n = (int)(t / s.K);
+    const int ih0 = p * s.stride - s.pad, iw0 = q * s.stride - s.pad;
+    float acc = 0.0f;
+    for (int c = 0; c < s.C; ++c) {
+      const float* ip = in + ((long long)n * s.C + c) * s.H * s.W;
+      const float* fp = filt + ((long long)k * s.C + c) * s.R * s.S;
+      for (int r = 0; r < s.R; ++r) {
+        int ih = ih0 + r;
+        if (ih < 0 || ih >= s.H) continue;
+        for (int ss = 0; ss < s.S; ++ss) {
+          int iw = iw0 + ss;
+          if (iw < 0 || iw >= s.W) continue;
+          acc = fmaf(ip[(long long)ih * s.W + iw], fp[r * s.S + ss], acc);
+        }
+      }
+    }
+    if (bias) acc += bias[k];
+    if (relu) acc = acc > 0.0f ? acc : 0.0f;
+    out[idx] = acc;
+  }
+}
+
+hipError_t launch_direct_conv(const float* in, const float* filt, const float* bias, float* out,
+                              const Shape& s, int relu, hipStream_t st) {
+  long long total = (long long)s.N * s.K * s.P * s.Q;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 65536 * 16) blocks = 65536 * 16;
+  hipLaunchKernelGGL(direct_conv_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, filt, bias,
+                     out, s, relu, total);
+  return hipGetLastError();
+}
+
+// out[i] = act(bias[k(i)] + sum_z partial[z][i]), summed in split order.
+__global__ __launch_bounds__(256)
+void splitk_reduce_kernel(const float* __restrict__ partial, const float* __restrict__ bias,
+                          float* __restrict__ out, int nsplit, int out_elems, int K, int PQ,
+                          int relu) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < out_elems;
+       i += gridDim.x * blockDim.x) {
+    float v = 0.0f;
+    for (int z = 0; z < nsplit; ++z) v += partial[(size_t)z * out_elems + i];
+    if (bias) v += bias[(i / PQ) % K];
+    if (relu) v = v > 0.0f ? v : 0.0f;
+    out[i] = v;
+  }
+}
+
+hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* out, int nsplit,
+                                int out_elems, int K, int PQ, int relu, hipStream_t st) {
+  int blocks = (out_elems + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, partial, bias, out,
+                     nsplit, out_elems, K, PQ, relu);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256)
+void maxpool_kernel(const float* __restrict__ in, float* __restrict__ out, int H, int W, int ksz,
+                    int stride, int P, int Q, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    int q = (int)(idx % Q);
+    long long t = idx / Q;
+    int p = (int)(t % P);
+    long long nc = t / P;
+    const float* src = in + nc * H * W + (long long)(p * stride) * W + q * stride;
+    float m = src[0];
+    for (int r = 0; r < ksz; ++r)
+      for (int s = 0; s < ksz; ++s) {
+        float v = src[r * W + s];
+        m = v > m ? v : m;
+      }
+    out[idx] = m;
+  }
+}
+
+hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int W, int ksz,
+                          int stride, int P, int Q, hipStream_t st) {
+  long long total = (long long)N * C * P * Q;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 65536 * 16) blocks = 65536 * 16;
+  hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, out, H, W, ksz,
+                     stride, P, Q, total);
+  return hipGetLastError();
+}
+
+}  // namespace bconv

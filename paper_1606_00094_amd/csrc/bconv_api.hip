@@ -1,0 +1,362 @@
+// C ABI of libbconv: argument validation, the variant catalogue, launch planning,
+// the per-shape selection (paper Section V: operation -> variant -> blocking
+// constants) and the host-only bounds audit.  No arithmetic of the convolution
+// is done on the host.
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/bconv.h"
+#include "bconv_internal.h"
+
+namespace bconv {
+
+// ------------------------------------------------------------------ catalogue
+static const TileLaunchFn kLaunch[] = {
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT) launch_##name,
+#include "variants.def"
+#undef X
+};
+static const TileDesc* const kTiles = kTileDescs;
+
+// Reduction splits offered for every tile variant.
+static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+constexpr int kNumSplits = (int)(sizeof(kSplits) / sizeof(kSplits[0]));
+
+// variant id 0 = direct kernel; 1 + tile*kNumSplits + split_index otherwise.
+constexpr int kNumVariants = 1 + kNumTiles * kNumSplits;
+
+static bool decode_variant(int id, int* tile, int* nsplit) {
+  if (id < 1 || id >= kNumVariants) return false;
+  *tile = (id - 1) / kNumSplits;
+  *nsplit = kSplits[(id - 1) % kNumSplits];
+  return true;
+}
+
+// ------------------------------------------------------------------ validation
+static int make_shape(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      Shape* s) {
+  if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 ||
+      pad < 0)
+    return BCONV_EINVAL;
+  if ((long long)H + 2LL * pad < R || (long long)W + 2LL * pad < S) return BCONV_ESHAPE;
+  long long P = ((long long)H + 2LL * pad - R) / stride + 1;
+  long long Q = ((long long)W + 2LL * pad - S) / stride + 1;
+  const long long lim = (1LL << 40);
+  if ((long long)N * C * H * W >= lim || (long long)K * C * R * S >= lim ||
+      (long long)N * K * P * Q >= lim || P > (1 << 30) || Q > (1 << 30))
+    return BCONV_ESHAPE;
+  *s = Shape{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q};
+  return BCONV_OK;
+}
+
+// ------------------------------------------------------------------ selection
+struct TableRow {
+  int N, C, H, W, K, R, S, stride, pad;
+  const char* tile;
+  int nsplit;
+};
+static const TableRow kTable[] = {
+#include "selection_table.inc"
+    {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
+
+static int find_variant(const char* tile, int nsplit) {
+  for (int t = 0; t < kNumTiles; ++t)
+    if (std::strcmp(kTiles[t].name, tile) == 0)
+      for (int i = 0; i < kNumSplits; ++i)
+        if (kSplits[i] == nsplit) return 1 + t * kNumSplits + i;
+  return -1;
+}
+
+// Rough time model used for shapes the table does not list: MFMA work of the
+// busiest compute unit (two resident workgroups share a unit's matrix pipes)
+// plus a fixed per-chunk and per-launch cost and the split-K round trip.
+static double model_cost(const TileDesc& v, const Plan& pl) {
+  const TconvParams& p = pl.p;
+  const double cus = 256.0;
+  double tiles = (double)pl.gx * pl.gy * pl.gz;
+  int per_cu = (int)(kLdsLimitBytes / pl.lds_bytes);
+  if (per_cu > 2) per_cu = 2;
+  if (per_cu < 1) per_cu = 1;
+  double rounds = (double)(long long)((tiles + cus * per_cu - 1) / (cus * per_cu));
+  double busiest = tiles <= cus ? 1.0 : (tiles <= cus * per_cu ? (double)per_cu : rounds * per_cu);
+  double rows = (double)p.chunks_per_split * v.KR;
+  double wg_cycles = (double)v.BM() * v.BN() * rows * p.S * 2.0 / 256.0;   // at full unit rate
+  double chunk_over = 400.0 * p.chunks_per_split;
+  double t = busiest * (wg_cycles + chunk_over / per_cu) + 6000.0;
+  if (p.nsplit > 1) t += 8000.0 + (double)p.nsplit * p.out_elems * 8.0 / 2000.0;
+  return t;
+}
+
+static int select_variant(const Shape& s) {
+  for (const TableRow* r = kTable; r->tile; ++r) {
+    if (r->N == s.N && r->C == s.C && r->H == s.H && r->W == s.W && r->K == s.K && r->R == s.R &&
+        r->S == s.S && r->stride == s.stride && r->pad == s.pad) {
+      int id = find_variant(r->tile, r->nsplit);
+      int t, ns;
+      Plan pl;
+      if (id > 0 && decode_variant(id, &t, &ns) && plan_tconv(s, kTiles[t], ns, &pl)) return id;
+    }
+  }
+  int best = 0;
+  double best_cost = 0.0;
+  for (int t = 0; t < kNumTiles; ++t) {
+    // a tile compiled for this kernel size beats the run-time generic one
+    for (int i = 0; i < kNumSplits; ++i) {
+      Plan pl;
+      if (!plan_tconv(s, kTiles[t], kSplits[i], &pl)) continue;
+      double c = model_cost(kTiles[t], pl);
+      if (!kTiles[t].S) c *= 1.3;
+      if (best == 0 || c < best_cost) {
+        best = 1 + t * kNumSplits + i;
+        best_cost = c;
+      }
+    }
+  }
+  return best;   // 0 = direct kernel when no tile applies
+}
+
+// ------------------------------------------------------------------ workspace
+struct DeviceWorkspace {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+static DeviceWorkspace g_ws[64];
+static std::mutex g_ws_mutex;
+
+static int internal_workspace(size_t need, void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BCONV_ELAUNCH;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  DeviceWorkspace& w = g_ws[dev];
+  if (w.bytes < need) {
+    if (w.ptr) {
+      if (hipDeviceSynchronize() != hipSuccess) return BCONV_ELAUNCH;
+      (void)hipFree(w.ptr);
+      w.ptr = nullptr;
+      w.bytes = 0;
+    }
+    size_t want = need < (size_t)(32u << 20) ? (size_t)(32u << 20) : need;
+    if (hipMalloc(&w.ptr, want) != hipSuccess) {
+      w.ptr = nullptr;
+      (void)hipGetLastError();
+      return BCONV_ELAUNCH;
+    }
+    w.bytes = want;
+  }
+  *out = w.ptr;
+  return BCONV_OK;
+}
+
+// ------------------------------------------------------------------ run
+static int run_conv(const float* in, const float* filt, const float* bias, float* out,
+                    const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
+                    hipStream_t st, int variant_id) {
+  if (variant_id < 0) variant_id = select_variant(s);
+  if (variant_id == 0) {
+    return launch_direct_conv(in, filt, bias, out, s, relu, st) == hipSuccess ? BCONV_OK
+                                                                              : BCONV_ELAUNCH;
+  }
+  int t, nsplit;
+  if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
+  Plan pl;
+  if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
+  if (pl.ws_bytes) {
+    if (own_ws) {
+      int rc = internal_workspace(pl.ws_bytes, &ws);
+      if (rc != BCONV_OK) return rc;
+    } else if (!ws || ws_bytes < pl.ws_bytes) {
+      return BCONV_EWORKSPACE;
+    }
+  }
+  pl.p.in = in;
+  pl.p.filt = filt;
+  pl.p.bias = bias;
+  pl.p.out = out;
+  pl.p.partial = pl.ws_bytes ? static_cast<float*>(ws) : nullptr;
+  pl.p.relu = relu;
+  if (kLaunch[t](pl.p, dim3(pl.gx, pl.gy, pl.gz), pl.lds_bytes, st) != hipSuccess) return BCONV_ELAUNCH;
+  if (nsplit > 1) {
+    if (launch_splitk_reduce(pl.p.partial, bias, out, nsplit, pl.p.out_elems, s.K, s.P * s.Q, relu,
+                             st) != hipSuccess)
+      return BCONV_ELAUNCH;
+  }
+  return BCONV_OK;
+}
+
+// ------------------------------------------------------------------ audit
+static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
+  const TconvParams& p = pl.p;
+  long long bad = 0;
+  const int BN = v.BN(), BM = v.BM(), NTHR = v.NTHR();
+  const long long in_elems = (long long)p.N * p.CHW;
+  const int ncell = p.nrows * p.rowst;
+  if (p.ast < v.KR * p.S) ++bad;
+  if ((size_t)(2 * BM * p.ast + 2 * v.KR * p.plane) * 4 != pl.lds_bytes) ++bad;
+  for (unsigned bx = 0; bx < pl.gx; ++bx) {
+    PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
+    if (t.cnt < 1 || t.cnt > BN) ++bad;
+    if (t.rho1 - t.rho0 + 1 > p.nrows) ++bad;
+    // staged cells: each LDS word of a plane is written by exactly one cell
+    for (int e = 0; e < v.EPT * NTHR; ++e) {
+      if (e >= ncell) continue;
+      BCell c = b_cell(p, t, e, p.S, p.stride);
+      if (c.lds < 0 || c.lds >= p.plane) ++bad;
+      if (c.ih0 == kNeverValid) continue;
+      for (int ci = 0; ci < 2; ++ci) {
+        int cc = ci ? p.C - 1 : 0;
+        for (int r = 0; r < p.R; ++r) {
+          if ((unsigned)(c.ih0 + r) >= (unsigned)p.H) continue;
+          long long off = (long long)c.goff + (long long)cc * p.HW + (long long)r * p.W;
+          if (off < 0 || off >= in_elems) ++bad;
+        }
+      }
+    }
+    // lanes: every tap read stays inside the plane; stores inside out
+    for (int col = 0; col < BN; ++col) {
+      BLane l = b_lane(p, t, col);
+      for (int ss = 0; ss < p.S; ++ss) {
+        int a = l.ldsbase + tap_off(ss, p.stride, p.phst);
+        if (a < 0 || a >= p.plane) ++bad;
+      }
+      if (l.valid) {
+        long long lo = l.outoff, hi = (long long)l.outoff + (long long)(p.K - 1) * p.PQ;
+        if (lo < 0 || hi >= p.out_elems) ++bad;
+      }
+    }
+  }
+  // filters: last word a workgroup row can touch
+  for (unsigned by = 0; by < pl.gy; ++by) {
+    int m0 = (int)by * BM;
+    if (m0 >= p.K) ++bad;
+  }
+  if ((long long)p.nchunks * v.KR < p.CRrows) ++bad;
+  if ((long long)p.chunks_per_split * p.nsplit < p.nchunks) ++bad;
+  (void)s;
+  return bad;
+}
+
+static const char* status_text(int st) {
+  switch (st) {
+    case BCONV_OK: return "ok";
+    case BCONV_EINVAL: return "invalid argument (dimension, stride, pad or relu flag)";
+    case BCONV_ENULL: return "required pointer is NULL";
+    case BCONV_ESHAPE: return "shape has no output point or a tensor is too large";
+    case BCONV_EWORKSPACE: return "workspace missing or too small";
+    case BCONV_ELAUNCH: return "HIP runtime refused an allocation or a kernel launch";
+    case BCONV_EVARIANT: return "variant id out of range or not applicable to this shape";
+    default: return "unknown status";
+  }
+}
+
+}  // namespace bconv
+
+using namespace bconv;
+
+extern "C" {
+
+int conv_out_dims(int H, int W, int R, int S, int stride, int pad, int* P, int* Q) {
+  if (!P || !Q) return BCONV_ENULL;
+  Shape s;
+  int rc = make_shape(1, 1, H, W, 1, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  *P = s.P;
+  *Q = s.Q;
+  return BCONV_OK;
+}
+
+int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* out, int N, int C,
+                int H, int W, int K, int R, int S, int stride, int pad, int relu, void* workspace,
+                size_t workspace_bytes, void* hip_stream, int variant_id) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (relu != 0 && relu != 1) return BCONV_EINVAL;
+  if (!in || !filt || !out) return BCONV_ENULL;
+  if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
+  return run_conv(in, filt, bias, out, s, relu, workspace, workspace_bytes, false,
+                  static_cast<hipStream_t>(hip_stream), variant_id);
+}
+
+int conv_fwd(const float* in, const float* filt, const float* bias, float* out, int N, int C,
+             int H, int W, int K, int R, int S, int stride, int pad, int relu) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (relu != 0 && relu != 1) return BCONV_EINVAL;
+  if (!in || !filt || !out) return BCONV_ENULL;
+  return run_conv(in, filt, bias, out, s, relu, nullptr, 0, true, nullptr, -1);
+}
+
+size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                int pad, int variant_id) {
+  Shape s;
+  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+  if (variant_id < 0) variant_id = select_variant(s);
+  int t, nsplit;
+  Plan pl;
+  if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return 0;
+  return pl.ws_bytes;
+}
+
+int conv_num_variants(void) { return kNumVariants; }
+
+int conv_variant_name(int variant_id, char* buf, size_t buflen) {
+  if (!buf || buflen == 0) return BCONV_ENULL;
+  if (variant_id == 0) {
+    std::snprintf(buf, buflen, "direct");
+    return BCONV_OK;
+  }
+  int t, nsplit;
+  if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
+  std::snprintf(buf, buflen, "%s/s%d", kTiles[t].name, nsplit);
+  return BCONV_OK;
+}
+
+int conv_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  return select_variant(s);
+}
+
+int conv_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            int variant_id) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (variant_id == 0) return 1;
+  int t, nsplit;
+  Plan pl;
+  if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
+  return plan_tconv(s, kTiles[t], nsplit, &pl) ? 1 : 0;
+}
+
+long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            int variant_id) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (variant_id == 0) return 0;
+  int t, nsplit;
+  Plan pl;
+  if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
+  if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
+  return audit(s, kTiles[t], pl);
+}
+
+int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz, int stride,
+                void* hip_stream) {
+  if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || ksz <= 0 || stride <= 0) return BCONV_EINVAL;
+  if (H < ksz || W < ksz) return BCONV_ESHAPE;
+  if (!in || !out) return BCONV_ENULL;
+  int P = (H - ksz) / stride + 1, Q = (W - ksz) / stride + 1;
+  return launch_maxpool(in, out, N, C, H, W, ksz, stride, P, Q,
+                        static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
+const char* bconv_strerror(int status) { return status_text(status); }
+
+}  // extern "C"

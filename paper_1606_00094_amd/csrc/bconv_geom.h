@@ -1,0 +1,145 @@
+// Index arithmetic of the tiled MFMA convolution kernel, usable from device code
+// and from plain host C++ (the host-side bounds audit walks exactly these
+// functions for every workgroup, thread and reduction chunk before a shape /
+// variant pair is ever launched).
+//
+// Problem view (paper Section III, convolution as a matrix product, with the
+// roles fixed by the NCHW / KCRS layouts):
+//     out_n[K x PQ] = filt[K x (C*R*S)] . rows_of(in_n)[(C*R*S) x PQ]
+// Rows of the left operand are filters, columns of the right operand are output
+// pixels.  The reduction index is split as (kk, s) with kk = c*R + r a
+// "reduction row" (one input channel, one kernel row) and s the kernel column.
+//
+// Workgroup tile: BM filters x BN consecutive flattened output pixels
+// g = (img*P + p)*Q + q.  The pixels of a tile lie on at most `nrows` output
+// rows rho = img*P + p ("row slots").  For one reduction row kk = (c, r) and
+// one slot the kernel stages the piece of input row (img, c, p*stride-pad+r)
+// that the slot's pixels read -- the paper's tiled-convolution idea (Section VI:
+// load whole X tiles of the input per workgroup, unroll over the kernel's X
+// extent) -- so the S taps of a pixel are S shifted reads of one staged row.
+// For stride > 1 a staged row is split into `stride` phase planes so that
+// consecutive pixels read consecutive LDS words for every tap.
+#pragma once
+
+#if defined(__HIPCC__)
+#define BCONV_HD __host__ __device__ __forceinline__
+#else
+#define BCONV_HD inline
+#endif
+
+namespace bconv {
+
+// Kernel argument block of the tiled MFMA kernel (plain data).
+struct TconvParams {
+  const float* in;
+  const float* filt;
+  const float* bias;    // may be null
+  float* out;
+  float* partial;       // split-K partial sums [nsplit][N*K*P*Q], null when nsplit == 1
+  int N, C, H, W, K, R, S, stride, pad, P, Q;
+  int relu;
+  int PQ, NPQ, HW, CHW, CRS, CRrows;   // CRrows = C*R reduction rows
+  int nrows, phst, rowst, plane;       // staged-input geometry, plane = nrows*rowst
+  int ast;                             // LDS stride between filter rows (odd)
+  int nchunks, chunks_per_split, nsplit;
+  int out_elems;                       // N*K*P*Q
+};
+
+struct PixTile {
+  int g0, cnt;        // first flattened pixel and number of valid pixels
+  int rho0, q00;      // output row / column of the first pixel
+  int rho1, qlast;    // output row / column of the last valid pixel
+};
+
+BCONV_HD PixTile pix_tile(int tile_idx, int BN, int NPQ, int Q) {
+  PixTile t;
+  t.g0 = tile_idx * BN;
+  int rem = NPQ - t.g0;
+  t.cnt = rem < BN ? rem : BN;
+  t.rho0 = t.g0 / Q;
+  t.q00 = t.g0 - t.rho0 * Q;
+  int gl = t.g0 + t.cnt - 1;
+  t.rho1 = gl / Q;
+  t.qlast = gl - t.rho1 * Q;
+  return t;
+}
+
+// Upper bound on the row slots a tile of BN consecutive pixels can touch.
+BCONV_HD int tile_nrows(int BN, int Q, int total_rows) {
+  int n = (BN - 1) / Q + 2;
+  return n < total_rows ? n : total_rows;
+}
+
+// Words per phase plane of one staged row.
+BCONV_HD int tile_phst(int BN, int Q, int S, int stride) {
+  return (Q < BN ? Q : BN) + (S - 1) / stride;
+}
+
+constexpr int kNeverValid = -(1 << 24);
+
+// One staged-input cell: where it lives in a B plane, which input word it takes
+// for reduction row (c=0, r=0), and the input row index for r = 0.  A cell that
+// never loads (outside the tile's need, or in the zero padding columns) has
+// ih0 = kNeverValid so that the per-row test (unsigned)(ih0 + r) < H fails.
+struct BCell {
+  int lds;
+  int goff;
+  int ih0;
+};
+
+BCONV_HD BCell b_cell(const TconvParams& p, const PixTile& t, int e, int S, int STR) {
+  BCell c;
+  int slot = e / p.rowst;
+  int xrel = e - slot * p.rowst;
+  int rho = t.rho0 + slot;
+  bool ok = (slot < p.nrows) && (rho <= t.rho1);
+  int img = rho / p.P;
+  int pp = rho - img * p.P;
+  int qlo = (slot == 0) ? t.q00 : 0;
+  int qhi = (rho == t.rho1) ? t.qlast : p.Q - 1;
+  int width = (qhi - qlo) * STR + S;
+  ok = ok && (xrel < width);
+  int iw = qlo * STR + xrel - p.pad;
+  ok = ok && (iw >= 0) && (iw < p.W);
+  int ih0 = pp * STR - p.pad;
+  int ph = xrel % STR;
+  c.lds = slot * p.rowst + ph * p.phst + xrel / STR;
+  c.goff = img * p.CHW + ih0 * p.W + iw;
+  c.ih0 = ok ? ih0 : kNeverValid;
+  return c;
+}
+
+// One output column of the tile as a lane sees it.
+struct BLane {
+  int ldsbase;   // slot*rowst + (q - qlo(slot)): add tap_off(s) and kl*plane
+  int outoff;    // img*K*PQ + p*Q + q: add k*PQ
+  int valid;
+};
+
+BCONV_HD BLane b_lane(const TconvParams& p, const PixTile& t, int col) {
+  BLane l;
+  l.valid = col < t.cnt;
+  int cc = l.valid ? col : t.cnt - 1;   // ragged tail: alias the last valid pixel
+  int g = t.g0 + cc;
+  int rho = g / p.Q;
+  int q = g - rho * p.Q;
+  int slot = rho - t.rho0;
+  int qlo = (slot == 0) ? t.q00 : 0;
+  int img = rho / p.P;
+  int pp = rho - img * p.P;
+  l.ldsbase = slot * p.rowst + (q - qlo);
+  l.outoff = img * p.K * p.PQ + pp * p.Q + q;
+  return l;
+}
+
+// LDS word offset of kernel column s relative to a lane's ldsbase.
+BCONV_HD int tap_off(int s, int STR, int phst) {
+  return (s % STR) * phst + s / STR;
+}
+
+// Row of a 32x32 MFMA accumulator tile held by (lane, register i), i in [0,16).
+BCONV_HD int acc_row_32(int lane, int i) {
+  return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+}
+
+}  // namespace bconv

@@ -1,0 +1,98 @@
+// Launch planning of the tiled MFMA kernel: plain host C++ (no HIP types) so that
+// the library and the host-side emulation used by the CPU tests derive the
+// argument block and grid from the same code.
+#pragma once
+#include <cstddef>
+#include <cstring>
+
+#include "bconv_geom.h"
+
+namespace bconv {
+
+struct Shape {
+  int N, C, H, W, K, R, S, stride, pad, P, Q;
+};
+
+// One row of variants.def.
+struct TileDesc {
+  const char* name;
+  int R, S, STR;            // 0 = run-time value
+  int WM, WN, MT, NT, KR, EPT;
+  int BM() const { return WM * MT * 32; }
+  int BN() const { return WN * NT * 32; }
+  int NTHR() const { return WM * WN * 64; }
+};
+
+static const TileDesc kTileDescs[] = {
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT) {#name, R, S, STR, WM, WN, MT, NT, KR, EPT},
+#include "variants.def"
+#undef X
+};
+constexpr int kNumTiles = (int)(sizeof(kTileDescs) / sizeof(kTileDescs[0]));
+
+constexpr size_t kLdsLimitBytes = 160 * 1024;
+constexpr int kSmaxGeneric = 16;   // widest kernel the run-time generic tiles take
+
+struct Plan {
+  TconvParams p;
+  unsigned gx, gy, gz;
+  size_t lds_bytes;
+  size_t ws_bytes;
+};
+
+// Fills the argument block (pointers left null) and launch geometry of tile v
+// for shape s0, or returns false if the tile cannot run the shape.
+inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl) {
+  Shape s = s0;
+  if ((v.R && v.R != s.R) || (v.S && v.S != s.S) || (v.STR && v.STR != s.stride)) return false;
+  if (!v.S && s.S > kSmaxGeneric) return false;
+  const long long i31 = (1LL << 31) - 1;
+  if ((long long)s.N * s.C * s.H * s.W > i31 || (long long)s.K * s.C * s.R * s.S > i31 ||
+      (long long)s.N * s.K * s.P * s.Q > i31)
+    return false;
+  // A pointwise layer reads each image as one long row (per-image im2col is the
+  // identity, paper Section VI k1conv).
+  if (s.R == 1 && s.S == 1 && s.stride == 1 && s.pad == 0) {
+    s.W = s.H * s.W;
+    s.H = 1;
+    s.Q = s.P * s.Q;
+    s.P = 1;
+  }
+  TconvParams& p = pl->p;
+  std::memset(&p, 0, sizeof(p));
+  p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.R = s.R; p.S = s.S;
+  p.stride = s.stride; p.pad = s.pad; p.P = s.P; p.Q = s.Q;
+  p.PQ = s.P * s.Q;
+  p.NPQ = s.N * p.PQ;
+  p.HW = s.H * s.W;
+  p.CHW = s.C * p.HW;
+  p.CRS = s.C * s.R * s.S;
+  p.CRrows = s.C * s.R;
+  p.out_elems = s.N * s.K * p.PQ;
+  const int BN = v.BN(), BM = v.BM();
+  long long total_rows = (long long)s.N * s.P;
+  p.nrows = tile_nrows(BN, s.Q, total_rows > i31 ? (int)i31 : (int)total_rows);
+  p.phst = tile_phst(BN, s.Q, s.S, s.stride);
+  p.rowst = s.stride * p.phst;
+  p.plane = p.nrows * p.rowst;
+  if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR()) return false;
+  p.ast = (v.KR * s.S) | 1;
+  size_t lds = (size_t)(2 * BM * p.ast + 2 * v.KR * p.plane) * sizeof(float);
+  if (lds > kLdsLimitBytes) return false;
+  p.nchunks = (p.CRrows + v.KR - 1) / v.KR;
+  if (nsplit < 1 || nsplit > p.nchunks) return false;
+  p.chunks_per_split = (p.nchunks + nsplit - 1) / nsplit;
+  // no empty split: the request must be reproduced by its own chunk count
+  if ((p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split != nsplit) return false;
+  p.nsplit = nsplit;
+  long long gx = (p.NPQ + BN - 1) / BN, gy = (s.K + BM - 1) / BM;
+  if (gx > i31 || gy > 65535 || nsplit > 65535) return false;
+  pl->gx = (unsigned)gx;
+  pl->gy = (unsigned)gy;
+  pl->gz = (unsigned)nsplit;
+  pl->lds_bytes = lds;
+  pl->ws_bytes = nsplit > 1 ? (size_t)nsplit * (size_t)p.out_elems * sizeof(float) : 0;
+  return true;
+}
+
+}  // namespace bconv

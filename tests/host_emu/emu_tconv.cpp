@@ -1,0 +1,165 @@
+// Host-side model of the tiled MFMA convolution kernel, for CPU tests only.
+//
+// It walks the same index functions (bconv_geom.h) and the same launch plan
+// (bconv_plan.h) as the device kernel, thread by thread and chunk by chunk, with
+// every LDS and global access bounds-checked and LDS poisoned with NaN before
+// each chunk, and models v_mfma_f32_32x32x2_f32 by its definition
+// (D[i][j] += sum_k A[i][k]*B[k][j], lane l supplying A[l%32][l/32] and
+// B[l/32][l%32]).  It checks the kernel's indexing and staging logic on the CPU;
+// it is not part of the library and the library never calls it.
+#include <cmath>
+#include <cstdio>
+#include <limits>
+#include <vector>
+
+#include "../../paper_1606_00094_amd/csrc/bconv_plan.h"
+
+using namespace bconv;
+
+namespace {
+struct Oob {
+  long long count = 0;
+  void hit(const char* what, long long idx, long long lim) {
+    if (count < 5) std::fprintf(stderr, "emu_tconv: %s index %lld outside [0,%lld)\n", what, idx, lim);
+    ++count;
+  }
+};
+}  // namespace
+
+extern "C" int emu_num_tiles() { return kNumTiles; }
+extern "C" const char* emu_tile_name(int t) { return (t >= 0 && t < kNumTiles) ? kTileDescs[t].name : ""; }
+
+// Returns 0 on success, 1 if the tile does not apply, or 2 + number of
+// out-of-bounds / poisoned accesses.
+extern "C" long long emu_tconv(const float* in, const float* filt, const float* bias, float* out,
+                               int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               int relu, int tile, int nsplit) {
+  if (tile < 0 || tile >= kNumTiles) return 1;
+  const TileDesc& v = kTileDescs[tile];
+  Shape sh{N, C, H, W, K, R, S, stride, pad, (H + 2 * pad - R) / stride + 1,
+           (W + 2 * pad - S) / stride + 1};
+  Plan pl;
+  if (!plan_tconv(sh, v, nsplit, &pl)) return 1;
+  const TconvParams& p = pl.p;
+  const int BM = v.BM(), BN = v.BN(), NTHR = v.NTHR(), KR = v.KR, EPT = v.EPT;
+  const int Rk = p.R, Sk = p.S, STR = p.stride;
+  const int KRS = KR * Sk;
+  const int SP = v.S > 0 ? v.S : kSmaxGeneric;
+  const int KRSP = KR * SP;
+  const int APT = (BM * KRSP + NTHR - 1) / NTHR;
+  const long long in_elems = (long long)p.N * p.CHW, filt_elems = (long long)p.K * p.CRS;
+  const int abuf = BM * p.ast, bbuf = KR * p.plane;
+  if ((size_t)(2 * abuf + 2 * bbuf) * 4 != pl.lds_bytes) return 2;
+  Oob oob;
+  const float nanv = std::numeric_limits<float>::quiet_NaN();
+  std::vector<float> partial((size_t)p.nsplit * p.out_elems, nanv);
+  std::vector<float> As(abuf), Bs(bbuf);
+  const int ncell = p.nrows * p.rowst;
+
+  for (unsigned bz = 0; bz < pl.gz; ++bz)
+  for (unsigned by = 0; by < pl.gy; ++by)
+  for (unsigned bx = 0; bx < pl.gx; ++bx) {
+    const PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
+    const int m0 = (int)by * BM;
+    // accumulators per wave tile as plain matrices [BM][BN]
+    std::vector<float> acc((size_t)BM * BN, 0.0f);
+    const int ch_begin = (int)bz * p.chunks_per_split;
+    int ch_end = ch_begin + p.chunks_per_split;
+    if (ch_end > p.nchunks) ch_end = p.nchunks;
+    for (int ch = ch_begin; ch < ch_end; ++ch) {
+      std::fill(As.begin(), As.end(), nanv);
+      std::fill(Bs.begin(), Bs.end(), nanv);
+      const int kk0 = ch * KR;
+      const int col0 = kk0 * Sk;
+      for (int tid = 0; tid < NTHR; ++tid) {
+        for (int i = 0; i < APT; ++i) {
+          int e = tid + i * NTHR;
+          int m = e / KRSP, j = e - m * KRSP;
+          bool ok = (m < BM) && (j < KRS) && (m0 + m < p.K) && (col0 + j < p.CRS);
+          long long gi = ok ? (long long)(m0 + m) * p.CRS + col0 + j : 0;
+          if (gi < 0 || gi >= filt_elems) { oob.hit("filt", gi, filt_elems); continue; }
+          float val = ok ? filt[gi] : 0.0f;
+          if ((m < BM) && (j < KRS)) {
+            int li = m * p.ast + j;
+            if (li < 0 || li >= abuf) oob.hit("A lds", li, abuf); else As[li] = val;
+          }
+        }
+        int c = kk0 / Rk, r = kk0 - c * Rk;
+        for (int kl = 0; kl < KR; ++kl) {
+          const bool rowok = (kk0 + kl) < p.CRrows;
+          const int koff = c * p.HW + r * p.W;
+          for (int i = 0; i < EPT; ++i) {
+            int e = tid + i * NTHR;
+            if (e >= ncell) continue;
+            BCell cell = b_cell(p, t, e, Sk, STR);
+            bool ok = rowok && ((unsigned)(cell.ih0 + r) < (unsigned)p.H);
+            long long gi = ok ? (long long)cell.goff + koff : 0;
+            if (gi < 0 || gi >= in_elems) { oob.hit("in", gi, in_elems); continue; }
+            float val = ok ? in[gi] : 0.0f;
+            long long li = (long long)kl * p.plane + cell.lds;
+            if (cell.lds < 0 || cell.lds >= p.plane) oob.hit("B lds", cell.lds, p.plane);
+            else Bs[li] = val;
+          }
+          if (++r == Rk) { r = 0; ++c; }
+        }
+      }
+      // compute: every wave, every (j, s) step
+      for (int wave = 0; wave < v.WM * v.WN; ++wave) {
+        const int wm = wave / v.WN, wn = wave % v.WN;
+        for (int j = 0; j < KR / 2; ++j)
+        for (int s = 0; s < Sk; ++s) {
+          const int aoff = 2 * j * Sk + s;
+          const int boff = 2 * j * p.plane + tap_off(s, STR, p.phst);
+          for (int mt = 0; mt < v.MT; ++mt)
+          for (int nt = 0; nt < v.NT; ++nt) {
+            float a[64], b[64];
+            for (int lane = 0; lane < 64; ++lane) {
+              const int l32 = lane & 31, h = lane >> 5;
+              const int laneA = (wm * v.MT * 32 + l32) * p.ast + h * Sk;
+              BLane bl = b_lane(p, t, (wn * v.NT + nt) * 32 + l32);
+              const int laneB = bl.ldsbase + h * p.plane;
+              long long ai = (long long)laneA + mt * 32 * p.ast + aoff;
+              long long bi = (long long)laneB + boff;
+              if (ai < 0 || ai >= abuf) { oob.hit("A read", ai, abuf); a[lane] = 0; } else a[lane] = As[ai];
+              if (bi < 0 || bi >= bbuf) { oob.hit("B read", bi, bbuf); b[lane] = 0; } else b[lane] = Bs[bi];
+            }
+            for (int i = 0; i < 32; ++i)
+              for (int jn = 0; jn < 32; ++jn) {
+                float d = acc[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn];
+                for (int k = 0; k < 2; ++k) d = std::fmaf(a[k * 32 + i], b[k * 32 + jn], d);
+                acc[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn] = d;
+              }
+          }
+        }
+      }
+    }
+    // epilogue through the lane/register map
+    for (int wave = 0; wave < v.WM * v.WN; ++wave) {
+      const int wm = wave / v.WN, wn = wave % v.WN;
+      for (int lane = 0; lane < 64; ++lane)
+      for (int mt = 0; mt < v.MT; ++mt)
+      for (int i = 0; i < 16; ++i) {
+        const int row = (wm * v.MT + mt) * 32 + acc_row_32(lane, i);
+        const int k = m0 + row;
+        if (k >= p.K) continue;
+        for (int nt = 0; nt < v.NT; ++nt) {
+          const int col = (wn * v.NT + nt) * 32 + (lane & 31);
+          BLane bl = b_lane(p, t, col);
+          if (!bl.valid) continue;
+          long long oi = (long long)bl.outoff + (long long)k * p.PQ;
+          if (oi < 0 || oi >= p.out_elems) { oob.hit("out", oi, p.out_elems); continue; }
+          partial[(size_t)bz * p.out_elems + oi] = acc[(size_t)row * BN + col];
+        }
+      }
+    }
+  }
+  const int PQ = p.PQ;
+  for (int i = 0; i < p.out_elems; ++i) {
+    float val = 0.0f;
+    for (int z = 0; z < p.nsplit; ++z) val += partial[(size_t)z * p.out_elems + i];
+    if (bias) val += bias[(i / PQ) % p.K];
+    if (relu) val = val > 0.0f ? val : 0.0f;
+    out[i] = val;
+  }
+  return oob.count ? 2 + oob.count : 0;
+}

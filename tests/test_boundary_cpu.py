@@ -1,0 +1,103 @@
+"""Host-side tests of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, rejects bad arguments before touching the device,
+and its launch plans pass the bounds audit for the benchmark shapes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import workloads
+from paper_1606_00094_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "bconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted(set(n for n in names if n.startswith(("conv_", "bconv_", "maxpool_"))))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    declared = _declared_functions()
+    assert "conv_fwd" in declared and "conv_fwd_ex" in declared and "maxpool_fwd" in declared
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == declared
+
+
+def test_out_dims_and_errors():
+    assert binding.conv_out_dims(227, 227, 11, 11, 4, 0) == (55, 55)
+    assert binding.conv_out_dims(10, 12, 3, 5, 2, 1) == (5, 5)
+    lib = binding.lib()
+    P, Q = ctypes.c_int(), ctypes.c_int()
+    assert lib.conv_out_dims(3, 3, 5, 5, 1, 0, ctypes.byref(P), ctypes.byref(Q)) == -3
+    assert lib.conv_out_dims(3, 3, 1, 1, 0, 0, ctypes.byref(P), ctypes.byref(Q)) == -1
+    assert lib.conv_out_dims(3, 3, 1, 1, 1, -1, ctypes.byref(P), ctypes.byref(Q)) == -1
+    assert lib.conv_out_dims(3, 3, 1, 1, 1, 0, None, None) == -2
+
+
+def test_conv_fwd_rejects_bad_arguments_without_a_gpu():
+    lib = binding.lib()
+    fake = ctypes.c_void_p(4096)   # never dereferenced: every call below fails validation
+    ok_dims = (1, 3, 8, 8, 4, 3, 3, 1, 1)
+    assert lib.conv_fwd(None, fake, fake, fake, *ok_dims, 1) == -2
+    assert lib.conv_fwd(fake, None, fake, fake, *ok_dims, 0) == -2
+    assert lib.conv_fwd(fake, fake, fake, None, *ok_dims, 0) == -2
+    assert lib.conv_fwd(fake, fake, fake, fake, 0, 3, 8, 8, 4, 3, 3, 1, 1, 0) == -1
+    assert lib.conv_fwd(fake, fake, fake, fake, 1, 3, 8, 8, 4, 3, 3, 0, 1, 0) == -1
+    assert lib.conv_fwd(fake, fake, fake, fake, 1, 3, 8, 8, 4, 3, 3, 1, -1, 0) == -1
+    assert lib.conv_fwd(fake, fake, fake, fake, *ok_dims, 2) == -1
+    assert lib.conv_fwd(fake, fake, fake, fake, 1, 3, 2, 2, 4, 5, 5, 1, 0, 0) == -3
+    nv = binding.conv_num_variants()
+    assert lib.conv_fwd_ex(fake, fake, fake, fake, *ok_dims, 0, None, 0, None, nv) == -6
+    assert lib.conv_fwd_ex(fake, fake, fake, fake, *ok_dims, 0, None, 0, None, -2) == -6
+    assert lib.maxpool_fwd(None, fake, 1, 1, 5, 5, 3, 2, None) == -2
+    assert lib.maxpool_fwd(fake, fake, 1, 1, 2, 2, 3, 2, None) == -3
+    assert lib.maxpool_fwd(fake, fake, 1, 1, 5, 5, 0, 2, None) == -1
+    for st in range(-6, 1):
+        assert binding.strerror(st) != "unknown status"
+    assert binding.strerror(-99) == "unknown status"
+
+
+def test_variant_catalogue():
+    nv = binding.conv_num_variants()
+    assert nv > 10
+    names = [binding.conv_variant_name(v) for v in range(nv)]
+    assert names[0] == "direct"
+    assert len(set(names)) == nv
+    buf = ctypes.create_string_buffer(4)
+    assert binding.lib().conv_variant_name(1, buf, 4) == 0 and len(buf.value) == 3
+    assert binding.lib().conv_variant_name(nv, buf, 4) == -6
+
+
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS, ids=lambda l: l.name)
+def test_selection_and_audit_for_benchmark_shapes(layer):
+    for N in (1, 5, 32):
+        dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        v = binding.conv_selected_variant(*dims)
+        assert v > 0, "benchmark shapes must get a tiled MFMA variant"
+        assert binding.conv_variant_applicable(*dims, v)
+        assert binding.bconv_debug_audit(*dims, v) == 0
+
+
+def test_audit_every_applicable_variant_on_small_batch():
+    checked = 0
+    for layer in workloads.ALL_LAYERS:
+        dims = (2, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        for v in range(1, binding.conv_num_variants()):
+            if binding.conv_variant_applicable(*dims, v):
+                assert binding.bconv_debug_audit(*dims, v) == 0, binding.conv_variant_name(v)
+                checked += 1
+    assert checked > 100
+
+
+def test_workspace_query_matches_split():
+    names = binding.variant_ids_by_name()
+    dims = (1, 256, 13, 13, 384, 3, 3, 1, 1)
+    assert binding.conv_fwd_workspace_bytes(*dims, names["k3_64x64_k12/s1"]) == 0
+    assert binding.conv_fwd_workspace_bytes(*dims, names["k3_64x64_k12/s4"]) == 4 * 384 * 169 * 4
+    assert binding.conv_fwd_workspace_bytes(*dims, names["direct"]) == 0

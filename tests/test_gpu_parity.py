@@ -1,0 +1,297 @@
+"""Parity of the HIP library against the CPU oracle, through the C ABI.
+
+Tolerance (stated by the build target): every element must satisfy
+|gpu - oracle| <= max(1e-5, 1e-4 * |oracle|).  Integer-valued problems must
+match bit for bit (fp32 sums of small integers are exact in any order).
+Every float case is checked with relu = 0 and relu = 1: ReLU zeroes about half
+of the outputs, relu = 0 exposes them.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from paper_1606_00094_amd import binding
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-4, 1e-5
+
+
+def assert_close(got, ref, what=""):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    lim = np.maximum(ATOL, RTOL * np.abs(ref.astype(np.float64)))
+    bad = err > lim
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - lim), err.shape)
+        raise AssertionError("%s: %d of %d elements out of tolerance; worst at %s: got %r ref %r"
+                             % (what, int(bad.sum()), bad.size, i, got[i], ref[i]))
+
+
+def gpu_conv(x, f, b, stride, pad, relu, variant=-1, use_simple_entry=False, guard=64):
+    """Runs the library on host arrays; returns out as numpy.  `out` sits between
+    two guard bands that must come back untouched."""
+    dev = torch.device("cuda:0")
+    xd = torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    fd = torch.from_numpy(np.ascontiguousarray(f)).to(dev)
+    bd = torch.from_numpy(np.ascontiguousarray(b)).to(dev) if b is not None else None
+    N, C, H, W = x.shape
+    K, _, R, S = f.shape
+    P, Q = binding.conv_out_dims(H, W, R, S, stride, pad)
+    n_out = N * K * P * Q
+    canary = 1234.5
+    buf = torch.full((n_out + 2 * guard,), canary, dtype=torch.float32, device=dev)
+    out = buf[guard:guard + n_out].view(N, K, P, Q)
+    if use_simple_entry:
+        torch.cuda.synchronize()
+        binding.conv_fwd(xd, fd, bd, out, stride, pad, relu)
+    else:
+        ws = None
+        need = binding.conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant)
+        if need:
+            ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=dev)
+        binding.conv_fwd_ex(xd, fd, bd, out, stride, pad, relu, workspace=ws, variant=variant)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert (host[:guard] == canary).all() and (host[guard + n_out:] == canary).all(), \
+        "store outside the output tensor"
+    return host[guard:guard + n_out].reshape(N, K, P, Q).copy()
+
+
+def _layer_case(layer, N):
+    x, f, b = workloads.make_layer_inputs(layer, N)
+    return x, f, b, layer.stride, layer.pad
+
+
+# ------------------------------------------------------------------ benchmark shapes
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS, ids=lambda l: l.name)
+def test_benchmark_layers_batch1(layer):
+    x, f, b, s, p = _layer_case(layer, 1)
+    ref = oracle.conv_fwd(x, f, b, stride=s, pad=p, relu=False)
+    got = gpu_conv(x, f, b, s, p, False)
+    assert_close(got, ref, layer.name + " relu=0")
+    got = gpu_conv(x, f, b, s, p, True)
+    assert_close(got, np.maximum(ref, 0), layer.name + " relu=1")
+
+
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS[1:], ids=lambda l: l.name)
+def test_benchmark_layers_batch32_sampled_images(layer):
+    """Full-size launch (the configuration the benchmark times); the oracle
+    recomputes three whole images of the batch one by one (images are
+    independent, Section II)."""
+    N = 32
+    x, f, b, s, p = _layer_case(layer, N)
+    refs = {n: oracle.conv_fwd(x[n:n + 1], f, b, stride=s, pad=p, relu=False) for n in (0, 13, 31)}
+    for relu in (False, True):
+        got = gpu_conv(x, f, b, s, p, relu)
+        for n, ref in refs.items():
+            ref = np.maximum(ref, 0) if relu else ref
+            assert_close(got[n:n + 1], ref, "%s N=32 image %d relu=%d" % (layer.name, n, relu))
+        assert np.isfinite(got).all()
+
+
+@pytest.mark.parametrize("layer", [workloads.TOY, workloads.CONV3, workloads.PW_B],
+                         ids=lambda l: l.name)
+def test_simple_entry_point_with_internal_workspace(layer):
+    x, f, b, s, p = _layer_case(layer, 1)
+    ref = oracle.conv_fwd(x, f, b, stride=s, pad=p, relu=True)
+    got = gpu_conv(x, f, b, s, p, True, use_simple_entry=True)
+    assert_close(got, ref, layer.name)
+
+
+def test_direct_variant_on_toy_and_first_layer():
+    for layer in (workloads.TOY, workloads.CONV1):
+        x, f, b, s, p = _layer_case(layer, 1)
+        ref = oracle.conv_fwd(x, f, b, stride=s, pad=p, relu=True)
+        got = gpu_conv(x, f, b, s, p, True, variant=0)
+        assert_close(got, ref, layer.name + " direct")
+
+
+# ------------------------------------------------------------------ exact-integer, every tile
+FAMILY_SHAPES = {
+    # (R, S, stride) of a tile family -> list of (N, C, H, W, K, pad)
+    (3, 3, 1): [(2, 13, 13, 13, 70, 1), (1, 5, 30, 31, 129, 1), (3, 4, 7, 5, 33, 0)],
+    (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2)],
+    (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0)],
+    (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
+    (0, 0, 0): [(2, 3, 9, 10, 7, 1, 2, 4, 2), (1, 5, 20, 17, 40, 3, 7, 7, 2),
+                (1, 4, 8, 8, 6, 0, 1, 1, 2), (2, 3, 12, 12, 130, 2, 3, 3, 3),
+                (1, 2, 6, 40, 3, 0, 1, 16, 1)],
+}
+
+
+def _tile_families():
+    fams = {}
+    for v in range(1, binding.conv_num_variants()):
+        name = binding.conv_variant_name(v)
+        tile = name.split("/")[0]
+        fams.setdefault(tile, []).append(v)
+    return fams
+
+
+def _family_of(tile):
+    if tile.startswith("k3_"):
+        return (3, 3, 1)
+    if tile.startswith("k5_"):
+        return (5, 5, 1)
+    if tile.startswith("pw_"):
+        return (1, 1, 1)
+    if tile.startswith("k11s4_"):
+        return (11, 11, 4)
+    if tile.startswith("gen_"):
+        return (0, 0, 0)
+    raise KeyError(tile)
+
+
+@pytest.mark.parametrize("tile", sorted(_tile_families()))
+def test_every_tile_variant_exact_on_integers(tile):
+    """Each compiled tile, unsplit and with every applicable reduction split, on
+    shapes with ragged filter / pixel / channel tails: bitwise equal to the oracle."""
+    fam = _family_of(tile)
+    ran = 0
+    for shp in FAMILY_SHAPES[fam]:
+        if fam == (0, 0, 0):
+            N, C, H, W, K, pad, R, S, stride = shp
+        else:
+            N, C, H, W, K, pad = shp
+            R, S, stride = fam
+        x, f, b = workloads.make_integer_problem(len(tile) + sum(shp), N, C, H, W, K, R, S)
+        ref = oracle.conv_fwd(x, f, b, stride=stride, pad=pad, relu=False)
+        for v in _tile_families()[tile]:
+            if not binding.conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+                continue
+            assert binding.bconv_debug_audit(N, C, H, W, K, R, S, stride, pad, v) == 0
+            got = gpu_conv(x, f, b, stride, pad, False, variant=v)
+            assert np.array_equal(got, ref), "%s on %s" % (binding.conv_variant_name(v), (shp,))
+            ran += 1
+        got = gpu_conv(x, f, b, stride, pad, True, variant=_tile_families()[tile][0]) \
+            if binding.conv_variant_applicable(N, C, H, W, K, R, S, stride, pad,
+                                               _tile_families()[tile][0]) else np.maximum(ref, 0)
+        assert np.array_equal(got, np.maximum(ref, 0))
+    assert ran > 0
+
+
+# ------------------------------------------------------------------ fuzz
+def test_fuzz_small_shapes_selected_and_direct():
+    rng = np.random.default_rng(20260)
+    for it in range(40):
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride = int(rng.integers(1, 4))
+        pad = int(rng.integers(0, max(R, S) + 1))
+        H = int(rng.integers(max(1, R - 2 * pad), 24))
+        W = int(rng.integers(max(1, S - 2 * pad), 24))
+        N, C, K = int(rng.integers(1, 4)), int(rng.integers(1, 20)), int(rng.integers(1, 70))
+        x, f, b = workloads.make_random_problem(1000 + it, N, C, H, W, K, R, S,
+                                                with_bias=bool(it % 3))
+        ref = oracle.conv_fwd(x, f, b, stride=stride, pad=pad, relu=False)
+        what = "fuzz %d: N%d C%d H%d W%d K%d R%d S%d s%d p%d" % (it, N, C, H, W, K, R, S, stride, pad)
+        assert_close(gpu_conv(x, f, b, stride, pad, False), ref, what + " selected")
+        assert_close(gpu_conv(x, f, b, stride, pad, True, variant=0), np.maximum(ref, 0),
+                     what + " direct")
+
+
+# ------------------------------------------------------------------ edge cases
+@pytest.mark.parametrize("shape", [
+    # N C H  W  K R S s p
+    (1, 1, 1, 1, 1, 1, 1, 1, 0),      # single point
+    (1, 1, 3, 3, 1, 3, 3, 1, 0),      # one output
+    (1, 2, 3, 3, 2, 3, 3, 1, 3),      # windows wholly inside the padding -> bias
+    (2, 3, 5, 9, 4, 1, 1, 2, 0),      # strided pointwise
+    (1, 3, 8, 11, 5, 2, 5, 3, 1),     # R != S, stride 3
+    (1, 1, 4, 300, 2, 3, 3, 1, 1),    # row wider than any pixel tile
+    (5, 7, 1, 1, 33, 1, 1, 1, 0),     # HW = 1: a tile spans many images
+    (1, 35, 6, 6, 3, 3, 3, 1, 1),     # odd channel count: last reduction pair half empty
+])
+def test_edge_shapes(shape):
+    N, C, H, W, K, R, S, s, p = shape
+    x, f, b = workloads.make_integer_problem(sum(shape), N, C, H, W, K, R, S)
+    ref = oracle.conv_fwd(x, f, b, stride=s, pad=p)
+    assert np.array_equal(gpu_conv(x, f, b, s, p, False), ref)
+    assert np.array_equal(gpu_conv(x, f, b, s, p, False, variant=0), ref)
+    assert np.array_equal(gpu_conv(x, f, None, s, p, True), np.maximum(
+        oracle.conv_fwd(x, f, None, stride=s, pad=p), 0))
+
+
+def test_errors_through_binding():
+    dev = torch.device("cuda:0")
+    x = torch.zeros(1, 3, 8, 8, device=dev)
+    f = torch.zeros(4, 3, 3, 3, device=dev)
+    out = torch.zeros(1, 4, 8, 8, device=dev)
+    names = binding.variant_ids_by_name()
+    with pytest.raises(binding.BconvError) as e:      # 5x5-only tile on a 3x3 layer
+        binding.conv_fwd_ex(x, f, None, out, 1, 1, False, variant=names["k5_64x64_k10/s1"])
+    assert e.value.status == -6
+    with pytest.raises(binding.BconvError) as e:      # split needs a workspace
+        binding.conv_fwd_ex(x, f, None, out, 1, 1, False, variant=names["k3_64x64_k12/s2"])
+    assert e.value.status in (-4, -6)
+    big = torch.zeros(1, 64, 8, 8, device=dev)
+    fb = torch.zeros(4, 64, 3, 3, device=dev)
+    with pytest.raises(binding.BconvError) as e:
+        binding.conv_fwd_ex(big, fb, None, out, 1, 1, False, variant=names["k3_64x64_k12/s2"])
+    assert e.value.status == -4
+    tiny = torch.zeros(4, device=dev)
+    with pytest.raises(binding.BconvError) as e:
+        binding.conv_fwd_ex(big, fb, None, out, 1, 1, False, workspace=tiny,
+                            variant=names["k3_64x64_k12/s2"])
+    assert e.value.status == -4
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ max pooling and the stack
+def test_maxpool_parity():
+    dev = torch.device("cuda:0")
+    for (N, C, H, W, k, s) in [(2, 96, 55, 55, 3, 2), (1, 256, 27, 27, 3, 2), (1, 3, 7, 9, 2, 1),
+                               (2, 2, 5, 5, 5, 1)]:
+        x = workloads.make_random_problem(H * W, N, C, H, W, 1, 1, 1)[0]
+        ref = oracle.maxpool_fwd(x, k, s)
+        out = torch.empty(ref.shape, dtype=torch.float32, device=dev)
+        binding.maxpool_fwd(torch.from_numpy(x).to(dev), out, k, s)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), ref)
+
+
+def gpu_stack(img, params):
+    """conv1 -> pool -> conv2 -> pool -> conv3 -> conv4 -> conv5, all fused bias+ReLU,
+    one stream, no host synchronisation between layers.  Returns every layer's
+    input and output as numpy."""
+    dev = torch.device("cuda:0")
+    cur = torch.from_numpy(img).to(dev)
+    acts = []
+    for li, (layer, (f, b)) in enumerate(zip(workloads.STACK, params)):
+        N, C, H, W = cur.shape
+        P, Q = binding.conv_out_dims(H, W, layer.R, layer.S, layer.stride, layer.pad)
+        out = torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)
+        fd, bd = torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev)
+        need = binding.conv_fwd_workspace_bytes(N, C, H, W, layer.K, layer.R, layer.S,
+                                                layer.stride, layer.pad, -1)
+        ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        binding.conv_fwd_ex(cur, fd, bd, out, layer.stride, layer.pad, True, workspace=ws)
+        acts.append((cur, out))
+        cur = out
+        if li in workloads.STACK_POOL_AFTER:
+            pooled = torch.empty((N, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1),
+                                 dtype=torch.float32, device=dev)
+            binding.maxpool_fwd(cur, pooled, 3, 2)
+            cur = pooled
+    torch.cuda.synchronize()
+    return [(a.cpu().numpy(), o.cpu().numpy()) for a, o in acts]
+
+
+@pytest.mark.parametrize("N", [1, 5])
+def test_five_layer_stack(N):
+    img, params = workloads.make_stack_inputs(N)
+    acts = gpu_stack(img, params)
+    # each GPU layer against the oracle applied to that layer's actual GPU input
+    for layer, (f, b), (a_in, a_out) in zip(workloads.STACK, params, acts):
+        ref = oracle.conv_fwd(a_in, f, b, stride=layer.stride, pad=layer.pad, relu=True)
+        assert_close(a_out, ref, "stack N=%d %s" % (N, layer.name))
+    # end to end against the oracle chain
+    cur = img
+    for li, (layer, (f, b)) in enumerate(zip(workloads.STACK, params)):
+        cur = oracle.conv_fwd(cur, f, b, stride=layer.stride, pad=layer.pad, relu=True)
+        if li in workloads.STACK_POOL_AFTER:
+            cur = oracle.maxpool_fwd(cur, 3, 2)
+    assert cur.shape == (N, 256, 13, 13)
+    err = np.abs(acts[-1][1] - cur)
+    assert (err <= np.maximum(1e-4, 1e-3 * np.abs(cur))).all()   # five layers of propagated rounding

@@ -1,0 +1,104 @@
+"""CPU checks of the tiled kernel's host logic and indexing.
+
+``tests/host_emu/emu_tconv.cpp`` walks the device kernel's own index functions
+and launch plan thread by thread on the CPU (bounds-checked, LDS poisoned) and
+models the MFMA by its definition.  Small-integer data makes fp32 exact in any
+order, so the emulated result must equal the oracle bit for bit; any staging,
+padding, tail or split mistake shows up here before a kernel is launched.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "host_emu", "emu_tconv.cpp")
+LIB = os.path.join(HERE, "host_emu", "libemu.so")
+_f32p = ctypes.POINTER(ctypes.c_float)
+
+
+@pytest.fixture(scope="module")
+def emu():
+    csrc = os.path.join(HERE, "..", "paper_1606_00094_amd", "csrc")
+    deps = [SRC] + [os.path.join(csrc, f) for f in ("bconv_plan.h", "bconv_geom.h", "variants.def")]
+    if not os.path.exists(LIB) or os.path.getmtime(LIB) < max(os.path.getmtime(d) for d in deps):
+        subprocess.run(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", LIB, SRC], check=True)
+    lib = ctypes.CDLL(LIB)
+    lib.emu_tconv.argtypes = [_f32p] * 4 + [ctypes.c_int] * 12
+    lib.emu_tconv.restype = ctypes.c_longlong
+    lib.emu_num_tiles.restype = ctypes.c_int
+    lib.emu_tile_name.restype = ctypes.c_char_p
+    lib.emu_tile_name.argtypes = [ctypes.c_int]
+    return lib
+
+
+def _tiles(lib):
+    return {lib.emu_tile_name(t).decode(): t for t in range(lib.emu_num_tiles())}
+
+
+def _run(lib, tile, nsplit, x, f, b, stride, pad, relu):
+    N, C, H, W = x.shape
+    K, _, R, S = f.shape
+    P, Q = oracle.conv_out_dims(H, W, R, S, stride, pad)
+    out = np.full((N, K, P, Q), np.nan, np.float32)
+    ptr = lambda a: a.ctypes.data_as(_f32p)
+    rc = lib.emu_tconv(ptr(x), ptr(f), ptr(b) if b is not None else None, ptr(out),
+                       N, C, H, W, K, R, S, stride, pad, int(relu), tile, nsplit)
+    return rc, out
+
+
+# (tile name, N, C, H, W, K, R, S, stride, pad, nsplit)
+CASES = [
+    ("k3_64x64_k12", 2, 5, 13, 13, 40, 3, 3, 1, 1, 1),
+    ("k3_64x64_k12", 3, 13, 13, 13, 70, 3, 3, 1, 1, 2),
+    ("k3_128x128_k12", 2, 7, 13, 13, 130, 3, 3, 1, 1, 1),
+    ("k3_32x128_k12", 1, 3, 32, 32, 16, 3, 3, 1, 1, 1),
+    ("k3_64x64_k12", 1, 6, 9, 200, 33, 3, 3, 1, 0, 1),      # wide rows: Q > BN
+    ("k3_64x64_k12", 1, 4, 6, 7, 5, 3, 3, 1, 3, 1),         # pad >= kernel
+    ("k5_64x64_k10", 2, 3, 11, 9, 20, 5, 5, 1, 2, 1),
+    ("k5_32x128_k10", 1, 16, 28, 28, 32, 5, 5, 1, 2, 2),
+    ("pw_64x64_k16", 3, 21, 7, 7, 50, 1, 1, 1, 0, 1),
+    ("pw_128x128_k16", 2, 33, 14, 14, 100, 1, 1, 1, 0, 3),
+    ("pw_32x128_k16", 1, 5, 28, 28, 9, 1, 1, 1, 0, 1),
+    ("k11s4_32x128_k4", 1, 3, 67, 71, 20, 11, 11, 4, 0, 1),
+    ("k11s4_96x128_k4", 2, 3, 43, 43, 96, 11, 11, 4, 0, 3),
+    ("k11s4_96x64_k4", 1, 3, 51, 47, 10, 11, 11, 4, 2, 1),
+    ("gen_64x64_k2", 2, 3, 9, 10, 7, 2, 4, 2, 1, 1),
+    ("gen_64x64_k2", 1, 2, 12, 12, 5, 3, 3, 3, 2, 2),
+    ("gen_32x128_k2", 1, 4, 8, 8, 6, 1, 1, 2, 0, 1),        # strided pointwise: no flattening
+    ("gen_128x128_k2", 1, 3, 20, 17, 9, 7, 7, 2, 3, 1),
+    ("gen_64x64_k2", 1, 1, 5, 40, 3, 1, 16, 1, 0, 1),        # widest generic kernel
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "%s-N%dC%dH%dW%dK%dR%dS%ds%dp%d-sk%d" % c)
+def test_emulated_kernel_matches_oracle_bitwise_on_integers(emu, case):
+    name, N, C, H, W, K, R, S, stride, pad, nsplit = case
+    tile = _tiles(emu)[name]
+    x, f, b = workloads.make_integer_problem(hash(case) % 10000, N, C, H, W, K, R, S)
+    for relu in (False, True):
+        rc, got = _run(emu, tile, nsplit, x, f, b, stride, pad, relu)
+        assert rc == 0, "emulation reported %d (1 = tile not applicable, >1 = bad accesses)" % rc
+        ref = oracle.conv_fwd(x, f, b, stride=stride, pad=pad, relu=relu)
+        assert np.array_equal(got, ref)
+
+
+def test_emulated_kernel_float_data_within_tolerance(emu):
+    tile = _tiles(emu)["k3_64x64_k12"]
+    x, f, b = workloads.make_random_problem(5, 2, 24, 13, 13, 48, 3, 3)
+    rc, got = _run(emu, tile, 1, x, f, b, 1, 1, False)
+    assert rc == 0
+    ref = oracle.conv_fwd(x, f, b, stride=1, pad=1)
+    assert np.all(np.abs(got - ref) <= np.maximum(1e-5, 1e-4 * np.abs(ref)))
+
+
+def test_tile_that_does_not_apply_is_refused(emu):
+    tile = _tiles(emu)["k3_64x64_k12"]
+    x, f, b = workloads.make_integer_problem(1, 1, 2, 8, 8, 4, 5, 5)
+    rc, _ = _run(emu, tile, 1, x, f, b, 1, 2, False)
+    assert rc == 1
