@@ -40,6 +40,10 @@ def lib():
     """The loaded library; raises if it has not been built."""
     global _lib
     if _lib is None:
+        # torch ships its own HIP runtime; it must be in the process first so that
+        # libbconv binds to that same runtime (two runtimes in one process do not
+        # share devices, streams or allocations).
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libbconv.so not built: run `python -m paper_1606_00094_amd.build` "
                                "(there is no CPU fallback)")

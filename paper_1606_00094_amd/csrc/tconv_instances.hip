@@ -1,33 +1,43 @@
 // Instantiations of the tiled MFMA convolution kernel, one group of variants.def
 // rows per translation unit (BCONV_GROUP is set on the compiler command line).
+#include <cstdio>
+#include <cstdlib>
+
 #include "bconv_internal.h"
 #include "tconv_mfma.hpp"
 
 namespace bconv {
 
+static void report(const char* what, hipError_t e) {
+  if (std::getenv("BCONV_DEBUG"))
+    std::fprintf(stderr, "bconv: %s: %s\n", what, hipGetErrorString(e));
+}
+
 template <typename KernelT>
 static hipError_t launch_tile_kernel(KernelT kernel, int nthr, const TconvParams& p, dim3 grid,
-                                     size_t lds_bytes, hipStream_t st, bool* attr_set) {
-  // Dynamic LDS above 64 KB must be allowed once per kernel and device.
+                                     size_t lds_bytes, hipStream_t st, size_t* lds_allowed) {
+  // Dynamic LDS above the default limit must be allowed per kernel and device.
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess) { report("hipGetDevice", e); return e; }
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (!attr_set[dev]) {
+  if (lds_bytes > 32768 && lds_bytes > lds_allowed[dev]) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimitBytes);
-    if (e != hipSuccess) return e;
-    attr_set[dev] = true;
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) { report("hipFuncSetAttribute", e); (void)hipGetLastError(); return e; }
+    lds_allowed[dev] = lds_bytes;
   }
   hipLaunchKernelGGL(kernel, grid, dim3(nthr), lds_bytes, st, p);
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (e != hipSuccess) report("kernel launch", e);
+  return e;
 }
 
 #define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT)                                          \
   hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st) { \
-    static bool attr_set[64] = {false};                                                       \
+    static size_t lds_allowed[64] = {0};                                                       \
     return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT>,          \
-                              WM * WN * 64, p, grid, lds_bytes, st, attr_set);                \
+                              WM * WN * 64, p, grid, lds_bytes, st, lds_allowed);                \
   }
 #include "variants.def"
 #undef X
