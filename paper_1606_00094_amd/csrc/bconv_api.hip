@@ -2,6 +2,7 @@
 // the per-shape selection (paper Section V: operation -> variant -> blocking
 // constants) and the host-only bounds audit.  No arithmetic of the convolution
 // is done on the host.
+#include <cstdint>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -13,7 +14,7 @@ namespace bconv {
 
 // ------------------------------------------------------------------ catalogue
 static const TileLaunchFn kLaunch[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT) launch_##name,
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV) launch_##name,
 #include "variants.def"
 #undef X
 };
@@ -88,25 +89,28 @@ static double model_cost(const TileDesc& v, const Plan& pl) {
   return t;
 }
 
-static int select_variant(const Shape& s) {
+static int select_variant(const Shape& s, bool filt_aligned16 = true) {
   for (const TableRow* r = kTable; r->tile; ++r) {
     if (r->N == s.N && r->C == s.C && r->H == s.H && r->W == s.W && r->K == s.K && r->R == s.R &&
         r->S == s.S && r->stride == s.stride && r->pad == s.pad) {
       int id = find_variant(r->tile, r->nsplit);
       int t, ns;
       Plan pl;
-      if (id > 0 && decode_variant(id, &t, &ns) && plan_tconv(s, kTiles[t], ns, &pl)) return id;
+      if (id > 0 && decode_variant(id, &t, &ns) && (filt_aligned16 || kTiles[t].AV == 1) &&
+          plan_tconv(s, kTiles[t], ns, &pl))
+        return id;
     }
   }
   int best = 0;
   double best_cost = 0.0;
   for (int t = 0; t < kNumTiles; ++t) {
-    // a tile compiled for this kernel size beats the run-time generic one
+    if (!filt_aligned16 && kTiles[t].AV != 1) continue;
     for (int i = 0; i < kNumSplits; ++i) {
       Plan pl;
       if (!plan_tconv(s, kTiles[t], kSplits[i], &pl)) continue;
       double c = model_cost(kTiles[t], pl);
-      if (!kTiles[t].S) c *= 1.3;
+      if (!kTiles[t].S) c *= 3.0;          // a tile compiled for this kernel size beats the generic one
+      if (kTiles[t].AV == 4) c *= 0.97;    // wider filter loads, otherwise the same tile
       if (best == 0 || c < best_cost) {
         best = 1 + t * kNumSplits + i;
         best_cost = c;
@@ -152,7 +156,8 @@ static int internal_workspace(size_t need, void** out) {
 static int run_conv(const float* in, const float* filt, const float* bias, float* out,
                     const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
                     hipStream_t st, int variant_id) {
-  if (variant_id < 0) variant_id = select_variant(s);
+  const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & 15u) == 0;
+  if (variant_id < 0) variant_id = select_variant(s, aligned16);
   if (variant_id == 0) {
     return launch_direct_conv(in, filt, bias, out, s, relu, st) == hipSuccess ? BCONV_OK
                                                                               : BCONV_ELAUNCH;
@@ -161,6 +166,7 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
   Plan pl;
   if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
+  if (kTiles[t].AV == 4 && !aligned16) return BCONV_EVARIANT;
   if (pl.ws_bytes) {
     if (own_ws) {
       int rc = internal_workspace(pl.ws_bytes, &ws);
@@ -192,11 +198,11 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
   const long long in_elems = (long long)p.N * p.CHW;
   const int ncell = p.nrows * p.rowst;
   if (p.ast < v.KR * p.S) ++bad;
-  if ((size_t)(2 * BM * p.ast + 2 * v.KR * p.plane) * 4 != pl.lds_bytes) ++bad;
+  if ((size_t)(2 * BM * p.ast + 2 * v.KR * p.plane + kLdsTrashWords) * 4 != pl.lds_bytes) ++bad;
   for (unsigned bx = 0; bx < pl.gx; ++bx) {
     PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
     if (t.cnt < 1 || t.cnt > BN) ++bad;
-    if (t.rho1 - t.rho0 + 1 > p.nrows) ++bad;
+    if (!p.compact && t.rho1 - t.rho0 + 1 > p.nrows) ++bad;
     // staged cells: each LDS word of a plane is written by exactly one cell
     for (int e = 0; e < v.EPT * NTHR; ++e) {
       if (e >= ncell) continue;

@@ -40,6 +40,7 @@ struct TconvParams {
   int relu;
   int PQ, NPQ, HW, CHW, CRS, CRrows;   // CRrows = C*R reduction rows
   int nrows, phst, rowst, plane;       // staged-input geometry, plane = nrows*rowst
+  int compact;                         // S == 1 and stride == 1: one staged cell per tile pixel
   int ast;                             // LDS stride between filter rows (odd)
   int nchunks, chunks_per_split, nsplit;
   int out_elems;                       // N*K*P*Q
@@ -89,6 +90,22 @@ struct BCell {
 
 BCONV_HD BCell b_cell(const TconvParams& p, const PixTile& t, int e, int S, int STR) {
   BCell c;
+  if (p.compact) {
+    // kernel width 1 at stride 1: cell e is the input word under tile pixel e
+    bool ok = e < t.cnt;
+    int g = t.g0 + (ok ? e : 0);
+    int rho = g / p.Q;
+    int q = g - rho * p.Q;
+    int img = rho / p.P;
+    int pp = rho - img * p.P;
+    int iw = q - p.pad;
+    ok = ok && (iw >= 0) && (iw < p.W);
+    int ih0 = pp - p.pad;
+    c.lds = e;
+    c.goff = img * p.CHW + ih0 * p.W + iw;
+    c.ih0 = ok ? ih0 : kNeverValid;
+    return c;
+  }
   int slot = e / p.rowst;
   int xrel = e - slot * p.rowst;
   int rho = t.rho0 + slot;
@@ -127,7 +144,7 @@ BCONV_HD BLane b_lane(const TconvParams& p, const PixTile& t, int col) {
   int qlo = (slot == 0) ? t.q00 : 0;
   int img = rho / p.P;
   int pp = rho - img * p.P;
-  l.ldsbase = slot * p.rowst + (q - qlo);
+  l.ldsbase = p.compact ? cc : slot * p.rowst + (q - qlo);
   l.outoff = img * p.K * p.PQ + pp * p.Q + q;
   return l;
 }

@@ -17,14 +17,14 @@ struct Shape {
 struct TileDesc {
   const char* name;
   int R, S, STR;            // 0 = run-time value
-  int WM, WN, MT, NT, KR, EPT;
+  int WM, WN, MT, NT, KR, EPT, AV;
   int BM() const { return WM * MT * 32; }
   int BN() const { return WN * NT * 32; }
   int NTHR() const { return WM * WN * 64; }
 };
 
 static const TileDesc kTileDescs[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT) {#name, R, S, STR, WM, WN, MT, NT, KR, EPT},
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV) {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV},
 #include "variants.def"
 #undef X
 };
@@ -32,6 +32,7 @@ constexpr int kNumTiles = (int)(sizeof(kTileDescs) / sizeof(kTileDescs[0]));
 
 constexpr size_t kLdsLimitBytes = 160 * 1024;
 constexpr int kSmaxGeneric = 16;   // widest kernel the run-time generic tiles take
+constexpr int kLdsTrashWords = 16; // LDS words behind the staging buffers that absorb masked stores
 
 struct Plan {
   TconvParams p;
@@ -46,6 +47,7 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   Shape s = s0;
   if ((v.R && v.R != s.R) || (v.S && v.S != s.S) || (v.STR && v.STR != s.stride)) return false;
   if (!v.S && s.S > kSmaxGeneric) return false;
+  if (v.AV == 4 && ((long long)s.C * s.R * s.S) % 4 != 0) return false;
   const long long i31 = (1LL << 31) - 1;
   if ((long long)s.N * s.C * s.H * s.W > i31 || (long long)s.K * s.C * s.R * s.S > i31 ||
       (long long)s.N * s.K * s.P * s.Q > i31)
@@ -71,13 +73,20 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   p.out_elems = s.N * s.K * p.PQ;
   const int BN = v.BN(), BM = v.BM();
   long long total_rows = (long long)s.N * s.P;
-  p.nrows = tile_nrows(BN, s.Q, total_rows > i31 ? (int)i31 : (int)total_rows);
-  p.phst = tile_phst(BN, s.Q, s.S, s.stride);
-  p.rowst = s.stride * p.phst;
+  p.compact = (s.S == 1 && s.stride == 1) ? 1 : 0;
+  if (p.compact) {
+    p.nrows = 1;
+    p.phst = BN;
+    p.rowst = BN;
+  } else {
+    p.nrows = tile_nrows(BN, s.Q, total_rows > i31 ? (int)i31 : (int)total_rows);
+    p.phst = tile_phst(BN, s.Q, s.S, s.stride);
+    p.rowst = s.stride * p.phst;
+  }
   p.plane = p.nrows * p.rowst;
   if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR()) return false;
   p.ast = (v.KR * s.S) | 1;
-  size_t lds = (size_t)(2 * BM * p.ast + 2 * v.KR * p.plane) * sizeof(float);
+  size_t lds = (size_t)(2 * BM * p.ast + 2 * v.KR * p.plane + kLdsTrashWords) * sizeof(float);
   if (lds > kLdsLimitBytes) return false;
   p.nchunks = (p.CRrows + v.KR - 1) / v.KR;
   if (nsplit < 1 || nsplit > p.nchunks) return false;

@@ -1,0 +1,120 @@
+"""Offline tuning sweep: times every applicable variant (tile shape x reduction
+split) on each benchmark layer shape and batch size and writes the per-shape
+selection table the library compiles in.
+
+This plays the role the paper gives to its per-operation choice of variant and
+blocking constants (Section V: blocking chosen by heuristics and manual tuning,
+automated tuning named as future work; Section VI: variant per convolution).
+
+    python -m paper_1606_00094_amd.tune --out gpurun_out/tune.json \
+        --table gpurun_out/selection_table.inc
+
+Each candidate is timed as a HIP graph of back-to-back launches (no host launch
+overhead in the figure) and its output is compared with the direct kernel's.
+"""
+import argparse
+import json
+import sys
+
+import torch
+
+import workloads
+from paper_1606_00094_amd import binding, roofline
+
+
+def graph_time_us(fn, launches=20, replays=5):
+    """Microseconds per launch of fn, from replaying a captured graph of
+    `launches` back-to-back calls; best of `replays`."""
+    fn()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(launches):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    best = float("inf")
+    for _ in range(replays):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) * 1e3 / launches)
+    return best
+
+
+def sweep_layer(layer, N, check=True):
+    dev = torch.device("cuda:0")
+    x, f, b = workloads.make_layer_inputs(layer, N)
+    xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
+    dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+    P, Q = workloads.out_hw(layer)
+    out = torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)
+    ref = torch.empty_like(out)
+    binding.conv_fwd_ex(xd, fd, bd, ref, layer.stride, layer.pad, True, variant=0)
+    flops = roofline.conv_flops(*dims)
+    rows = []
+    for v in range(1, binding.conv_num_variants()):
+        if not binding.conv_variant_applicable(*dims, v):
+            continue
+        need = binding.conv_fwd_workspace_bytes(*dims, v)
+        ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+
+        def run():
+            binding.conv_fwd_ex(xd, fd, bd, out, layer.stride, layer.pad, True, workspace=ws,
+                                variant=v)
+        us = graph_time_us(run)
+        ok = True
+        if check:
+            err = (out - ref).abs()
+            ok = bool((err <= torch.clamp(ref.abs() * 1e-4, min=1e-5) * 2).all())
+        rows.append({"variant": binding.conv_variant_name(v), "us": round(us, 2),
+                     "tflops": round(flops / us / 1e6, 2), "ok": ok})
+        del ws
+    rows.sort(key=lambda r: r["us"])
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default="gpurun_out/tune.json")
+    ap.add_argument("--table", default="gpurun_out/selection_table.inc")
+    ap.add_argument("--batches", default="1,5,20,32")
+    ap.add_argument("--layers", default="")
+    args = ap.parse_args()
+    batches = [int(t) for t in args.batches.split(",")]
+    names = [t for t in args.layers.split(",") if t]
+    layers = [l for l in workloads.ALL_LAYERS if not names or l.name in names]
+    results, table = [], []
+    for layer in layers:
+        for N in batches:
+            rows = sweep_layer(layer, N)
+            good = [r for r in rows if r["ok"]]
+            best = good[0] if good else None
+            results.append({"layer": layer.name, "N": N, "best": best, "all": rows})
+            print("%-18s N=%-3d best %-24s %9.2f us %7.2f TFLOP/s  (%d candidates, %d failed check)"
+                  % (layer.name, N, best["variant"] if best else "-", best["us"] if best else 0,
+                     best["tflops"] if best else 0, len(rows), len(rows) - len(good)), flush=True)
+            if best:
+                tile, split = best["variant"].split("/s")
+                table.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, "%s", %s},  // %s N=%d: %.1f us'
+                             % (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride,
+                                layer.pad, tile, split, layer.name, N, best["us"]))
+    with open(args.out, "w") as fh:
+        json.dump(results, fh, indent=1)
+    with open(args.table, "w") as fh:
+        fh.write("// Per-shape variant choices, written by the offline tuning sweep\n"
+                 "// (paper_1606_00094_amd/tune.py).  Row: {N, C, H, W, K, R, S, stride, pad, \"tile\", nsplit},\n")
+        fh.write("\n".join(table) + "\n")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -46,10 +46,12 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
   const int KRS = KR * Sk;
   const int SP = v.S > 0 ? v.S : kSmaxGeneric;
   const int KRSP = KR * SP;
-  const int APT = (BM * KRSP + NTHR - 1) / NTHR;
+  const int AV = v.AV;
+  const int AGRP = KRSP / AV;
+  const int NA = (BM * AGRP + NTHR - 1) / NTHR;
   const long long in_elems = (long long)p.N * p.CHW, filt_elems = (long long)p.K * p.CRS;
   const int abuf = BM * p.ast, bbuf = KR * p.plane;
-  if ((size_t)(2 * abuf + 2 * bbuf) * 4 != pl.lds_bytes) return 2;
+  if ((size_t)(2 * abuf + 2 * bbuf + kLdsTrashWords) * 4 != pl.lds_bytes) return 2;
   Oob oob;
   const float nanv = std::numeric_limits<float>::quiet_NaN();
   std::vector<float> partial((size_t)p.nsplit * p.out_elems, nanv);
@@ -72,16 +74,19 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
       const int kk0 = ch * KR;
       const int col0 = kk0 * Sk;
       for (int tid = 0; tid < NTHR; ++tid) {
-        for (int i = 0; i < APT; ++i) {
+        for (int i = 0; i < NA; ++i) {
           int e = tid + i * NTHR;
-          int m = e / KRSP, j = e - m * KRSP;
+          int m = e / AGRP, j = (e - m * AGRP) * AV;
           bool ok = (m < BM) && (j < KRS) && (m0 + m < p.K) && (col0 + j < p.CRS);
           long long gi = ok ? (long long)(m0 + m) * p.CRS + col0 + j : 0;
-          if (gi < 0 || gi >= filt_elems) { oob.hit("filt", gi, filt_elems); continue; }
-          float val = ok ? filt[gi] : 0.0f;
-          if ((m < BM) && (j < KRS)) {
-            int li = m * p.ast + j;
-            if (li < 0 || li >= abuf) oob.hit("A lds", li, abuf); else As[li] = val;
+          if (AV == 4 && (gi % 4) != 0) oob.hit("filt alignment", gi, 4);
+          for (int u = 0; u < AV; ++u) {
+            if (gi + u < 0 || gi + u >= filt_elems) { oob.hit("filt", gi + u, filt_elems); continue; }
+            float val = ok ? filt[gi + u] : 0.0f;
+            if ((m < BM) && (j < KRS)) {
+              int li = m * p.ast + j + u;
+              if (li < 0 || li >= abuf) oob.hit("A lds", li, abuf); else As[li] = val;
+            }
           }
         }
         int c = kk0 / Rk, r = kk0 - c * Rk;

@@ -112,7 +112,7 @@ def test_direct_variant_on_toy_and_first_layer():
 FAMILY_SHAPES = {
     # (R, S, stride) of a tile family -> list of (N, C, H, W, K, pad)
     (3, 3, 1): [(2, 13, 13, 13, 70, 1), (1, 5, 30, 31, 129, 1), (3, 4, 7, 5, 33, 0)],
-    (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2)],
+    (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2), (1, 8, 27, 27, 70, 2)],
     (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0)],
     (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
     (0, 0, 0): [(2, 3, 9, 10, 7, 1, 2, 4, 2), (1, 5, 20, 17, 40, 3, 7, 7, 2),
@@ -220,7 +220,7 @@ def test_errors_through_binding():
     out = torch.zeros(1, 4, 8, 8, device=dev)
     names = binding.variant_ids_by_name()
     with pytest.raises(binding.BconvError) as e:      # 5x5-only tile on a 3x3 layer
-        binding.conv_fwd_ex(x, f, None, out, 1, 1, False, variant=names["k5_64x64_k10/s1"])
+        binding.conv_fwd_ex(x, f, None, out, 1, 1, False, variant=names["k5_64x64_k8/s1"])
     assert e.value.status == -6
     with pytest.raises(binding.BconvError) as e:      # split needs a workspace
         binding.conv_fwd_ex(x, f, None, out, 1, 1, False, variant=names["k3_64x64_k12/s2"])

@@ -60,15 +60,26 @@ CASES = [
     ("k3_32x128_k12", 1, 3, 32, 32, 16, 3, 3, 1, 1, 1),
     ("k3_64x64_k12", 1, 6, 9, 200, 33, 3, 3, 1, 0, 1),      # wide rows: Q > BN
     ("k3_64x64_k12", 1, 4, 6, 7, 5, 3, 3, 1, 3, 1),         # pad >= kernel
-    ("k5_64x64_k10", 2, 3, 11, 9, 20, 5, 5, 1, 2, 1),
-    ("k5_32x128_k10", 1, 16, 28, 28, 32, 5, 5, 1, 2, 2),
+    ("k5_64x64_k8", 2, 3, 11, 9, 20, 5, 5, 1, 2, 1),
+    ("k5_32x128_k8", 1, 16, 28, 28, 32, 5, 5, 1, 2, 2),
     ("pw_64x64_k16", 3, 21, 7, 7, 50, 1, 1, 1, 0, 1),
     ("pw_128x128_k16", 2, 33, 14, 14, 100, 1, 1, 1, 0, 3),
     ("pw_32x128_k16", 1, 5, 28, 28, 9, 1, 1, 1, 0, 1),
     ("k11s4_32x128_k4", 1, 3, 67, 71, 20, 11, 11, 4, 0, 1),
     ("k11s4_96x128_k4", 2, 3, 43, 43, 96, 11, 11, 4, 0, 3),
     ("k11s4_96x64_k4", 1, 3, 51, 47, 10, 11, 11, 4, 2, 1),
+    ("k3_64x64_k12_v4", 2, 8, 13, 13, 40, 3, 3, 1, 1, 1),
+    ("k3_128x256_k12_v4", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),
+    ("k3_64x256_k12", 2, 5, 13, 13, 40, 3, 3, 1, 1, 1),
+    ("k5_128x64_k8_v4", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
+    ("k5_256x128_k8", 1, 3, 27, 27, 260, 5, 5, 1, 2, 1),
+    ("pw_64x256_k16_v4", 2, 20, 14, 14, 70, 1, 1, 1, 0, 1),
+    ("pw_128x256_k32_v4", 3, 68, 7, 7, 130, 1, 1, 1, 0, 2),
+    ("pw_64x128_k16", 2, 6, 5, 9, 40, 1, 1, 1, 1, 1),           # pointwise with padding
+    ("k11s4_96x256_k4", 2, 3, 67, 71, 96, 11, 11, 4, 0, 1),
+    ("k11s4_32x128_k2", 1, 3, 51, 47, 10, 11, 11, 4, 2, 2),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 2, 4, 2, 1, 1),
+    ("gen_64x64_k2", 2, 3, 9, 10, 7, 3, 1, 1, 1, 1),            # S = 1, stride 1, R = 3: compact cells
     ("gen_64x64_k2", 1, 2, 12, 12, 5, 3, 3, 3, 2, 2),
     ("gen_32x128_k2", 1, 4, 8, 8, 6, 1, 1, 2, 0, 1),        # strided pointwise: no flattening
     ("gen_128x128_k2", 1, 3, 20, 17, 9, 7, 7, 2, 3, 1),
