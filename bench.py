@@ -127,7 +127,7 @@ def run_stack(N, reps):
             else:
                 binding.maxpool_fwd(bufs[op[1]], bufs[op[2]], 3, 2)
 
-    ms = time_launches(step, reps)
+    ms = graph_time_us(step, launches=reps) * 1e-3
     return {"N": N, "ms": round(ms, 4), "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
             "frac_mfma": round(flops / (ms * 1e-3) / 1e12 / roofline.PEAK_FP32_MFMA_TFLOPS, 4)}
 
@@ -162,6 +162,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer-table", action="store_true")
     ap.add_argument("--cpu-baseline-batch", type=int, default=8)
+    ap.add_argument("--layers", default="", help="comma-separated layer names (default: all ten)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (--gpus %d refused)" % args.gpus)
@@ -170,6 +174,8 @@ def main():
     import torch
     import workloads
     from paper_1606_00094_amd import binding, roofline
+    global graph_time_us
+    from paper_1606_00094_amd.timing import graph_time_us
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible; the library has no CPU path")
         sys.exit(1)
@@ -177,6 +183,15 @@ def main():
     torch.cuda.set_device(0)
 
     layers = workloads.CONFIG_FIRST + workloads.CONFIG_MIDDLE + workloads.CONFIG_POINTWISE
+    if args.layers:
+        layers = [workloads.BY_NAME[n] for n in args.layers.split(",")]
+    if args.calibration_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     probs = [LayerProblem(l, args.batch) for l in layers]
     total_flops = sum(p.flops for p in probs)
 
@@ -204,24 +219,25 @@ def main():
     table = []
     per_layer_ms = {}
     for p in probs:
-        ms = time_launches(p.launch, 30)
+        ms = graph_time_us(p.launch, launches=10) * 1e-3
         per_layer_ms[p.layer.name] = ms
         table.append(layer_row(p, ms, "warm"))
     if not args.no_layer_table:
         for l in [workloads.TOY] + layers:
             p1 = LayerProblem(l, 1)
-            table.append(layer_row(p1, time_launches(p1.launch, 200, warm=10), "warm"))
+            table.append(layer_row(p1, graph_time_us(p1.launch, launches=20) * 1e-3, "warm"))
             # cold: rotate through enough distinct tensor sets that nothing stays in cache
-            copies = int(min(256, max(2, (600 << 20) // max(1, p1.bytes))))
+            copies = int(min(192, max(2, (600 << 20) // max(1, p1.bytes))))
             pc = LayerProblem(l, 1, copies=copies)
-            table.append(layer_row(pc, time_launches(pc.launch, copies, warm=2), "cold"))
+            table.append(layer_row(pc, graph_time_us(pc.launch, launches=copies, replays=3) * 1e-3,
+                                   "cold"))
             del p1, pc
     for row in table:
         log(json.dumps(row))
 
     # ---- roofline of the dominant kernel (largest share of the step)
     dom = max(probs, key=lambda p: per_layer_ms[p.layer.name])
-    dom_ms = time_launches(dom.launch, 50)
+    dom_ms = graph_time_us(dom.launch, launches=20) * 1e-3
     achieved = dom.flops / (dom_ms * 1e-3) / 1e12
     roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": roofline.PEAK_FP32_MFMA_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / roofline.PEAK_FP32_MFMA_TFLOPS, 4),
@@ -242,8 +258,10 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "one pass over the 10 benchmark conv layers (first layer, 4 middle, "
-                               "3 pointwise, 2 reduce) at batch %d, bias + ReLU fused" % args.batch,
+        "config": {"workload": ("one pass over the 10 benchmark conv layers (first layer, 4 middle, "
+                                "3 pointwise, 2 reduce) at batch %d, bias + ReLU fused" % args.batch)
+                               if not args.layers else
+                               "layers %s at batch %d, bias + ReLU fused" % (args.layers, args.batch),
                    "batch": args.batch, "gflop_per_step": round(total_flops / 1e9, 2)},
         "roofline": roof, "cpu_baseline": cpu, "layers": table, "stack": stack,
     }), flush=True)

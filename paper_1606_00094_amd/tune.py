@@ -20,34 +20,7 @@ import torch
 
 import workloads
 from paper_1606_00094_amd import binding, roofline
-
-
-def graph_time_us(fn, launches=20, replays=5):
-    """Microseconds per launch of fn, from replaying a captured graph of
-    `launches` back-to-back calls; best of `replays`."""
-    fn()
-    torch.cuda.synchronize()
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        fn()
-    torch.cuda.current_stream().wait_stream(side)
-    torch.cuda.synchronize()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
-        for _ in range(launches):
-            fn()
-    g.replay()
-    torch.cuda.synchronize()
-    best = float("inf")
-    for _ in range(replays):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        g.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        best = min(best, e0.elapsed_time(e1) * 1e3 / launches)
-    return best
+from paper_1606_00094_amd.timing import graph_time_us
 
 
 def sweep_layer(layer, N, check=True):
