@@ -14,7 +14,7 @@ namespace bconv {
 
 // ------------------------------------------------------------------ catalogue
 static const TileLaunchFn kLaunch[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV) launch_##name,
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS) launch_##name,
 #include "variants.def"
 #undef X
 };
@@ -198,7 +198,8 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
   const long long in_elems = (long long)p.N * p.CHW;
   const int ncell = p.nrows * p.rowst;
   if (p.ast < v.KR * p.S) ++bad;
-  if ((size_t)(2 * BM * p.ast + 2 * v.KR * p.plane + kLdsTrashWords) * 4 != pl.lds_bytes) ++bad;
+  if ((size_t)(2 * BM * p.ast + 2 * (v.KR * p.plane + kLdsTrashWords) + kLdsTrashWords) * 4 > pl.lds_bytes) ++bad;
+  if (v.KS > 1 && (size_t)BM * BN * 4 > pl.lds_bytes) ++bad;
   for (unsigned bx = 0; bx < pl.gx; ++bx) {
     PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
     if (t.cnt < 1 || t.cnt > BN) ++bad;

@@ -41,6 +41,7 @@ struct TconvParams {
   int PQ, NPQ, HW, CHW, CRS, CRrows;   // CRrows = C*R reduction rows
   int nrows, phst, rowst, plane;       // staged-input geometry, plane = nrows*rowst
   int compact;                         // S == 1 and stride == 1: one staged cell per tile pixel
+  int gbias;                           // pad*W + pad: most negative cell offset, see the kernel's loads
   int ast;                             // LDS stride between filter rows (odd)
   int nchunks, chunks_per_split, nsplit;
   int out_elems;                       // N*K*P*Q
@@ -152,6 +153,22 @@ BCONV_HD BLane b_lane(const TconvParams& p, const PixTile& t, int col) {
 // LDS word offset of kernel column s relative to a lane's ldsbase.
 BCONV_HD int tap_off(int s, int STR, int phst) {
   return (s % STR) * phst + s / STR;
+}
+
+// Words per LDS read of a lane's filter run: the run of reduction group g inside
+// half-chunk h starts at word h*(KR/2)*S + g*(KR/2/KS)*S of a filter row, so the
+// read width is limited by the alignment of both terms.  Run-time S (S = 0): 1.
+BCONV_HD constexpr int a_read_width(int KR, int S, int KS) {
+  return S <= 0 ? 1
+         : ((((KR / 2) * S) % 4 == 0 && ((KR / 2 / KS) * S) % 4 == 0) ? 4
+            : ((((KR / 2) * S) % 2 == 0 && ((KR / 2 / KS) * S) % 2 == 0) ? 2 : 1));
+}
+
+// LDS stride (words) between filter rows holding KRS words each: a multiple of
+// the read width whose quotient is odd, which spreads rows over all banks for
+// 4-, 8- and 16-byte reads alike.
+BCONV_HD constexpr int a_row_stride(int KRS, int vw) {
+  return (((KRS + vw - 1) / vw) | 1) * vw;
 }
 
 // Row of a 32x32 MFMA accumulator tile held by (lane, register i), i in [0,16).

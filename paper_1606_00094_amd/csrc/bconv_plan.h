@@ -17,14 +17,15 @@ struct Shape {
 struct TileDesc {
   const char* name;
   int R, S, STR;            // 0 = run-time value
-  int WM, WN, MT, NT, KR, EPT, AV;
+  int WM, WN, MT, NT, KR, EPT, AV, KS;
   int BM() const { return WM * MT * 32; }
   int BN() const { return WN * NT * 32; }
-  int NTHR() const { return WM * WN * 64; }
+  int NTHR() const { return WM * WN * KS * 64; }
 };
 
 static const TileDesc kTileDescs[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV) {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV},
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS) \
+  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS},
 #include "variants.def"
 #undef X
 };
@@ -32,7 +33,7 @@ constexpr int kNumTiles = (int)(sizeof(kTileDescs) / sizeof(kTileDescs[0]));
 
 constexpr size_t kLdsLimitBytes = 160 * 1024;
 constexpr int kSmaxGeneric = 16;   // widest kernel the run-time generic tiles take
-constexpr int kLdsTrashWords = 16; // LDS words behind the staging buffers that absorb masked stores
+constexpr int kLdsTrashWords = 16; // LDS words (in front of the filter buffers, behind each input buffer) that absorb masked stores
 
 struct Plan {
   TconvParams p;
@@ -49,6 +50,10 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   if (!v.S && s.S > kSmaxGeneric) return false;
   if (v.AV == 4 && ((long long)s.C * s.R * s.S) % 4 != 0) return false;
   const long long i31 = (1LL << 31) - 1;
+  // the kernel addresses both inputs through 32-bit byte offsets below 2 GiB
+  const long long gbias = (long long)s.pad * s.W + s.pad;
+  if (((long long)s.N * s.C * s.H * s.W + gbias) * 4 > i31 || (long long)s.K * s.C * s.R * s.S * 4 > i31)
+    return false;
   if ((long long)s.N * s.C * s.H * s.W > i31 || (long long)s.K * s.C * s.R * s.S > i31 ||
       (long long)s.N * s.K * s.P * s.Q > i31)
     return false;
@@ -73,6 +78,7 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   p.out_elems = s.N * s.K * p.PQ;
   const int BN = v.BN(), BM = v.BM();
   long long total_rows = (long long)s.N * s.P;
+  p.gbias = s.pad * s.W + s.pad;
   p.compact = (s.S == 1 && s.stride == 1) ? 1 : 0;
   if (p.compact) {
     p.nrows = 1;
@@ -85,8 +91,9 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   }
   p.plane = p.nrows * p.rowst;
   if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR()) return false;
-  p.ast = (v.KR * s.S) | 1;
-  size_t lds = (size_t)(2 * BM * p.ast + 2 * v.KR * p.plane + kLdsTrashWords) * sizeof(float);
+  p.ast = a_row_stride(v.KR * s.S, a_read_width(v.KR, v.S, v.KS));
+  size_t lds = (size_t)(2 * BM * p.ast + 2 * (v.KR * p.plane + kLdsTrashWords) + kLdsTrashWords) * sizeof(float);
+  if (v.KS > 1 && lds < (size_t)BM * BN * sizeof(float)) lds = (size_t)BM * BN * sizeof(float);
   if (lds > kLdsLimitBytes) return false;
   p.nchunks = (p.CRrows + v.KR - 1) / v.KR;
   if (nsplit < 1 || nsplit > p.nchunks) return false;

@@ -33,11 +33,11 @@ static hipError_t launch_tile_kernel(KernelT kernel, int nthr, const TconvParams
   return e;
 }
 
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV)                                          \
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS)                                          \
   hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st) { \
     static size_t lds_allowed[64] = {0};                                                       \
-    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV>,          \
-                              WM * WN * 64, p, grid, lds_bytes, st, lds_allowed);                \
+    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS>,      \
+                              WM * WN * KS * 64, p, grid, lds_bytes, st, lds_allowed);                \
   }
 #include "variants.def"
 #undef X

@@ -11,17 +11,27 @@
 // A 1x1 layer (the paper's k1conv case) is the same kernel with R = S = 1, the
 // host having flattened each image to one row of H*W pixels.
 //
-// Reduction order inside a chunk of KR reduction rows kk = c*R + r: pairs of
-// rows (2j, 2j+1) feed the two k-slices of one MFMA (lanes 0-31 carry row 2j,
-// lanes 32-63 row 2j+1), kernel column s innermost.
+// Reduction order inside a chunk of KR reduction rows kk = c*R + r: row i of the
+// first half of the chunk and row KR/2 + i of the second half feed the two
+// k-slices of one MFMA (lanes 0-31 carry the first, lanes 32-63 the second),
+// kernel column s innermost.  With this pairing the filter words one lane needs
+// during a chunk are contiguous both in HBM and in LDS, so they are fetched with
+// 16-byte global loads, stored with 16-byte LDS writes and read back with
+// 16-byte LDS reads.
 //
-// Staging is software-pipelined by hand: while chunk i is consumed from one LDS
-// buffer, the global loads of chunk i+1 are issued between the MFMAs of the
-// first half of the chunk and their LDS stores (into the other buffer) between
-// the MFMAs of the second half, so that a single wave per SIMD keeps the matrix
-// pipe fed; one barrier per chunk.
+// The matrix pipe is the only unit with real work; what limits the kernel is the
+// number of other instructions a wave has to issue per MFMA.  Hence: buffer loads
+// whose out-of-range lanes return zero (no selects for padding and tails), wide
+// LDS accesses for the filter operand, tap offsets as immediates, (c, r) of a
+// reduction row resolved at compile time where the chunk holds whole channels,
+// and a hand-made software pipeline: while chunk i is consumed from one LDS
+// buffer, the global loads of chunk i+1 are issued between the MFMAs of the first
+// steps and their LDS stores (into the other buffer) between the MFMAs of the
+// last steps; one barrier per chunk.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "bconv_plan.h"
 
@@ -29,59 +39,84 @@ namespace bconv {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+template <int VW> struct VecOf;
+template <> struct VecOf<1> { typedef float type; };
+template <> struct VecOf<2> { typedef floatx2 type; };
+template <> struct VecOf<4> { typedef floatx4 type; };
 
 // R_/S_/STR_ > 0: compile-time kernel height / width / stride (tap offsets become
 // instruction immediates); 0: taken from the argument block at run time, with
 // S <= kSmaxGeneric.  AV = 4: filter rows are fetched with 16-byte loads (the host
-// guarantees CRS % 4 == 0, a 16-byte aligned filter pointer, and KR*S % 4 == 0
+// guarantees CRS % 4 == 0 and a 16-byte aligned filter pointer; KR*S % 4 == 0
 // holds by construction); AV = 1: 4-byte loads, no alignment demand.
-template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV>
-__global__ __launch_bounds__(WM * WN * 64)
+//
+// KS > 1 splits the reduction inside the workgroup: KS groups of WM*WN waves share
+// the staged tiles, group g consuming row pairs [g*NPAIR, (g+1)*NPAIR) of every
+// chunk, and their accumulators are summed through LDS before the epilogue.
+template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS>
+__global__ __launch_bounds__(WM * WN * KS * 64)
 void tconv_mfma_kernel(const TconvParams p) {
-  constexpr int NTHR = WM * WN * 64;
+  constexpr int NW = WM * WN;              // waves per reduction group
+  constexpr int NTHR = NW * KS * 64;
+  static_assert(KR % 2 == 0, "reduction rows are consumed in pairs");
+  static_assert((KR / 2) % KS == 0, "row pairs of a chunk must divide among the reduction groups");
+  constexpr int NPAIR = KR / 2 / KS;       // row pairs per chunk and group
   constexpr int BM = WM * MT * 32, BN = WN * NT * 32;
   constexpr int SP = S_ > 0 ? S_ : kSmaxGeneric;   // filter columns per reduction row (bound)
   constexpr int KRSP = KR * SP;
-  static_assert(KR % 2 == 0, "reduction rows are consumed in pairs");
   static_assert(AV == 1 || (AV == 4 && S_ > 0 && KRSP % 4 == 0), "vector filter loads need KR*S % 4 == 0");
   constexpr int AGRP = KRSP / AV;                      // load groups per filter row
   constexpr int NA = (BM * AGRP + NTHR - 1) / NTHR;    // filter load items per thread
   constexpr int NB = KR * EPT;                         // input load items per thread
   constexpr int NL = NA + NB;
+  constexpr int VW = a_read_width(KR, S_, KS);         // words per LDS read of the filter operand
+  constexpr int SW = (AV == 4) ? VW : 1;               // words per LDS store of the filter operand
+  constexpr bool WHOLE_CH = R_ > 0 && (KR % (R_ > 0 ? R_ : 1)) == 0;   // chunks hold whole channels
+  typedef typename VecOf<VW>::type avec_t;
+  typedef typename VecOf<SW>::type svec_t;
 
   const int R = R_ > 0 ? R_ : p.R;
   const int S = S_ > 0 ? S_ : p.S;
   const int STR = STR_ > 0 ? STR_ : p.stride;
   const int KRS = KR * S;            // valid filter words per row per chunk
-  const int ast = p.ast;
+  const int HALF = (KR / 2) * S;     // words of one half-chunk of a filter row
+  const int RUN = NPAIR * S;         // words of this group's run inside a half-chunk
+  const int ast = S_ > 0 ? a_row_stride(KR * (S_ > 0 ? S_ : 1), VW) : p.ast;
   const int plane = p.plane;
   const int phst = p.phst;
 
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int abuf = BM * ast;
-  const int bbuf = KR * plane;
-  float* const As = smem;               // [2][BM][ast]
-  float* const Bs = smem + 2 * abuf;    // [2][KR][nrows][rowst]
-  float* const trash = Bs + 2 * bbuf;   // kLdsTrashWords words nobody reads
+  const int bbuf = KR * plane + kLdsTrashWords;    // each input buffer ends in its own trash words
+  float* const trash = smem;                       // kLdsTrashWords words nobody reads
+  float* const As = smem + kLdsTrashWords;         // [2][BM][ast]
+  float* const Bs = As + 2 * abuf;                 // [2][KR][nrows][rowst] (+ trash)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;
+  const int kgrp = wave / NW;
+  const int wv = wave - kgrp * NW;
+  const int wm = wv / WN, wn = wv % WN;
   const int l32 = lane & 31, h = lane >> 5;
 
   const PixTile t = pix_tile(blockIdx.x, BN, p.NPQ, p.Q);
   const int m0 = blockIdx.y * BM;
 
   // ---- per-thread staging cells of the input tile (fixed for the whole loop)
-  int c_lds[EPT], c_goff[EPT], c_ih0[EPT];
+  int c_lds[EPT], c_pl[EPT], c_goff[EPT], c_ih0[EPT];
   const int ncell = p.nrows * p.rowst;
 #pragma unroll
   for (int i = 0; i < EPT; ++i) {
     int e = tid + i * NTHR;
     BCell c = b_cell(p, t, e < ncell ? e : 0, S, STR);
-    c_lds[i] = e < ncell ? c.lds : -1;
-    c_goff[i] = c.goff;
+    // LDS word offset from Bs of the cell in plane 0 and the plane stride to add per
+    // reduction row; a cell outside the tile writes to the trash words (stride 0)
+    c_lds[i] = e < ncell ? c.lds : KR * plane;
+    c_pl[i] = e < ncell ? plane : 0;
+    c_goff[i] = (c.goff + p.gbias) * 4;   // byte offset from the biased descriptor base
     c_ih0[i] = e < ncell ? c.ih0 : kNeverValid;
   }
 
@@ -90,11 +125,11 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     BLane bl = b_lane(p, t, (wn * NT + nt) * 32 + l32);
-    laneB[nt] = bl.ldsbase + h * plane;
+    laneB[nt] = bl.ldsbase + (h * (KR / 2) + kgrp * NPAIR) * plane;
     outoff[nt] = bl.outoff;
     colvalid[nt] = bl.valid;
   }
-  const int laneA = (wm * MT * 32 + l32) * ast + h * S;
+  const int laneA = (wm * MT * 32 + l32) * ast + h * HALF + kgrp * RUN;
 
   floatx16 acc[MT][NT];
 #pragma unroll
@@ -109,66 +144,104 @@ void tconv_mfma_kernel(const TconvParams p) {
   int ch_end = ch_begin + p.chunks_per_split;
   if (ch_end > p.nchunks) ch_end = p.nchunks;
 
-  float ra[NA * AV];
-  float rb[NB];
+  // two register sets: the words of chunk i+2 are in flight while those of chunk
+  // i+1 are being stored to LDS and chunk i is consumed
+  float ra[2][NA * AV];
+  float rb[2][NB];
+
+  // Global loads go through raw buffer descriptors: a load whose offset is out of
+  // range returns 0, so zero padding, ragged tails and masked lanes need no select
+  // after the load (the loaded registers are not touched until they are stored to
+  // LDS, which keeps the memory latency off the wave's critical path).  The input
+  // descriptor starts gbias words before the tensor so that cell offsets, which may
+  // point above the first image row, are never negative.
+  constexpr unsigned kOob = 0x80000000u;
+  const __amdgpu_buffer_rsrc_t rsrc_in = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(p.in) - p.gbias, 0, (p.N * p.CHW + p.gbias) * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_filt = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(p.filt), 0, p.K * p.CRS * 4, 0x00020000);
+
+  // (c, r) of reduction row kl of chunk ch: compile-time r when a chunk holds
+  // whole channels, one conditional wrap when a chunk is shorter than a channel.
+  auto row_cr = [&](int ch, int kl, int c0, int r0, int& c, int& r) {
+    if constexpr (WHOLE_CH) {
+      c = ch * (KR / (R_ > 0 ? R_ : 1)) + kl / (R_ > 0 ? R_ : 1);
+      r = kl % (R_ > 0 ? R_ : 1);
+    } else if constexpr (R_ > 0 && KR <= R_) {
+      const bool wrap = (r0 + kl) >= R_;
+      c = c0 + (wrap ? 1 : 0);
+      r = r0 + kl - (wrap ? R_ : 0);
+    } else {
+      const int kk = ch * KR + kl;
+      c = kk / R;
+      r = kk - c * R;
+    }
+  };
 
   // Load item q of chunk ch: q < NA is a group of AV filter words, otherwise the
   // input cell (kl, i) = ((q - NA) / EPT, (q - NA) % EPT).
-  auto load_item = [&](int ch, int q) {
+  auto load_item = [&](auto set_tag, int ch, int q, int c0, int r0) {
+    constexpr int SET = decltype(set_tag)::value;
+    const bool chok = ch < ch_end;      // chunks past this workgroup's range load zeros
     const int kk0 = ch * KR;
     if (q < NA) {
       const int col0 = kk0 * S;
       const int e = tid + q * NTHR;
       const int m = e / AGRP;
       const int j = (e - m * AGRP) * AV;
-      const bool ok = (m < BM) && (j < KRS) && (m0 + m < p.K) && (col0 + j < p.CRS);
-      const float* src = p.filt + (ok ? (m0 + m) * p.CRS + col0 + j : 0);   // word 0 always exists
+      // (q + 1) * NTHR <= BM * AGRP folds to true for all but a ragged last item
+      const bool inside = ((q + 1) * NTHR <= BM * AGRP) || (m < BM);
+      const bool ok = chok && inside && (S_ > 0 || j < KRS) && (m0 + m < p.K) && (col0 + j < p.CRS);
+      const unsigned voff = ok ? (unsigned)(((m0 + m) * p.CRS + j) * 4) : kOob;
       if constexpr (AV == 4) {
-        floatx4 v = *reinterpret_cast<const floatx4*>(src);
+        floatx4 v = __builtin_bit_cast(
+            floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_filt, voff, col0 * 4, 0));
 #pragma unroll
-        for (int u = 0; u < 4; ++u) ra[q * 4 + u] = ok ? v[u] : 0.0f;
+        for (int u = 0; u < 4; ++u) ra[SET][q * 4 + u] = v[u];
       } else {
-        float v = *src;
-        ra[q] = ok ? v : 0.0f;
+        ra[SET][q] = __builtin_bit_cast(float,
+                                   __builtin_amdgcn_raw_buffer_load_b32(rsrc_filt, voff, col0 * 4, 0));
       }
     } else {
       const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
-      const int kk = kk0 + kl;
-      const int c = kk / R;
-      const int r = kk - c * R;
-      const bool ok = (kk < p.CRrows) && ((unsigned)(c_ih0[i] + r) < (unsigned)p.H);
-      float v = p.in[ok ? c_goff[i] + c * p.HW + r * p.W : 0];
-      rb[q - NA] = ok ? v : 0.0f;
+      int c, r;
+      row_cr(ch, kl, c0, r0, c, r);
+      const bool ok = chok && (kk0 + kl < p.CRrows) && ((unsigned)(c_ih0[i] + r) < (unsigned)p.H);
+      const unsigned voff = ok ? (unsigned)c_goff[i] : kOob;
+      rb[SET][q - NA] = __builtin_bit_cast(
+          float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, voff, (c * p.HW + r * p.W) * 4, 0));
     }
   };
 
-  auto store_item = [&](int buf, int q) {
+  auto store_item = [&](auto set_tag, int buf, int q) {
+    constexpr int SET = decltype(set_tag)::value;
     if (q < NA) {
       float* A = As + buf * abuf;
       const int e = tid + q * NTHR;
       const int m = e / AGRP;
       const int j = (e - m * AGRP) * AV;
-      // words outside the tile go to the trash words behind the buffers, so that
-      // the store needs no branch
-      const bool ok = (m < BM) && (j < KRS);
+      // words outside the tile go to the trash words in front of the buffers, so
+      // that the store needs no branch
+      const bool ok = (((q + 1) * NTHR <= BM * AGRP) || (m < BM)) && (S_ > 0 || j < KRS);
       float* dst = ok ? A + m * ast + j : trash;
 #pragma unroll
-      for (int u = 0; u < AV; ++u) dst[u] = ra[q * AV + u];
+      for (int u = 0; u < AV; u += SW) {
+        svec_t v;
+        if constexpr (SW == 1) {
+          v = ra[SET][q * AV + u];
+        } else {
+#pragma unroll
+          for (int w = 0; w < SW; ++w) v[w] = ra[SET][q * AV + u + w];
+        }
+        *reinterpret_cast<svec_t*>(dst + u) = v;
+      }
     } else {
       float* B = Bs + buf * bbuf;
       const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
-      float* dst = c_lds[i] >= 0 ? B + kl * plane + c_lds[i] : trash;
-      *dst = rb[q - NA];
+      B[kl * c_pl[i] + c_lds[i]] = rb[SET][q - NA];
     }
   };
 
-  auto read_operands = [&](const float* A, const float* B, int aoff, int boff, float (&a)[MT],
-                           float (&b)[NT]) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) a[mt] = A[laneA + mt * 32 * ast + aoff];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) b[nt] = B[laneB[nt] + boff];
-  };
   auto mfma_tile = [&](const float (&a)[MT], const float (&b)[NT]) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -177,73 +250,138 @@ void tconv_mfma_kernel(const TconvParams p) {
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
   };
 
-  // Consumes LDS buffer `buf`; with STAGE also fetches chunk `next` into buf ^ 1.
-  auto compute_chunk = [&](int buf, int next, auto stage_tag) {
-    constexpr bool STAGE = decltype(stage_tag)::value;
-    const float* A = As + buf * abuf;
-    const float* B = Bs + buf * bbuf;
+  // One pipeline stage: consumes chunk ch from LDS buffer P; between its MFMAs the
+  // global loads of chunk ch + 2 are issued into register set P and register set
+  // 1 - P (chunk ch + 1, loaded during the previous stage) is stored to LDS buffer
+  // 1 - P.  Staging work is spread evenly over the steps and needs no conditions:
+  // chunks past the end load zeros and are stored to a buffer nobody reads.
+  auto stage = [&](auto par_tag, int ch) {
+    constexpr int P = decltype(par_tag)::value;
+    typedef std::integral_constant<int, P> SetLoad;
+    typedef std::integral_constant<int, 1 - P> SetStore;
+    const float* A = As + P * abuf;
+    const float* B = Bs + P * bbuf;
+    const int next = ch + 2;
+    int c0 = 0, r0 = 0;
+    if constexpr (!WHOLE_CH) {
+      c0 = (next * KR) / R;
+      r0 = next * KR - c0 * R;
+    }
     if constexpr (S_ > 0 && STR_ > 0) {
-      constexpr int NSTEPS = (KR / 2) * S_;
-      constexpr int LSTEPS = NSTEPS > 1 ? (NSTEPS + 1) / 2 : 1;   // loads issued in steps [0, LSTEPS)
-      constexpr int SSTEPS = NSTEPS - LSTEPS;                     // stores in steps [LSTEPS, NSTEPS)
-      // operands of step st+1 are read from LDS before the MFMAs of step st issue
-      float a[2][MT], b[2][NT];
-      read_operands(A, B, 0, 0, a[0], b[0]);
+      constexpr int NSTEPS = NPAIR * (S_ > 0 ? S_ : 1);
+      // this lane's filter words of the whole chunk, read with wide LDS loads
+      float areg[MT][NSTEPS];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int w = 0; w < NSTEPS; w += VW) {
+          avec_t v = *reinterpret_cast<const avec_t*>(A + laneA + mt * 32 * ast + w);
+          if constexpr (VW == 1) {
+            areg[mt][w] = v;
+          } else {
+#pragma unroll
+            for (int u = 0; u < VW; ++u) areg[mt][w + u] = v[u];
+          }
+        }
+      // input operands of step st+1 are read from LDS before the MFMAs of step st issue
+      float b[2][NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) b[0][nt] = B[laneB[nt]];
 #pragma unroll
       for (int st = 0; st < NSTEPS; ++st) {
         if (st + 1 < NSTEPS) {
-          const int j = (st + 1) / S_, s = (st + 1) % S_;
-          read_operands(A, B, 2 * j * S_ + s, 2 * j * plane + (s % STR_) * phst + s / STR_,
-                        a[(st + 1) & 1], b[(st + 1) & 1]);
-        }
-        mfma_tile(a[st & 1], b[st & 1]);
-        if constexpr (STAGE) {
+          const int i = (st + 1) / (S_ > 0 ? S_ : 1), s = (st + 1) % (S_ > 0 ? S_ : 1);
 #pragma unroll
-          for (int q = 0; q < NL; ++q) {
-            if (q * LSTEPS / NL == st) load_item(next, q);
-            if (SSTEPS > 0 && LSTEPS + q * SSTEPS / NL == st) store_item(buf ^ 1, q);
+          for (int nt = 0; nt < NT; ++nt)
+            b[(st + 1) & 1][nt] =
+                B[laneB[nt] + i * plane + (s % (STR_ > 0 ? STR_ : 1)) * phst + s / (STR_ > 0 ? STR_ : 1)];
+        }
+        float a[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a[mt] = areg[mt][st];
+        mfma_tile(a, b[st & 1]);
+#pragma unroll
+        for (int q = 0; q < NL; ++q) {
+          if (q * NSTEPS / NL == st) {
+            load_item(SetLoad{}, next, q, c0, r0);
+            store_item(SetStore{}, 1 - P, q);
           }
         }
-      }
-      if constexpr (STAGE && SSTEPS == 0) {
-#pragma unroll
-        for (int q = 0; q < NL; ++q) store_item(buf ^ 1, q);
+        // keep the compiler from regrouping the staging work of different steps
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
-      if constexpr (STAGE) {
 #pragma unroll
-        for (int q = 0; q < NL; ++q) load_item(next, q);
-      }
-      for (int j = 0; j < KR / 2; ++j) {
+      for (int q = 0; q < NL; ++q) load_item(SetLoad{}, next, q, c0, r0);
+      for (int i = 0; i < NPAIR; ++i) {
         int ph = 0, xq = 0;
         for (int s = 0; s < S; ++s) {
           float a[MT], b[NT];
-          read_operands(A, B, 2 * j * S + s, 2 * j * plane + ph * phst + xq, a, b);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) a[mt] = A[laneA + mt * 32 * ast + i * S + s];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) b[nt] = B[laneB[nt] + i * plane + ph * phst + xq];
           mfma_tile(a, b);
           if (++ph == STR) { ph = 0; ++xq; }
         }
       }
-      if constexpr (STAGE) {
 #pragma unroll
-        for (int q = 0; q < NL; ++q) store_item(buf ^ 1, q);
-      }
+      for (int q = 0; q < NL; ++q) store_item(SetStore{}, 1 - P, q);
     }
   };
 
-  if (ch_begin < ch_end) {
+  typedef std::integral_constant<int, 0> Zero;
+  typedef std::integral_constant<int, 1> One;
+  {
+    // prologue: chunk 0 through registers into buffer 0, chunk 1 into register set 1
+    int c0 = (ch_begin * KR) / R;
+    int r0 = ch_begin * KR - c0 * R;
 #pragma unroll
-    for (int q = 0; q < NL; ++q) load_item(ch_begin, q);
+    for (int q = 0; q < NL; ++q) load_item(Zero{}, ch_begin, q, c0, r0);
+    c0 = ((ch_begin + 1) * KR) / R;
+    r0 = (ch_begin + 1) * KR - c0 * R;
 #pragma unroll
-    for (int q = 0; q < NL; ++q) store_item(0, q);
+    for (int q = 0; q < NL; ++q) load_item(One{}, ch_begin + 1, q, c0, r0);
+#pragma unroll
+    for (int q = 0; q < NL; ++q) store_item(Zero{}, 0, q);
   }
   __syncthreads();
-  int buf = 0;
-  for (int ch = ch_begin; ch + 1 < ch_end; ++ch) {
-    compute_chunk(buf, ch + 1, std::true_type{});
+  for (int ch = ch_begin; ch < ch_end; ch += 2) {
+    stage(Zero{}, ch);
     __syncthreads();
-    buf ^= 1;
+    if (ch + 1 < ch_end) {
+      stage(One{}, ch + 1);
+      __syncthreads();
+    }
   }
-  if (ch_begin < ch_end) compute_chunk(buf, 0, std::false_type{});
+
+  // ---- sum the reduction groups' accumulators through LDS (staging buffers are free now)
+  if constexpr (KS > 1) {
+    float* const red = smem;
+    for (int g = 1; g < KS; ++g) {
+      __syncthreads();
+      if (kgrp == g) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              red[(((wv * MT + mt) * NT + nt) * 16 + i) * 64 + lane] = acc[mt][nt][i];
+      }
+      __syncthreads();
+      if (kgrp == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              acc[mt][nt][i] += red[(((wv * MT + mt) * NT + nt) * 16 + i) * 64 + lane];
+      }
+    }
+    if (kgrp != 0) return;
+  }
 
   // ---- epilogue: bias + optional ReLU + store (or raw partial sums for split-K)
   const bool split = p.nsplit > 1;

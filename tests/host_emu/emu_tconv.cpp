@@ -51,7 +51,7 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
   const int NA = (BM * AGRP + NTHR - 1) / NTHR;
   const long long in_elems = (long long)p.N * p.CHW, filt_elems = (long long)p.K * p.CRS;
   const int abuf = BM * p.ast, bbuf = KR * p.plane;
-  if ((size_t)(2 * abuf + 2 * bbuf + kLdsTrashWords) * 4 != pl.lds_bytes) return 2;
+  if ((size_t)(2 * abuf + 2 * (bbuf + kLdsTrashWords) + kLdsTrashWords) * 4 > pl.lds_bytes) return 2;
   Oob oob;
   const float nanv = std::numeric_limits<float>::quiet_NaN();
   std::vector<float> partial((size_t)p.nsplit * p.out_elems, nanv);
@@ -64,7 +64,8 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
     const PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
     const int m0 = (int)by * BM;
     // accumulators per wave tile as plain matrices [BM][BN]
-    std::vector<float> acc((size_t)BM * BN, 0.0f);
+    const int KS = v.KS, NW = v.WM * v.WN;
+    std::vector<float> acc((size_t)KS * BM * BN, 0.0f);   // one accumulator set per reduction group
     const int ch_begin = (int)bz * p.chunks_per_split;
     int ch_end = ch_begin + p.chunks_per_split;
     if (ch_end > p.nchunks) ch_end = p.nchunks;
@@ -109,20 +110,23 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
         }
       }
       // compute: every wave, every (j, s) step
-      for (int wave = 0; wave < v.WM * v.WN; ++wave) {
-        const int wm = wave / v.WN, wn = wave % v.WN;
-        for (int j = 0; j < KR / 2; ++j)
+      for (int wave = 0; wave < NW * KS; ++wave) {
+        const int kgrp = wave / NW, wv = wave % NW;
+        const int wm = wv / v.WN, wn = wv % v.WN;
+        float* accg = acc.data() + (size_t)kgrp * BM * BN;
+        const int NPAIR = KR / 2 / KS, HALF = (KR / 2) * Sk, RUN = NPAIR * Sk;
+        for (int j = 0; j < NPAIR; ++j)
         for (int s = 0; s < Sk; ++s) {
-          const int aoff = 2 * j * Sk + s;
-          const int boff = 2 * j * p.plane + tap_off(s, STR, p.phst);
+          const int aoff = j * Sk + s;
+          const int boff = j * p.plane + tap_off(s, STR, p.phst);
           for (int mt = 0; mt < v.MT; ++mt)
           for (int nt = 0; nt < v.NT; ++nt) {
             float a[64], b[64];
             for (int lane = 0; lane < 64; ++lane) {
               const int l32 = lane & 31, h = lane >> 5;
-              const int laneA = (wm * v.MT * 32 + l32) * p.ast + h * Sk;
+              const int laneA = (wm * v.MT * 32 + l32) * p.ast + h * HALF + kgrp * RUN;
               BLane bl = b_lane(p, t, (wn * v.NT + nt) * 32 + l32);
-              const int laneB = bl.ldsbase + h * p.plane;
+              const int laneB = bl.ldsbase + (h * (KR / 2) + kgrp * NPAIR) * p.plane;
               long long ai = (long long)laneA + mt * 32 * p.ast + aoff;
               long long bi = (long long)laneB + boff;
               if (ai < 0 || ai >= abuf) { oob.hit("A read", ai, abuf); a[lane] = 0; } else a[lane] = As[ai];
@@ -130,14 +134,18 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
             }
             for (int i = 0; i < 32; ++i)
               for (int jn = 0; jn < 32; ++jn) {
-                float d = acc[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn];
+                float d = accg[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn];
                 for (int k = 0; k < 2; ++k) d = std::fmaf(a[k * 32 + i], b[k * 32 + jn], d);
-                acc[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn] = d;
+                accg[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn] = d;
               }
           }
         }
       }
     }
+    // reduction groups summed in group order, as the kernel does through LDS
+    if ((size_t)BM * BN * 4 > pl.lds_bytes && KS > 1) oob.hit("reduction scratch", (long long)BM * BN * 4, (long long)pl.lds_bytes);
+    for (int g = 1; g < KS; ++g)
+      for (size_t i = 0; i < (size_t)BM * BN; ++i) acc[i] += acc[(size_t)g * BM * BN + i];
     // epilogue through the lane/register map
     for (int wave = 0; wave < v.WM * v.WN; ++wave) {
       const int wm = wave / v.WN, wn = wave % v.WN;

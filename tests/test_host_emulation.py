@@ -74,10 +74,15 @@ CASES = [
     ("k5_128x64_k8_v4", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
     ("k5_256x128_k8", 1, 3, 27, 27, 260, 5, 5, 1, 2, 1),
     ("pw_64x256_k16_v4", 2, 20, 14, 14, 70, 1, 1, 1, 0, 1),
-    ("pw_128x256_k32_v4", 3, 68, 7, 7, 130, 1, 1, 1, 0, 2),
+    ("pw_64x256_k32_v4", 3, 68, 7, 7, 130, 1, 1, 1, 0, 2),
     ("pw_64x128_k16", 2, 6, 5, 9, 40, 1, 1, 1, 1, 1),           # pointwise with padding
     ("k11s4_96x256_k4", 2, 3, 67, 71, 96, 11, 11, 4, 0, 1),
     ("k11s4_32x128_k2", 1, 3, 51, 47, 10, 11, 11, 4, 2, 2),
+    ("k3_128x64_k12_s3_v4", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),   # reduction split inside the workgroup
+    ("k3_64x64_k12_s2", 2, 7, 13, 13, 40, 3, 3, 1, 1, 2),
+    ("k5_128x64_k20_s2_v4", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
+    ("pw_128x128_k32_s4_v4", 2, 68, 14, 14, 130, 1, 1, 1, 0, 1),
+    ("k11s4_96x128_k6_s3", 1, 3, 67, 71, 96, 11, 11, 4, 0, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 2, 4, 2, 1, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 3, 1, 1, 1, 1),            # S = 1, stride 1, R = 3: compact cells
     ("gen_64x64_k2", 1, 2, 12, 12, 5, 3, 3, 3, 2, 2),
