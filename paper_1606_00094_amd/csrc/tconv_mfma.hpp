@@ -156,6 +156,11 @@ void tconv_mfma_kernel(const TconvParams p) {
   // descriptor starts gbias words before the tensor so that cell offsets, which may
   // point above the first image row, are never negative.
   constexpr unsigned kOob = 0x80000000u;
+  // sc0 | sc1: the loads are served by L2.  Every word is fetched once per workgroup
+  // and goes straight to LDS, so the vector L1 has nothing to reuse, and its in-order
+  // handling of requests that hit a line still in flight (neighbouring kernel rows of
+  // one channel, filter rows that straddle lines) only stalls the other loads.
+  constexpr int kLoadPolicy = 17;
   const __amdgpu_buffer_rsrc_t rsrc_in = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(p.in) - p.gbias, 0, (p.N * p.CHW + p.gbias) * 4, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_filt = __builtin_amdgcn_make_buffer_rsrc(
@@ -195,12 +200,12 @@ void tconv_mfma_kernel(const TconvParams p) {
       const unsigned voff = ok ? (unsigned)(((m0 + m) * p.CRS + j) * 4) : kOob;
       if constexpr (AV == 4) {
         floatx4 v = __builtin_bit_cast(
-            floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_filt, voff, col0 * 4, 0));
+            floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_filt, voff, col0 * 4, kLoadPolicy));
 #pragma unroll
         for (int u = 0; u < 4; ++u) ra[SET][q * 4 + u] = v[u];
       } else {
         ra[SET][q] = __builtin_bit_cast(float,
-                                   __builtin_amdgcn_raw_buffer_load_b32(rsrc_filt, voff, col0 * 4, 0));
+                                   __builtin_amdgcn_raw_buffer_load_b32(rsrc_filt, voff, col0 * 4, kLoadPolicy));
       }
     } else {
       const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
@@ -209,7 +214,7 @@ void tconv_mfma_kernel(const TconvParams p) {
       const bool ok = chok && (kk0 + kl < p.CRrows) && ((unsigned)(c_ih0[i] + r) < (unsigned)p.H);
       const unsigned voff = ok ? (unsigned)c_goff[i] : kOob;
       rb[SET][q - NA] = __builtin_bit_cast(
-          float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, voff, (c * p.HW + r * p.W) * 4, 0));
+          float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
     }
   };
 
@@ -269,20 +274,23 @@ void tconv_mfma_kernel(const TconvParams p) {
     }
     if constexpr (S_ > 0 && STR_ > 0) {
       constexpr int NSTEPS = NPAIR * (S_ > 0 ? S_ : 1);
-      // this lane's filter words of the whole chunk, read with wide LDS loads
-      float areg[MT][NSTEPS];
+      constexpr int LSTEPS = NSTEPS > 1 ? NSTEPS / 2 : 0;   // steps that issue global loads
+      // this lane's filter words are read VW at a time, one read ahead of their use
+      constexpr int NGRP = (NSTEPS + VW - 1) / VW;
+      float areg[2][MT][VW];
+      auto read_a = [&](int g, float (&dst)[MT][VW]) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int w = 0; w < NSTEPS; w += VW) {
-          avec_t v = *reinterpret_cast<const avec_t*>(A + laneA + mt * 32 * ast + w);
+        for (int mt = 0; mt < MT; ++mt) {
+          avec_t v = *reinterpret_cast<const avec_t*>(A + laneA + mt * 32 * ast + g * VW);
           if constexpr (VW == 1) {
-            areg[mt][w] = v;
+            dst[mt][0] = v;
           } else {
 #pragma unroll
-            for (int u = 0; u < VW; ++u) areg[mt][w + u] = v[u];
+            for (int u = 0; u < VW; ++u) dst[mt][u] = v[u];
           }
         }
+      };
+      read_a(0, areg[0]);
       // input operands of step st+1 are read from LDS before the MFMAs of step st issue
       float b[2][NT];
 #pragma unroll
@@ -296,16 +304,19 @@ void tconv_mfma_kernel(const TconvParams p) {
             b[(st + 1) & 1][nt] =
                 B[laneB[nt] + i * plane + (s % (STR_ > 0 ? STR_ : 1)) * phst + s / (STR_ > 0 ? STR_ : 1)];
         }
+        if (st % VW == 0 && st / VW + 1 < NGRP) read_a(st / VW + 1, areg[(st / VW + 1) & 1]);
         float a[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) a[mt] = areg[mt][st];
+        for (int mt = 0; mt < MT; ++mt) a[mt] = areg[(st / VW) & 1][mt][st % VW];
         mfma_tile(a, b[st & 1]);
+        // loads in the first half of the steps, stores in the second half: the
+        // memory counter retires loads in order, so a store waits for every load
+        // issued before it except this stage's own; this way those are a full
+        // chunk old
 #pragma unroll
         for (int q = 0; q < NL; ++q) {
-          if (q * NSTEPS / NL == st) {
-            load_item(SetLoad{}, next, q, c0, r0);
-            store_item(SetStore{}, 1 - P, q);
-          }
+          if (q * LSTEPS / NL == st) load_item(SetLoad{}, next, q, c0, r0);
+          if (LSTEPS + q * (NSTEPS - LSTEPS) / NL == st) store_item(SetStore{}, 1 - P, q);
         }
         // keep the compiler from regrouping the staging work of different steps
         __builtin_amdgcn_sched_barrier(0);
