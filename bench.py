@@ -43,7 +43,7 @@ class LayerProblem:
         self.bytes = roofline.conv_bytes(*self.dims)
         self.variant = binding.conv_selected_variant(*self.dims)
         need = binding.conv_fwd_workspace_bytes(*self.dims, self.variant)
-        self.ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        self.ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
         xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
         self.sets = []
         for c in range(copies):
@@ -104,7 +104,7 @@ def run_stack(N, reps):
         P, Q = binding.conv_out_dims(h, w, layer.R, layer.S, layer.stride, layer.pad)
         v = binding.conv_selected_variant(*dims)
         need = binding.conv_fwd_workspace_bytes(*dims, v)
-        ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
         out = torch.empty((n, layer.K, P, Q), dtype=torch.float32, device=dev)
         plan.append(("conv", len(bufs) - 1, len(bufs), torch.from_numpy(f).to(dev),
                      torch.from_numpy(b).to(dev), layer, ws, v))

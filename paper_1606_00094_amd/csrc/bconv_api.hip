@@ -14,7 +14,7 @@ namespace bconv {
 
 // ------------------------------------------------------------------ catalogue
 static const TileLaunchFn kLaunch[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS) launch_##name,
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV) launch_##name,
 #include "variants.def"
 #undef X
 };
@@ -89,7 +89,7 @@ static double model_cost(const TileDesc& v, const Plan& pl) {
   return t;
 }
 
-static int select_variant(const Shape& s, bool filt_aligned16 = true) {
+static int select_variant(const Shape& s, bool filt_aligned16 = true, bool in_aligned16 = true) {
   for (const TableRow* r = kTable; r->tile; ++r) {
     if (r->N == s.N && r->C == s.C && r->H == s.H && r->W == s.W && r->K == s.K && r->R == s.R &&
         r->S == s.S && r->stride == s.stride && r->pad == s.pad) {
@@ -97,6 +97,7 @@ static int select_variant(const Shape& s, bool filt_aligned16 = true) {
       int t, ns;
       Plan pl;
       if (id > 0 && decode_variant(id, &t, &ns) && (filt_aligned16 || kTiles[t].AV == 1) &&
+          (in_aligned16 || kTiles[t].BV == 1) &&
           plan_tconv(s, kTiles[t], ns, &pl))
         return id;
     }
@@ -105,6 +106,7 @@ static int select_variant(const Shape& s, bool filt_aligned16 = true) {
   double best_cost = 0.0;
   for (int t = 0; t < kNumTiles; ++t) {
     if (!filt_aligned16 && kTiles[t].AV != 1) continue;
+    if (!in_aligned16 && kTiles[t].BV != 1) continue;
     for (int i = 0; i < kNumSplits; ++i) {
       Plan pl;
       if (!plan_tconv(s, kTiles[t], kSplits[i], &pl)) continue;
@@ -157,7 +159,8 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
                     const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
                     hipStream_t st, int variant_id) {
   const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & 15u) == 0;
-  if (variant_id < 0) variant_id = select_variant(s, aligned16);
+  const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
+  if (variant_id < 0) variant_id = select_variant(s, aligned16, in_aligned16);
   if (variant_id == 0) {
     return launch_direct_conv(in, filt, bias, out, s, relu, st) == hipSuccess ? BCONV_OK
                                                                               : BCONV_ELAUNCH;
@@ -167,6 +170,7 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
   Plan pl;
   if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
   if (kTiles[t].AV == 4 && !aligned16) return BCONV_EVARIANT;
+  if (kTiles[t].BV == 4 && !in_aligned16) return BCONV_EVARIANT;
   if (pl.ws_bytes) {
     if (own_ws) {
       int rc = internal_workspace(pl.ws_bytes, &ws);
@@ -206,7 +210,7 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
     if (!p.compact && t.rho1 - t.rho0 + 1 > p.nrows) ++bad;
     // staged cells: each LDS word of a plane is written by exactly one cell
     for (int e = 0; e < v.EPT * NTHR; ++e) {
-      if (e >= ncell) continue;
+      if (e * p.bv >= ncell) continue;
       BCell c = b_cell(p, t, e, p.S, p.stride);
       if (c.lds < 0 || c.lds >= p.plane) ++bad;
       if (c.ih0 == kNeverValid) continue;

@@ -40,7 +40,8 @@ struct TconvParams {
   int relu;
   int PQ, NPQ, HW, CHW, CRS, CRrows;   // CRrows = C*R reduction rows
   int nrows, phst, rowst, plane;       // staged-input geometry, plane = nrows*rowst
-  int compact;                         // S == 1 and stride == 1: one staged cell per tile pixel
+  int compact;                         // S == 1 and stride == 1: one staged cell per bv tile pixels
+  int bv;                              // pixels per staged cell in compact mode (1 or 4)
   int gbias;                           // pad*W + pad: most negative cell offset, see the kernel's loads
   int ast;                             // LDS stride between filter rows (odd)
   int nchunks, chunks_per_split, nsplit;
@@ -92,9 +93,11 @@ struct BCell {
 BCONV_HD BCell b_cell(const TconvParams& p, const PixTile& t, int e, int S, int STR) {
   BCell c;
   if (p.compact) {
-    // kernel width 1 at stride 1: cell e is the input word under tile pixel e
-    bool ok = e < t.cnt;
-    int g = t.g0 + (ok ? e : 0);
+    // kernel width 1 at stride 1: cell e covers the input words under tile pixels
+    // bv*e .. bv*e + bv - 1 (bv = 4 only where a cell never straddles an image row)
+    int col = e * p.bv;
+    bool ok = col < t.cnt;
+    int g = t.g0 + (ok ? col : 0);
     int rho = g / p.Q;
     int q = g - rho * p.Q;
     int img = rho / p.P;
@@ -102,7 +105,7 @@ BCONV_HD BCell b_cell(const TconvParams& p, const PixTile& t, int e, int S, int 
     int iw = q - p.pad;
     ok = ok && (iw >= 0) && (iw < p.W);
     int ih0 = pp - p.pad;
-    c.lds = e;
+    c.lds = col;
     c.goff = img * p.CHW + ih0 * p.W + iw;
     c.ih0 = ok ? ih0 : kNeverValid;
     return c;

@@ -17,15 +17,15 @@ struct Shape {
 struct TileDesc {
   const char* name;
   int R, S, STR;            // 0 = run-time value
-  int WM, WN, MT, NT, KR, EPT, AV, KS;
+  int WM, WN, MT, NT, KR, EPT, AV, KS, BV;
   int BM() const { return WM * MT * 32; }
   int BN() const { return WN * NT * 32; }
   int NTHR() const { return WM * WN * KS * 64; }
 };
 
 static const TileDesc kTileDescs[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS) \
-  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS},
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV) \
+  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV},
 #include "variants.def"
 #undef X
 };
@@ -59,12 +59,16 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
     return false;
   // A pointwise layer reads each image as one long row (per-image im2col is the
   // identity, paper Section VI k1conv).
-  if (s.R == 1 && s.S == 1 && s.stride == 1 && s.pad == 0) {
+  const bool flat = (s.R == 1 && s.S == 1 && s.stride == 1 && s.pad == 0);
+  if (flat) {
     s.W = s.H * s.W;
     s.H = 1;
     s.Q = s.P * s.Q;
     s.P = 1;
   }
+  // 16-byte input loads: only for flattened pointwise layers whose images are a
+  // multiple of four pixels long, so that no group of four pixels straddles images
+  if (v.BV == 4 && !(flat && s.W % 4 == 0)) return false;
   TconvParams& p = pl->p;
   std::memset(&p, 0, sizeof(p));
   p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.R = s.R; p.S = s.S;
@@ -80,6 +84,7 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   long long total_rows = (long long)s.N * s.P;
   p.gbias = s.pad * s.W + s.pad;
   p.compact = (s.S == 1 && s.stride == 1) ? 1 : 0;
+  p.bv = p.compact ? v.BV : 1;
   if (p.compact) {
     p.nrows = 1;
     p.phst = BN;
@@ -90,7 +95,7 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
     p.rowst = s.stride * p.phst;
   }
   p.plane = p.nrows * p.rowst;
-  if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR()) return false;
+  if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR() * p.bv) return false;
   p.ast = a_row_stride(v.KR * s.S, a_read_width(v.KR, v.S, v.KS));
   size_t lds = (size_t)(2 * BM * p.ast + 2 * (v.KR * p.plane + kLdsTrashWords) + kLdsTrashWords) * sizeof(float);
   if (v.KS > 1 && lds < (size_t)BM * BN * sizeof(float)) lds = (size_t)BM * BN * sizeof(float);

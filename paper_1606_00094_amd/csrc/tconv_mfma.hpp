@@ -55,7 +55,7 @@ template <> struct VecOf<4> { typedef floatx4 type; };
 // KS > 1 splits the reduction inside the workgroup: KS groups of WM*WN waves share
 // the staged tiles, group g consuming row pairs [g*NPAIR, (g+1)*NPAIR) of every
 // chunk, and their accumulators are summed through LDS before the epilogue.
-template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS>
+template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV>
 __global__ __launch_bounds__(WM * WN * KS * 64)
 void tconv_mfma_kernel(const TconvParams p) {
   constexpr int NW = WM * WN;              // waves per reduction group
@@ -69,7 +69,8 @@ void tconv_mfma_kernel(const TconvParams p) {
   static_assert(AV == 1 || (AV == 4 && S_ > 0 && KRSP % 4 == 0), "vector filter loads need KR*S % 4 == 0");
   constexpr int AGRP = KRSP / AV;                      // load groups per filter row
   constexpr int NA = (BM * AGRP + NTHR - 1) / NTHR;    // filter load items per thread
-  constexpr int NB = KR * EPT;                         // input load items per thread
+  static_assert(BV == 1 || (BV == 4 && S_ == 1 && STR_ == 1), "16-byte input loads are for pointwise tiles");
+  constexpr int NB = KR * EPT;                         // input load items per thread (BV words each)
   constexpr int NL = NA + NB;
   constexpr int VW = a_read_width(KR, S_, KS);         // words per LDS read of the filter operand
   constexpr int SW = (AV == 4) ? VW : 1;               // words per LDS store of the filter operand
@@ -111,13 +112,14 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
   for (int i = 0; i < EPT; ++i) {
     int e = tid + i * NTHR;
-    BCell c = b_cell(p, t, e < ncell ? e : 0, S, STR);
+    const bool in_tile = e * BV < ncell;
+    BCell c = b_cell(p, t, in_tile ? e : 0, S, STR);
     // LDS word offset from Bs of the cell in plane 0 and the plane stride to add per
     // reduction row; a cell outside the tile writes to the trash words (stride 0)
-    c_lds[i] = e < ncell ? c.lds : KR * plane;
-    c_pl[i] = e < ncell ? plane : 0;
+    c_lds[i] = in_tile ? c.lds : KR * plane;
+    c_pl[i] = in_tile ? plane : 0;
     c_goff[i] = (c.goff + p.gbias) * 4;   // byte offset from the biased descriptor base
-    c_ih0[i] = e < ncell ? c.ih0 : kNeverValid;
+    c_ih0[i] = in_tile ? c.ih0 : kNeverValid;
   }
 
   // ---- per-lane operand bases
@@ -147,7 +149,7 @@ void tconv_mfma_kernel(const TconvParams p) {
   // two register sets: the words of chunk i+2 are in flight while those of chunk
   // i+1 are being stored to LDS and chunk i is consumed
   float ra[2][NA * AV];
-  float rb[2][NB];
+  float rb[2][NB * BV];
 
   // Global loads go through raw buffer descriptors: a load whose offset is out of
   // range returns 0, so zero padding, ragged tails and masked lanes need no select
@@ -213,8 +215,15 @@ void tconv_mfma_kernel(const TconvParams p) {
       row_cr(ch, kl, c0, r0, c, r);
       const bool ok = chok && (kk0 + kl < p.CRrows) && ((unsigned)(c_ih0[i] + r) < (unsigned)p.H);
       const unsigned voff = ok ? (unsigned)c_goff[i] : kOob;
-      rb[SET][q - NA] = __builtin_bit_cast(
-          float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
+      if constexpr (BV == 4) {
+        floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                    rsrc_in, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rb[SET][(q - NA) * 4 + u] = v[u];
+      } else {
+        rb[SET][q - NA] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
+      }
     }
   };
 
@@ -243,7 +252,14 @@ void tconv_mfma_kernel(const TconvParams p) {
     } else {
       float* B = Bs + buf * bbuf;
       const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
-      B[kl * c_pl[i] + c_lds[i]] = rb[SET][q - NA];
+      if constexpr (BV == 4) {
+        floatx4 v;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = rb[SET][(q - NA) * 4 + u];
+        *reinterpret_cast<floatx4*>(B + kl * c_pl[i] + c_lds[i]) = v;
+      } else {
+        B[kl * c_pl[i] + c_lds[i]] = rb[SET][q - NA];
+      }
     }
   };
 
@@ -391,10 +407,13 @@ void tconv_mfma_kernel(const TconvParams p) {
               acc[mt][nt][i] += red[(((wv * MT + mt) * NT + nt) * 16 + i) * 64 + lane];
       }
     }
-    if (kgrp != 0) return;
   }
+  if (KS > 1 && kgrp != 0) return;
 
-  // ---- epilogue: bias + optional ReLU + store (or raw partial sums for split-K)
+  // ---- epilogue: bias + optional ReLU + store (or raw partial sums for split-K;
+  // partial tiles are summed by a second kernel: exchanging them inside this one
+  // would need a device-scope release/acquire per workgroup, which on this part
+  // means writing back and invalidating a whole L2 slice each time)
   const bool split = p.nsplit > 1;
   float* const dst = split ? p.partial + (size_t)z * (size_t)p.out_elems : p.out;
   float bvals[MT][16];

@@ -38,7 +38,7 @@ def sweep_layer(layer, N, check=True):
         if not binding.conv_variant_applicable(*dims, v):
             continue
         need = binding.conv_fwd_workspace_bytes(*dims, v)
-        ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
 
         def run():
             binding.conv_fwd_ex(xd, fd, bd, out, layer.stride, layer.pad, True, workspace=ws,

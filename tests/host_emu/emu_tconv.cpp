@@ -96,15 +96,18 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
           const int koff = c * p.HW + r * p.W;
           for (int i = 0; i < EPT; ++i) {
             int e = tid + i * NTHR;
-            if (e >= ncell) continue;
+            if (e * p.bv >= ncell) continue;
             BCell cell = b_cell(p, t, e, Sk, STR);
             bool ok = rowok && ((unsigned)(cell.ih0 + r) < (unsigned)p.H);
-            long long gi = ok ? (long long)cell.goff + koff : 0;
-            if (gi < 0 || gi >= in_elems) { oob.hit("in", gi, in_elems); continue; }
-            float val = ok ? in[gi] : 0.0f;
-            long long li = (long long)kl * p.plane + cell.lds;
-            if (cell.lds < 0 || cell.lds >= p.plane) oob.hit("B lds", cell.lds, p.plane);
-            else Bs[li] = val;
+            for (int u = 0; u < p.bv; ++u) {
+              long long gi = ok ? (long long)cell.goff + koff + u : 0;
+              if (p.bv == 4 && u == 0 && ok && (gi % 4) != 0) oob.hit("in alignment", gi, 4);
+              if (gi < 0 || gi >= in_elems) { oob.hit("in", gi, in_elems); continue; }
+              float val = ok ? in[gi] : 0.0f;
+              long long li = (long long)kl * p.plane + cell.lds + u;
+              if (cell.lds + u < 0 || cell.lds + u >= p.plane) oob.hit("B lds", cell.lds + u, p.plane);
+              else Bs[li] = val;
+            }
           }
           if (++r == Rk) { r = 0; ++c; }
         }

@@ -50,7 +50,7 @@ def gpu_conv(x, f, b, stride, pad, relu, variant=-1, use_simple_entry=False, gua
         ws = None
         need = binding.conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant)
         if need:
-            ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=dev)
+            ws = torch.zeros((need + 3) // 4, dtype=torch.float32, device=dev)
         binding.conv_fwd_ex(xd, fd, bd, out, stride, pad, relu, workspace=ws, variant=variant)
     torch.cuda.synchronize()
     host = buf.cpu().numpy()
@@ -113,7 +113,7 @@ FAMILY_SHAPES = {
     # (R, S, stride) of a tile family -> list of (N, C, H, W, K, pad)
     (3, 3, 1): [(2, 13, 13, 13, 70, 1), (1, 5, 30, 31, 129, 1), (3, 4, 7, 5, 33, 0)],
     (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2), (1, 8, 27, 27, 70, 2)],
-    (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0)],
+    (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0), (5, 8, 6, 6, 33, 0)],
     (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
     (0, 0, 0): [(2, 3, 9, 10, 7, 1, 2, 4, 2), (1, 5, 20, 17, 40, 3, 7, 7, 2),
                 (1, 4, 8, 8, 6, 0, 1, 1, 2), (2, 3, 12, 12, 130, 2, 3, 3, 3),
@@ -238,6 +238,31 @@ def test_errors_through_binding():
     torch.cuda.synchronize()
 
 
+def test_split_reduction_is_deterministic_on_a_reused_workspace():
+    """A split variant run several times on one workspace gives the same bits every
+    time (partials are summed in split order, not in arrival order)."""
+    dev = torch.device("cuda:0")
+    layer = workloads.CONV3
+    x, f, b = workloads.make_layer_inputs(layer, 2)
+    dims = (2, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+    names = binding.variant_ids_by_name()
+    v = names["k3_64x64_k12_v4/s8"]
+    need = binding.conv_fwd_workspace_bytes(*dims, v)
+    assert need == 8 * 2 * layer.K * 169 * 4
+    ws = torch.zeros(need // 4, dtype=torch.float32, device=dev)
+    xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
+    ref = oracle.conv_fwd(x, f, b, stride=1, pad=1, relu=True)
+    outs = []
+    for _ in range(4):
+        out = torch.empty((2, layer.K, 13, 13), dtype=torch.float32, device=dev)
+        binding.conv_fwd_ex(xd, fd, bd, out, 1, 1, True, workspace=ws, variant=v)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    assert_close(outs[0], ref, "split conv3")
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+
+
 # ------------------------------------------------------------------ max pooling and the stack
 def test_maxpool_parity():
     dev = torch.device("cuda:0")
@@ -265,7 +290,7 @@ def gpu_stack(img, params):
         fd, bd = torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev)
         need = binding.conv_fwd_workspace_bytes(N, C, H, W, layer.K, layer.R, layer.S,
                                                 layer.stride, layer.pad, -1)
-        ws = torch.empty(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
         binding.conv_fwd_ex(cur, fd, bd, out, layer.stride, layer.pad, True, workspace=ws)
         acts.append((cur, out))
         cur = out

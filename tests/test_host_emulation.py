@@ -76,6 +76,8 @@ CASES = [
     ("pw_64x256_k16_v4", 2, 20, 14, 14, 70, 1, 1, 1, 0, 1),
     ("pw_64x256_k32_v4", 3, 68, 7, 7, 130, 1, 1, 1, 0, 2),
     ("pw_64x128_k16", 2, 6, 5, 9, 40, 1, 1, 1, 1, 1),           # pointwise with padding
+    ("pw_64x128_k16_v4b4", 3, 20, 14, 14, 70, 1, 1, 1, 0, 1),   # 16-byte input loads
+    ("pw_128x128_k64_s2_v4b4", 2, 132, 6, 6, 130, 1, 1, 1, 0, 2),
     ("k11s4_96x256_k4", 2, 3, 67, 71, 96, 11, 11, 4, 0, 1),
     ("k11s4_32x128_k2", 1, 3, 51, 47, 10, 11, 11, 4, 2, 2),
     ("k3_128x64_k12_s3_v4", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),   # reduction split inside the workgroup
