@@ -23,7 +23,11 @@ from paper_1606_00094_amd import binding, roofline
 from paper_1606_00094_amd.timing import graph_time_us
 
 
-def sweep_layer(layer, N, check=True):
+def _split_of(name):
+    return int(name.rsplit("/s", 1)[1])
+
+
+def sweep_layer(layer, N, check=True, max_split=32):
     dev = torch.device("cuda:0")
     x, f, b = workloads.make_layer_inputs(layer, N)
     xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
@@ -36,6 +40,8 @@ def sweep_layer(layer, N, check=True):
     rows = []
     for v in range(1, binding.conv_num_variants()):
         if not binding.conv_variant_applicable(*dims, v):
+            continue
+        if _split_of(binding.conv_variant_name(v)) > max_split:
             continue
         need = binding.conv_fwd_workspace_bytes(*dims, v)
         ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
@@ -61,6 +67,7 @@ def main():
     ap.add_argument("--table", default="gpurun_out/selection_table.inc")
     ap.add_argument("--batches", default="1,5,20,32")
     ap.add_argument("--layers", default="")
+    ap.add_argument("--max-split", type=int, default=0, help="largest reduction split to try (0: by batch)")
     args = ap.parse_args()
     batches = [int(t) for t in args.batches.split(",")]
     names = [t for t in args.layers.split(",") if t]
@@ -68,7 +75,8 @@ def main():
     results, table = [], []
     for layer in layers:
         for N in batches:
-            rows = sweep_layer(layer, N)
+            # large batches have enough tiles; deep reduction splits only cost traffic there
+            rows = sweep_layer(layer, N, max_split=args.max_split or (32 if N <= 2 else 12 if N <= 8 else 6))
             good = [r for r in rows if r["ok"]]
             best = good[0] if good else None
             results.append({"layer": layer.name, "N": N, "best": best, "all": rows})
