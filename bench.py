@@ -89,6 +89,24 @@ def layer_row(prob, ms, mode):
     }
 
 
+def recorded_traffic(prob):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3
+    FETCH_SIZE / WRITE_SIZE (two separate counter runs, scaled by a calibration
+    copy) and recorded under profiles/; None if the record is for another
+    variant, layer or batch than the one running now."""
+    from paper_1606_00094_amd import binding
+    path = os.path.join(ROOT, "profiles", "dominant_kernel_traffic.json")
+    try:
+        with open(path) as fh:
+            rec = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    if (rec.get("variant") == binding.conv_variant_name(prob.variant)
+            and rec.get("layer") == prob.layer.name and rec.get("N") == prob.N):
+        return rec.get("bytes")
+    return None
+
+
 def run_stack(N, reps):
     """Five-layer stack with 3x3/s2 max pooling after the first two layers."""
     import torch
@@ -132,25 +150,27 @@ def run_stack(N, reps):
             "frac_mfma": round(flops / (ms * 1e-3) / 1e12 / roofline.PEAK_FP32_MFMA_TFLOPS, 4)}
 
 
-def cpu_baseline(layers, N):
-    """The oracle as it stands, timed on this machine's host cores over one pass of
-    the same layer set at batch N (bounded: a single execution per layer)."""
+def cpu_baseline(layers, N, min_seconds=10.0, max_passes=8):
+    """The oracle as it stands, timed on this machine's host cores over whole passes of
+    the same layer set at batch N, repeated until about min_seconds of CPU work."""
     import oracle
     import workloads
     from paper_1606_00094_amd import roofline
     oracle.build()
-    flops, secs = 0, 0.0
-    for layer in layers:
-        x, f, b = workloads.make_layer_inputs(layer, N)
-        t0 = time.perf_counter()
-        oracle.conv_fwd(x, f, b, stride=layer.stride, pad=layer.pad, relu=True)
-        secs += time.perf_counter() - t0
-        flops += roofline.conv_flops(N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S,
-                                     layer.stride, layer.pad)
+    problems = [(layer, workloads.make_layer_inputs(layer, N)) for layer in layers]
+    flops, secs, passes = 0, 0.0, 0
+    while passes < max_passes and secs < min_seconds:
+        for layer, (x, f, b) in problems:
+            t0 = time.perf_counter()
+            oracle.conv_fwd(x, f, b, stride=layer.stride, pad=layer.pad, relu=True)
+            secs += time.perf_counter() - t0
+            flops += roofline.conv_flops(N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S,
+                                         layer.stride, layer.pad)
+        passes += 1
     return {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(secs, 2),
-            "sample": "one pass of the %d benchmark layers at batch %d (%.1f GFLOP)"
-                      % (len(layers), N, flops / 1e9)}
+            "sample": "%d pass(es) over the %d benchmark layers at batch %d (%.1f GFLOP)"
+                      % (passes, len(layers), N, flops / 1e9)}
 
 
 def main():
@@ -161,7 +181,7 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer-table", action="store_true")
-    ap.add_argument("--cpu-baseline-batch", type=int, default=8)
+    ap.add_argument("--cpu-baseline-batch", type=int, default=32)
     ap.add_argument("--layers", default="", help="comma-separated layer names (default: all ten)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic, for scaling "
@@ -241,7 +261,7 @@ def main():
     achieved = dom.flops / (dom_ms * 1e-3) / 1e12
     roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": roofline.PEAK_FP32_MFMA_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / roofline.PEAK_FP32_MFMA_TFLOPS, 4),
-            "traffic": None, "kernel": binding.conv_variant_name(dom.variant),
+            "traffic": recorded_traffic(dom), "kernel": binding.conv_variant_name(dom.variant),
             "layer": dom.layer.name, "N": dom.N, "us_per_launch": round(dom_ms * 1e3, 2)}
 
     stack = [] if args.no_layer_table else [run_stack(n, 20) for n in (1, 5, 20, 32)]

@@ -7,10 +7,11 @@ device's own kernel-to-kernel gap but no host launch overhead.
 import torch
 
 
-def graph_time_us(fn, launches=20, replays=5):
+def graph_time_us(fn, launches=20, replays=5, best=False):
     """Microseconds per call of fn() (which must only enqueue work on torch's
     current stream), from replaying a captured graph of `launches` back-to-back
-    calls; best of `replays`."""
+    calls: the mean over `replays` timed replays (after one untimed replay), or
+    the fastest replay with best=True (used to rank candidates in the sweep)."""
     fn()
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
@@ -25,13 +26,13 @@ def graph_time_us(fn, launches=20, replays=5):
             fn()
     g.replay()
     torch.cuda.synchronize()
-    best = float("inf")
+    times = []
     for _ in range(replays):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         g.replay()
         e1.record()
         torch.cuda.synchronize()
-        best = min(best, e0.elapsed_time(e1) * 1e3 / launches)
+        times.append(e0.elapsed_time(e1) * 1e3 / launches)
     del g
-    return best
+    return min(times) if best else sum(times) / len(times)
