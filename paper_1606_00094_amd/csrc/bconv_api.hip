@@ -97,7 +97,7 @@ static int select_variant(const Shape& s, bool filt_aligned16 = true, bool in_al
       int t, ns;
       Plan pl;
       if (id > 0 && decode_variant(id, &t, &ns) && (filt_aligned16 || kTiles[t].AV == 1) &&
-          (in_aligned16 || kTiles[t].BV == 1) &&
+          (in_aligned16 || kTiles[t].BV != kModeCompact4) &&
           plan_tconv(s, kTiles[t], ns, &pl))
         return id;
     }
@@ -106,7 +106,7 @@ static int select_variant(const Shape& s, bool filt_aligned16 = true, bool in_al
   double best_cost = 0.0;
   for (int t = 0; t < kNumTiles; ++t) {
     if (!filt_aligned16 && kTiles[t].AV != 1) continue;
-    if (!in_aligned16 && kTiles[t].BV != 1) continue;
+    if (!in_aligned16 && kTiles[t].BV == kModeCompact4) continue;
     for (int i = 0; i < kNumSplits; ++i) {
       Plan pl;
       if (!plan_tconv(s, kTiles[t], kSplits[i], &pl)) continue;
@@ -170,7 +170,7 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
   Plan pl;
   if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
   if (kTiles[t].AV == 4 && !aligned16) return BCONV_EVARIANT;
-  if (kTiles[t].BV == 4 && !in_aligned16) return BCONV_EVARIANT;
+  if (kTiles[t].BV == kModeCompact4 && !in_aligned16) return BCONV_EVARIANT;
   if (pl.ws_bytes) {
     if (own_ws) {
       int rc = internal_workspace(pl.ws_bytes, &ws);
@@ -201,12 +201,40 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
   const int BN = v.BN(), BM = v.BM(), NTHR = v.NTHR();
   const long long in_elems = (long long)p.N * p.CHW;
   const int ncell = p.nrows * p.rowst;
+  const int planes = p.halo ? v.KR / p.R : v.KR;
   if (p.ast < v.KR * p.S) ++bad;
-  if ((size_t)(2 * BM * p.ast + 2 * (v.KR * p.plane + kLdsTrashWords) + kLdsTrashWords) * 4 > pl.lds_bytes) ++bad;
+  if ((size_t)(2 * BM * p.ast + 2 * (planes * p.plane + kLdsTrashWords) + kLdsTrashWords) * 4 >
+      pl.lds_bytes)
+    ++bad;
   if (v.KS > 1 && (size_t)BM * BN * 4 > pl.lds_bytes) ++bad;
+  if ((long long)ncell > (long long)v.EPT * NTHR * p.bv) ++bad;
   for (unsigned bx = 0; bx < pl.gx; ++bx) {
     PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
     if (t.cnt < 1 || t.cnt > BN) ++bad;
+    if (p.halo) {
+      HaloTile ht = halo_tile(p, t);
+      if (ht.vr < 1 || ht.vr > p.vr) ++bad;
+      for (int e = 0; e < ncell; ++e) {
+        BCell c = h_cell(p, ht, e, p.stride);
+        if (c.lds < 0 || c.lds >= p.plane) ++bad;
+        if (c.ih0 == kNeverValid) continue;
+        long long lo = c.goff, hi = (long long)c.goff + (long long)(p.C - 1) * p.HW;
+        if (lo < 0 || hi >= in_elems) ++bad;
+      }
+      for (int col = 0; col < BN; ++col) {
+        BLane l = h_lane(p, t, ht, col);
+        for (int r = 0; r < p.R; ++r)
+          for (int ss = 0; ss < p.S; ++ss) {
+            int a = l.ldsbase + r * p.rowst + tap_off(ss, p.stride, p.phst);
+            if (a < 0 || a >= p.plane) ++bad;
+          }
+        if (l.valid) {
+          long long lo = l.outoff, hi = (long long)l.outoff + (long long)(p.K - 1) * p.PQ;
+          if (lo < 0 || hi >= p.out_elems) ++bad;
+        }
+      }
+      continue;
+    }
     if (!p.compact && t.rho1 - t.rho0 + 1 > p.nrows) ++bad;
     // staged cells: each LDS word of a plane is written by exactly one cell
     for (int e = 0; e < v.EPT * NTHR; ++e) {
@@ -236,7 +264,6 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
       }
     }
   }
-  // filters: last word a workgroup row can touch
   for (unsigned by = 0; by < pl.gy; ++by) {
     int m0 = (int)by * BM;
     if (m0 >= p.K) ++bad;

@@ -42,6 +42,8 @@ struct TconvParams {
   int nrows, phst, rowst, plane;       // staged-input geometry, plane = nrows*rowst
   int compact;                         // S == 1 and stride == 1: one staged cell per bv tile pixels
   int bv;                              // pixels per staged cell in compact mode (1 or 4)
+  int halo;                            // input staged as whole padded rows per channel (see h_cell)
+  int hp, wt, vr;                      // halo mode: padded height, padded width, staged rows per channel
   int gbias;                           // pad*W + pad: most negative cell offset, see the kernel's loads
   int ast;                             // LDS stride between filter rows (odd)
   int nchunks, chunks_per_split, nsplit;
@@ -149,6 +151,61 @@ BCONV_HD BLane b_lane(const TconvParams& p, const PixTile& t, int col) {
   int img = rho / p.P;
   int pp = rho - img * p.P;
   l.ldsbase = p.compact ? cc : slot * p.rowst + (q - qlo);
+  l.outoff = img * p.K * p.PQ + pp * p.Q + q;
+  return l;
+}
+
+// ---- halo staging -------------------------------------------------------------
+// Instead of one copy of an input row per kernel row that reads it, the tile's
+// input is staged once: for each channel of the chunk the padded input rows
+// u_first .. u_first + vr - 1, where u = img*(H + 2*pad) + (ih + pad) numbers the
+// padded rows of all images consecutively (rows of zeros separate the images).
+// An output pixel (img, p, q) then reads kernel row r, column s at
+//   (u(img, p*stride) - u_first + r) * rowst + tap_off(s) + q
+// so both kernel offsets are uniform over the lanes.  Whole padded rows are
+// staged (phase-split for stride > 1 exactly like the row-slot scheme).
+struct HaloTile {
+  int u_first, vr;
+};
+
+BCONV_HD HaloTile halo_tile(const TconvParams& p, const PixTile& t) {
+  HaloTile h;
+  int img0 = t.rho0 / p.P, p0 = t.rho0 - img0 * p.P;
+  int img1 = t.rho1 / p.P, p1 = t.rho1 - img1 * p.P;
+  h.u_first = img0 * p.hp + p0 * p.stride;
+  h.vr = img1 * p.hp + p1 * p.stride + p.R - h.u_first;
+  return h;
+}
+
+// Staged cell e of one channel plane: row e / rowst of the tile's halo, padded
+// column e % rowst.  goff is the input word for channel 0; ih0 = 0 marks a cell
+// that loads, kNeverValid one that holds padding (or lies outside the halo).
+BCONV_HD BCell h_cell(const TconvParams& p, const HaloTile& ht, int e, int STR) {
+  BCell c;
+  int v = e / p.rowst;
+  int xp = e - v * p.rowst;
+  bool ok = (v < ht.vr) && (xp < p.wt);
+  int u = ht.u_first + v;
+  int img = u / p.hp;
+  int ih = u - img * p.hp - p.pad;
+  int iw = xp - p.pad;
+  ok = ok && (img < p.N) && (ih >= 0) && (ih < p.H) && (iw >= 0) && (iw < p.W);
+  c.lds = v * p.rowst + (xp % STR) * p.phst + xp / STR;
+  c.goff = img * p.CHW + ih * p.W + iw;
+  c.ih0 = ok ? 0 : kNeverValid;
+  return c;
+}
+
+BCONV_HD BLane h_lane(const TconvParams& p, const PixTile& t, const HaloTile& ht, int col) {
+  BLane l;
+  l.valid = col < t.cnt;
+  int cc = l.valid ? col : t.cnt - 1;
+  int g = t.g0 + cc;
+  int rho = g / p.Q;
+  int q = g - rho * p.Q;
+  int img = rho / p.P;
+  int pp = rho - img * p.P;
+  l.ldsbase = (img * p.hp + pp * p.stride - ht.u_first) * p.rowst + q;
   l.outoff = img * p.K * p.PQ + pp * p.Q + q;
   return l;
 }

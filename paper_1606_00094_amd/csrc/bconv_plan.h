@@ -33,6 +33,10 @@ constexpr int kNumTiles = (int)(sizeof(kTileDescs) / sizeof(kTileDescs[0]));
 
 constexpr size_t kLdsLimitBytes = 160 * 1024;
 constexpr int kSmaxGeneric = 16;   // widest kernel the run-time generic tiles take
+// input staging mode of a tile (last column of variants.def)
+constexpr int kModeSlots = 1;      // one copy of an input row per kernel row and output row (or compact cells)
+constexpr int kModeCompact4 = 4;   // compact cells of four pixels, 16-byte loads (flattened pointwise)
+constexpr int kModeHalo = 2;       // whole padded rows per channel, staged once
 constexpr int kLdsTrashWords = 16; // LDS words (in front of the filter buffers, behind each input buffer) that absorb masked stores
 
 struct Plan {
@@ -68,7 +72,13 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   }
   // 16-byte input loads: only for flattened pointwise layers whose images are a
   // multiple of four pixels long, so that no group of four pixels straddles images
-  if (v.BV == 4 && !(flat && s.W % 4 == 0)) return false;
+  if (v.BV == kModeCompact4 && !(flat && s.W % 4 == 0)) return false;
+  // halo staging needs kernel sizes fixed at compile time, a kernel wider than one
+  // column or a stride, and half-chunks / reduction groups made of whole channels
+  if (v.BV == kModeHalo &&
+      !(v.R > 0 && v.S > 0 && v.STR > 0 && !(s.S == 1 && s.stride == 1) && (v.KR / 2) % v.R == 0 &&
+        (v.KR / 2 / v.KS) % v.R == 0))
+    return false;
   TconvParams& p = pl->p;
   std::memset(&p, 0, sizeof(p));
   p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.R = s.R; p.S = s.S;
@@ -84,8 +94,24 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   long long total_rows = (long long)s.N * s.P;
   p.gbias = s.pad * s.W + s.pad;
   p.compact = (s.S == 1 && s.stride == 1) ? 1 : 0;
-  p.bv = p.compact ? v.BV : 1;
-  if (p.compact) {
+  p.bv = (p.compact && v.BV == kModeCompact4) ? 4 : 1;
+  p.halo = (v.BV == kModeHalo) ? 1 : 0;
+  int planes = v.KR;                 // LDS planes per input buffer
+  if (p.halo) {
+    p.hp = s.H + 2 * s.pad;
+    p.wt = s.W + 2 * s.pad;
+    p.phst = (p.wt + s.stride - 1) / s.stride;
+    p.rowst = s.stride * p.phst;
+    p.nrows = 0;
+    p.vr = 0;
+    const int ntiles = (p.NPQ + BN - 1) / BN;
+    for (int ti = 0; ti < ntiles; ++ti) {
+      HaloTile ht = halo_tile(p, pix_tile(ti, BN, p.NPQ, p.Q));
+      if (ht.vr > p.vr) p.vr = ht.vr;
+    }
+    p.nrows = p.vr;
+    planes = v.KR / s.R;
+  } else if (p.compact) {
     p.nrows = 1;
     p.phst = BN;
     p.rowst = BN;
@@ -97,7 +123,7 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   p.plane = p.nrows * p.rowst;
   if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR() * p.bv) return false;
   p.ast = a_row_stride(v.KR * s.S, a_read_width(v.KR, v.S, v.KS));
-  size_t lds = (size_t)(2 * BM * p.ast + 2 * (v.KR * p.plane + kLdsTrashWords) + kLdsTrashWords) * sizeof(float);
+  size_t lds = (size_t)(2 * BM * p.ast + 2 * (planes * p.plane + kLdsTrashWords) + kLdsTrashWords) * sizeof(float);
   if (v.KS > 1 && lds < (size_t)BM * BN * sizeof(float)) lds = (size_t)BM * BN * sizeof(float);
   if (lds > kLdsLimitBytes) return false;
   p.nchunks = (p.CRrows + v.KR - 1) / v.KR;

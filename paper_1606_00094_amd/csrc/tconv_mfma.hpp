@@ -69,8 +69,17 @@ void tconv_mfma_kernel(const TconvParams p) {
   static_assert(AV == 1 || (AV == 4 && S_ > 0 && KRSP % 4 == 0), "vector filter loads need KR*S % 4 == 0");
   constexpr int AGRP = KRSP / AV;                      // load groups per filter row
   constexpr int NA = (BM * AGRP + NTHR - 1) / NTHR;    // filter load items per thread
-  static_assert(BV == 1 || (BV == 4 && S_ == 1 && STR_ == 1), "16-byte input loads are for pointwise tiles");
-  constexpr int NB = KR * EPT;                         // input load items per thread (BV words each)
+  // BV is the input staging mode: kModeSlots, kModeCompact4 or kModeHalo
+  constexpr bool HALO = (BV == kModeHalo);
+  constexpr int BVW = (BV == kModeCompact4) ? 4 : 1;   // words per input load
+  static_assert(BV == kModeSlots || BV == kModeCompact4 || BV == kModeHalo, "unknown staging mode");
+  static_assert(BV != kModeCompact4 || (S_ == 1 && STR_ == 1), "16-byte input loads are for pointwise tiles");
+  static_assert(!HALO || (R_ > 0 && S_ > 0 && STR_ > 0 && (KR / 2) % (R_ > 0 ? R_ : 1) == 0 &&
+                          (KR / 2 / KS) % (R_ > 0 ? R_ : 1) == 0),
+                "halo staging needs whole channels per half-chunk and reduction group");
+  constexpr int RDIV = R_ > 0 ? R_ : 1;
+  constexpr int NPL = HALO ? KR / RDIV : KR;           // LDS planes per input buffer
+  constexpr int NB = NPL * EPT;                        // input load items per thread (BVW words each)
   constexpr int NL = NA + NB;
   constexpr int VW = a_read_width(KR, S_, KS);         // words per LDS read of the filter operand
   constexpr int SW = (AV == 4) ? VW : 1;               // words per LDS store of the filter operand
@@ -90,7 +99,7 @@ void tconv_mfma_kernel(const TconvParams p) {
 
   extern __shared__ __attribute__((aligned(16))) float smem[];
   const int abuf = BM * ast;
-  const int bbuf = KR * plane + kLdsTrashWords;    // each input buffer ends in its own trash words
+  const int bbuf = NPL * plane + kLdsTrashWords;   // each input buffer ends in its own trash words
   float* const trash = smem;                       // kLdsTrashWords words nobody reads
   float* const As = smem + kLdsTrashWords;         // [2][BM][ast]
   float* const Bs = As + 2 * abuf;                 // [2][KR][nrows][rowst] (+ trash)
@@ -104,6 +113,7 @@ void tconv_mfma_kernel(const TconvParams p) {
   const int l32 = lane & 31, h = lane >> 5;
 
   const PixTile t = pix_tile(blockIdx.x, BN, p.NPQ, p.Q);
+  const HaloTile ht = HALO ? halo_tile(p, t) : HaloTile{0, 0};
   const int m0 = blockIdx.y * BM;
 
   // ---- per-thread staging cells of the input tile (fixed for the whole loop)
@@ -112,22 +122,24 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
   for (int i = 0; i < EPT; ++i) {
     int e = tid + i * NTHR;
-    const bool in_tile = e * BV < ncell;
-    BCell c = b_cell(p, t, in_tile ? e : 0, S, STR);
+    const bool in_tile = e * BVW < ncell;
+    BCell c = HALO ? h_cell(p, ht, in_tile ? e : 0, STR) : b_cell(p, t, in_tile ? e : 0, S, STR);
     // LDS word offset from Bs of the cell in plane 0 and the plane stride to add per
     // reduction row; a cell outside the tile writes to the trash words (stride 0)
-    c_lds[i] = in_tile ? c.lds : KR * plane;
+    c_lds[i] = in_tile ? c.lds : NPL * plane;
     c_pl[i] = in_tile ? plane : 0;
-    c_goff[i] = (c.goff + p.gbias) * 4;   // byte offset from the biased descriptor base
     c_ih0[i] = in_tile ? c.ih0 : kNeverValid;
+    // byte offset from the biased descriptor base; in halo mode a cell's validity
+    // does not depend on the kernel row, so it is folded into the offset here
+    c_goff[i] = (HALO && c_ih0[i] == kNeverValid) ? (int)0x80000000u : (c.goff + p.gbias) * 4;
   }
 
   // ---- per-lane operand bases
   int laneB[NT], outoff[NT], colvalid[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    BLane bl = b_lane(p, t, (wn * NT + nt) * 32 + l32);
-    laneB[nt] = bl.ldsbase + (h * (KR / 2) + kgrp * NPAIR) * plane;
+    BLane bl = HALO ? h_lane(p, t, ht, (wn * NT + nt) * 32 + l32) : b_lane(p, t, (wn * NT + nt) * 32 + l32);
+    laneB[nt] = bl.ldsbase + (HALO ? (h * (KR / 2) + kgrp * NPAIR) / RDIV : h * (KR / 2) + kgrp * NPAIR) * plane;
     outoff[nt] = bl.outoff;
     colvalid[nt] = bl.valid;
   }
@@ -149,7 +161,7 @@ void tconv_mfma_kernel(const TconvParams p) {
   // two register sets: the words of chunk i+2 are in flight while those of chunk
   // i+1 are being stored to LDS and chunk i is consumed
   float ra[2][NA * AV];
-  float rb[2][NB * BV];
+  float rb[2][NB * BVW];
 
   // Global loads go through raw buffer descriptors: a load whose offset is out of
   // range returns 0, so zero padding, ragged tails and masked lanes need no select
@@ -212,10 +224,18 @@ void tconv_mfma_kernel(const TconvParams p) {
     } else {
       const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
       int c, r;
-      row_cr(ch, kl, c0, r0, c, r);
-      const bool ok = chok && (kk0 + kl < p.CRrows) && ((unsigned)(c_ih0[i] + r) < (unsigned)p.H);
+      bool ok;
+      if constexpr (HALO) {
+        // plane kl is channel ch*NPL + kl; the cell offset already encodes padding
+        c = ch * NPL + kl;
+        r = 0;
+        ok = chok && (c < p.C);
+      } else {
+        row_cr(ch, kl, c0, r0, c, r);
+        ok = chok && (kk0 + kl < p.CRrows) && ((unsigned)(c_ih0[i] + r) < (unsigned)p.H);
+      }
       const unsigned voff = ok ? (unsigned)c_goff[i] : kOob;
-      if constexpr (BV == 4) {
+      if constexpr (BVW == 4) {
         floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
                                                     rsrc_in, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
 #pragma unroll
@@ -252,7 +272,7 @@ void tconv_mfma_kernel(const TconvParams p) {
     } else {
       float* B = Bs + buf * bbuf;
       const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
-      if constexpr (BV == 4) {
+      if constexpr (BVW == 4) {
         floatx4 v;
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = rb[SET][(q - NA) * 4 + u];
@@ -318,7 +338,8 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
             b[(st + 1) & 1][nt] =
-                B[laneB[nt] + i * plane + (s % (STR_ > 0 ? STR_ : 1)) * phst + s / (STR_ > 0 ? STR_ : 1)];
+                B[laneB[nt] + (HALO ? (i / RDIV) * plane + (i % RDIV) * p.rowst : i * plane) +
+                  (s % (STR_ > 0 ? STR_ : 1)) * phst + s / (STR_ > 0 ? STR_ : 1)];
         }
         if (st % VW == 0 && st / VW + 1 < NGRP) read_a(st / VW + 1, areg[(st / VW + 1) & 1]);
         float a[MT];

@@ -50,7 +50,8 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
   const int AGRP = KRSP / AV;
   const int NA = (BM * AGRP + NTHR - 1) / NTHR;
   const long long in_elems = (long long)p.N * p.CHW, filt_elems = (long long)p.K * p.CRS;
-  const int abuf = BM * p.ast, bbuf = KR * p.plane;
+  const int NPL = p.halo ? KR / p.R : KR;   // LDS planes per input buffer
+  const int abuf = BM * p.ast, bbuf = NPL * p.plane;
   if ((size_t)(2 * abuf + 2 * (bbuf + kLdsTrashWords) + kLdsTrashWords) * 4 > pl.lds_bytes) return 2;
   Oob oob;
   const float nanv = std::numeric_limits<float>::quiet_NaN();
@@ -62,6 +63,8 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
   for (unsigned by = 0; by < pl.gy; ++by)
   for (unsigned bx = 0; bx < pl.gx; ++bx) {
     const PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
+    const HaloTile ht = p.halo ? halo_tile(p, t) : HaloTile{0, 0};
+    if (p.halo && ht.vr > p.vr) oob.hit("halo rows", ht.vr, p.vr);
     const int m0 = (int)by * BM;
     // accumulators per wave tile as plain matrices [BM][BN]
     const int KS = v.KS, NW = v.WM * v.WN;
@@ -90,6 +93,22 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
             }
           }
         }
+        if (p.halo) {
+          for (int j = 0; j < NPL; ++j) {
+            const int c = ch * NPL + j;
+            for (int i = 0; i < EPT; ++i) {
+              int e = tid + i * NTHR;
+              if (e >= ncell) continue;
+              BCell cell = h_cell(p, ht, e, STR);
+              bool ok = (c < p.C) && (cell.ih0 != kNeverValid);
+              long long gi = ok ? (long long)cell.goff + (long long)c * p.HW : 0;
+              if (gi < 0 || gi >= in_elems) { oob.hit("in", gi, in_elems); continue; }
+              float val = ok ? in[gi] : 0.0f;
+              if (cell.lds < 0 || cell.lds >= p.plane) oob.hit("B lds", cell.lds, p.plane);
+              else Bs[(long long)j * p.plane + cell.lds] = val;
+            }
+          }
+        } else {
         int c = kk0 / Rk, r = kk0 - c * Rk;
         for (int kl = 0; kl < KR; ++kl) {
           const bool rowok = (kk0 + kl) < p.CRrows;
@@ -111,6 +130,7 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
           }
           if (++r == Rk) { r = 0; ++c; }
         }
+        }
       }
       // compute: every wave, every (j, s) step
       for (int wave = 0; wave < NW * KS; ++wave) {
@@ -121,15 +141,18 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
         for (int j = 0; j < NPAIR; ++j)
         for (int s = 0; s < Sk; ++s) {
           const int aoff = j * Sk + s;
-          const int boff = j * p.plane + tap_off(s, STR, p.phst);
+          const int boff = (p.halo ? (j / p.R) * p.plane + (j % p.R) * p.rowst : j * p.plane) +
+                           tap_off(s, STR, p.phst);
           for (int mt = 0; mt < v.MT; ++mt)
           for (int nt = 0; nt < v.NT; ++nt) {
             float a[64], b[64];
             for (int lane = 0; lane < 64; ++lane) {
               const int l32 = lane & 31, h = lane >> 5;
               const int laneA = (wm * v.MT * 32 + l32) * p.ast + h * HALF + kgrp * RUN;
-              BLane bl = b_lane(p, t, (wn * v.NT + nt) * 32 + l32);
-              const int laneB = bl.ldsbase + (h * (KR / 2) + kgrp * NPAIR) * p.plane;
+              BLane bl = p.halo ? h_lane(p, t, ht, (wn * v.NT + nt) * 32 + l32)
+                                : b_lane(p, t, (wn * v.NT + nt) * 32 + l32);
+              const int hk = h * (KR / 2) + kgrp * NPAIR;
+              const int laneB = bl.ldsbase + (p.halo ? hk / p.R : hk) * p.plane;
               long long ai = (long long)laneA + mt * 32 * p.ast + aoff;
               long long bi = (long long)laneB + boff;
               if (ai < 0 || ai >= abuf) { oob.hit("A read", ai, abuf); a[lane] = 0; } else a[lane] = As[ai];
@@ -160,7 +183,7 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
         if (k >= p.K) continue;
         for (int nt = 0; nt < v.NT; ++nt) {
           const int col = (wn * v.NT + nt) * 32 + (lane & 31);
-          BLane bl = b_lane(p, t, col);
+          BLane bl = p.halo ? h_lane(p, t, ht, col) : b_lane(p, t, col);
           if (!bl.valid) continue;
           long long oi = (long long)bl.outoff + (long long)k * p.PQ;
           if (oi < 0 || oi >= p.out_elems) { oob.hit("out", oi, p.out_elems); continue; }

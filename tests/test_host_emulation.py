@@ -85,6 +85,18 @@ CASES = [
     ("k5_128x64_k20_s2_v4", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
     ("pw_128x128_k32_s4_v4", 2, 68, 14, 14, 130, 1, 1, 1, 0, 1),
     ("k11s4_96x128_k6_s3", 1, 3, 67, 71, 96, 11, 11, 4, 0, 1),
+    ("k3_64x64_k12_h", 2, 5, 13, 13, 40, 3, 3, 1, 1, 1),          # halo staging: one copy of the input rows
+    ("k3_64x64_k12_h", 3, 13, 13, 13, 70, 3, 3, 1, 1, 2),
+    ("k3_128x128_k12_v4_h", 2, 8, 13, 13, 130, 3, 3, 1, 1, 1),
+    ("k3_64x256_k12_h", 3, 5, 13, 13, 40, 3, 3, 1, 1, 1),         # tile spans more than one image
+    ("k3_32x128_k12_h", 1, 3, 32, 32, 16, 3, 3, 1, 1, 1),
+    ("k3_64x64_k12_h", 1, 4, 6, 7, 5, 3, 3, 1, 3, 1),             # pad >= kernel
+    ("k3_64x64_k12_h", 1, 6, 9, 20, 33, 3, 3, 1, 0, 1),
+    ("k3_64x128_k12_s2_h", 2, 7, 13, 13, 40, 3, 3, 1, 1, 2),
+    ("k3_128x64_k24_s2_v4_h", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),
+    ("k5_64x64_k10_h", 2, 3, 11, 9, 20, 5, 5, 1, 2, 1),
+    ("k5_64x128_k20_v4_h", 1, 16, 27, 27, 70, 5, 5, 1, 2, 2),
+    ("k5_128x64_k20_s2_v4_h", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 2, 4, 2, 1, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 3, 1, 1, 1, 1),            # S = 1, stride 1, R = 3: compact cells
     ("gen_64x64_k2", 1, 2, 12, 12, 5, 3, 3, 3, 2, 2),
