@@ -18,14 +18,15 @@ struct TileDesc {
   const char* name;
   int R, S, STR;            // 0 = run-time value
   int WM, WN, MT, NT, KR, EPT, AV, KS, BV;
+  int PD;                   // register sets of the software pipeline (chunks in flight + 1)
   int BM() const { return WM * MT * 32; }
   int BN() const { return WN * NT * 32; }
   int NTHR() const { return WM * WN * KS * 64; }
 };
 
 static const TileDesc kTileDescs[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV) \
-  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV},
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD) \
+  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD},
 #include "variants.def"
 #undef X
 };

@@ -55,7 +55,18 @@ template <> struct VecOf<4> { typedef floatx4 type; };
 // KS > 1 splits the reduction inside the workgroup: KS groups of WM*WN waves share
 // the staged tiles, group g consuming row pairs [g*NPAIR, (g+1)*NPAIR) of every
 // chunk, and their accumulators are summed through LDS before the epilogue.
-template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV>
+// Calls f(std::integral_constant<int, I>{}) for I = BEGIN .. END-1, each call its own
+// instantiation.
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(std::integral_constant<int, BEGIN>{});
+    static_for<BEGIN + 1, END>(static_cast<F&&>(f));
+  }
+}
+constexpr int cdiv_c(int a, int b) { return (a + b - 1) / b; }
+
+template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV, int PD>
 __global__ __launch_bounds__(WM * WN * KS * 64)
 void tconv_mfma_kernel(const TconvParams p) {
   constexpr int NW = WM * WN;              // waves per reduction group
@@ -84,6 +95,13 @@ void tconv_mfma_kernel(const TconvParams p) {
   constexpr int VW = a_read_width(KR, S_, KS);         // words per LDS read of the filter operand
   constexpr int SW = (AV == 4) ? VW : 1;               // words per LDS store of the filter operand
   constexpr bool WHOLE_CH = R_ > 0 && (KR % (R_ > 0 ? R_ : 1)) == 0;   // chunks hold whole channels
+  // Scalar addressing: a load's per-lane offset is a register computed once before the
+  // loop, and everything that changes from chunk to chunk (channel, kernel row, "past
+  // the end") goes into the scalar offset and the descriptor's size.  No vector
+  // instruction then writes a register that a load also writes, so the compiler needs
+  // no wait on loads in flight before it issues the next ones.
+  constexpr bool A_SCALAR = NA <= 12;                  // one offset register per filter item
+  constexpr bool B_SCALAR = HALO || (R_ == 1 && S_ == 1 && STR_ == 1);
   typedef typename VecOf<VW>::type avec_t;
   typedef typename VecOf<SW>::type svec_t;
 
@@ -131,7 +149,9 @@ void tconv_mfma_kernel(const TconvParams p) {
     c_ih0[i] = in_tile ? c.ih0 : kNeverValid;
     // byte offset from the biased descriptor base; in halo mode a cell's validity
     // does not depend on the kernel row, so it is folded into the offset here
-    c_goff[i] = (HALO && c_ih0[i] == kNeverValid) ? (int)0x80000000u : (c.goff + p.gbias) * 4;
+    const bool never = HALO ? (c_ih0[i] == kNeverValid)
+                            : (B_SCALAR && (unsigned)c_ih0[i] >= (unsigned)p.H);
+    c_goff[i] = never ? (int)0x80000000u : (c.goff + p.gbias) * 4;
   }
 
   // ---- per-lane operand bases
@@ -158,10 +178,11 @@ void tconv_mfma_kernel(const TconvParams p) {
   int ch_end = ch_begin + p.chunks_per_split;
   if (ch_end > p.nchunks) ch_end = p.nchunks;
 
-  // two register sets: the words of chunk i+2 are in flight while those of chunk
-  // i+1 are being stored to LDS and chunk i is consumed
-  float ra[2][NA * AV];
-  float rb[2][NB * BVW];
+  // PD register sets: the words of chunks i+2 .. i+PD are in flight while those of
+  // chunk i+1 are being stored to LDS and chunk i is consumed
+  static_assert(PD == 2 || PD == 4, "prefetch depth");
+  float ra[PD][NA * AV];
+  float rb[PD][NB * BVW];
 
   // Global loads go through raw buffer descriptors: a load whose offset is out of
   // range returns 0, so zero padding, ragged tails and masked lanes need no select
@@ -179,6 +200,25 @@ void tconv_mfma_kernel(const TconvParams p) {
       const_cast<float*>(p.in) - p.gbias, 0, (p.N * p.CHW + p.gbias) * 4, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_filt = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(p.filt), 0, p.K * p.CRS * 4, 0x00020000);
+
+  // per-lane byte offsets of the filter load items (out-of-range marker where the
+  // item lies outside the tile, the filter count or the chunk's row width)
+  unsigned a_voff[A_SCALAR ? NA : 1];
+  if constexpr (A_SCALAR) {
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+      const int e = tid + q * NTHR;
+      const int m = e / AGRP;
+      const int j = (e - m * AGRP) * AV;
+      const bool ok = (((q + 1) * NTHR <= BM * AGRP) || (m < BM)) && (S_ > 0 || j < KRS) && (m0 + m < p.K);
+      a_voff[q] = ok ? (unsigned)(((m0 + m) * p.CRS + j) * 4) : kOob;
+    }
+  }
+  const unsigned filt_bytes = (unsigned)(p.K * p.CRS * 4);
+  const unsigned in_bytes = (unsigned)((p.N * p.CHW + p.gbias) * 4);
+  // the last chunk of the reduction may be narrower than KR rows: its filter words
+  // past the end of the row are zeroed in LDS after they are stored
+  const bool has_tail = p.nchunks * KR * S > p.CRS;
 
   // (c, r) of reduction row kl of chunk ch: compile-time r when a chunk holds
   // whole channels, one conditional wrap when a chunk is shorter than a channel.
@@ -211,15 +251,26 @@ void tconv_mfma_kernel(const TconvParams p) {
       // (q + 1) * NTHR <= BM * AGRP folds to true for all but a ragged last item
       const bool inside = ((q + 1) * NTHR <= BM * AGRP) || (m < BM);
       const bool ok = chok && inside && (S_ > 0 || j < KRS) && (m0 + m < p.K) && (col0 + j < p.CRS);
-      const unsigned voff = ok ? (unsigned)(((m0 + m) * p.CRS + j) * 4) : kOob;
+      unsigned voff;
+      __amdgpu_buffer_rsrc_t rsrc_a;
+      if constexpr (A_SCALAR) {
+        voff = a_voff[q];
+        // (the range check covers per-lane plus scalar offset, so a lane of the last
+        // filter row that would run past the tensor reads 0)
+        rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.filt), 0, chok ? filt_bytes : 0u,
+                                                   0x00020000);
+      } else {
+        voff = ok ? (unsigned)(((m0 + m) * p.CRS + j) * 4) : kOob;
+        rsrc_a = rsrc_filt;
+      }
       if constexpr (AV == 4) {
         floatx4 v = __builtin_bit_cast(
-            floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_filt, voff, col0 * 4, kLoadPolicy));
+            floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, voff, col0 * 4, kLoadPolicy));
 #pragma unroll
         for (int u = 0; u < 4; ++u) ra[SET][q * 4 + u] = v[u];
       } else {
         ra[SET][q] = __builtin_bit_cast(float,
-                                   __builtin_amdgcn_raw_buffer_load_b32(rsrc_filt, voff, col0 * 4, kLoadPolicy));
+                                   __builtin_amdgcn_raw_buffer_load_b32(rsrc_a, voff, col0 * 4, kLoadPolicy));
       }
     } else {
       const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
@@ -234,15 +285,26 @@ void tconv_mfma_kernel(const TconvParams p) {
         row_cr(ch, kl, c0, r0, c, r);
         ok = chok && (kk0 + kl < p.CRrows) && ((unsigned)(c_ih0[i] + r) < (unsigned)p.H);
       }
-      const unsigned voff = ok ? (unsigned)c_goff[i] : kOob;
+      unsigned voff;
+      __amdgpu_buffer_rsrc_t rsrc_b;
+      if constexpr (B_SCALAR) {
+        // what is left of ok is the same for every lane: switch the descriptor off
+        const bool sok = HALO ? ok : (chok && (kk0 + kl < p.CRrows));
+        voff = (unsigned)c_goff[i];
+        rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.in) - p.gbias, 0, sok ? in_bytes : 0u,
+                                                   0x00020000);
+      } else {
+        voff = ok ? (unsigned)c_goff[i] : kOob;
+        rsrc_b = rsrc_in;
+      }
       if constexpr (BVW == 4) {
         floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                    rsrc_in, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
+                                                    rsrc_b, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
 #pragma unroll
         for (int u = 0; u < 4; ++u) rb[SET][(q - NA) * 4 + u] = v[u];
       } else {
         rb[SET][q - NA] = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
+            float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_b, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
       }
     }
   };
@@ -283,6 +345,26 @@ void tconv_mfma_kernel(const TconvParams p) {
     }
   };
 
+  // zero the filter words of chunk ch in LDS buffer buf that lie past the end of the
+  // filter row (scalar addressing loads them from the next row)
+  auto zero_tail = [&](int buf, int ch) {
+    if constexpr (A_SCALAR) {
+      float* A = As + buf * abuf;
+      const int col0 = ch * KR * S;
+#pragma unroll
+      for (int q = 0; q < NA; ++q) {
+        const int e = tid + q * NTHR;
+        const int m = e / AGRP;
+        const int j = (e - m * AGRP) * AV;
+        const bool ok = (((q + 1) * NTHR <= BM * AGRP) || (m < BM)) && (S_ > 0 || j < KRS);
+        if (ok && col0 + j >= p.CRS) {
+#pragma unroll
+          for (int u = 0; u < AV; ++u) A[m * ast + j + u] = 0.0f;
+        }
+      }
+    }
+  };
+
   auto mfma_tile = [&](const float (&a)[MT], const float (&b)[NT]) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -291,18 +373,20 @@ void tconv_mfma_kernel(const TconvParams p) {
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
   };
 
-  // One pipeline stage: consumes chunk ch from LDS buffer P; between its MFMAs the
-  // global loads of chunk ch + 2 are issued into register set P and register set
-  // 1 - P (chunk ch + 1, loaded during the previous stage) is stored to LDS buffer
-  // 1 - P.  Staging work is spread evenly over the steps and needs no conditions:
-  // chunks past the end load zeros and are stored to a buffer nobody reads.
+  // One pipeline stage, J = (ch - ch_begin) % PD: consumes chunk ch from LDS buffer
+  // J % 2; between its MFMAs the global loads of chunk ch + PD are issued into
+  // register set J (free since the previous stage) and register set J + 1 (chunk
+  // ch + 1, loaded PD - 1 stages ago) is stored to the other LDS buffer.  Staging
+  // work is spread evenly over the steps and needs no conditions: chunks past the
+  // end load zeros and are stored to a buffer nobody reads.
   auto stage = [&](auto par_tag, int ch) {
-    constexpr int P = decltype(par_tag)::value;
-    typedef std::integral_constant<int, P> SetLoad;
-    typedef std::integral_constant<int, 1 - P> SetStore;
+    constexpr int J = decltype(par_tag)::value;
+    constexpr int P = J % 2;
+    typedef std::integral_constant<int, J> SetLoad;
+    typedef std::integral_constant<int, (J + 1) % PD> SetStore;
     const float* A = As + P * abuf;
     const float* B = Bs + P * bbuf;
-    const int next = ch + 2;
+    const int next = ch + PD;
     int c0 = 0, r0 = 0;
     if constexpr (!WHOLE_CH) {
       c0 = (next * KR) / R;
@@ -331,33 +415,38 @@ void tconv_mfma_kernel(const TconvParams p) {
       float b[2][NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) b[0][nt] = B[laneB[nt]];
-#pragma unroll
-      for (int st = 0; st < NSTEPS; ++st) {
-        if (st + 1 < NSTEPS) {
-          const int i = (st + 1) / (S_ > 0 ? S_ : 1), s = (st + 1) % (S_ > 0 ? S_ : 1);
+      // The steps are instantiated one by one (not a loop the compiler may decline to
+      // unroll), so that every register array index and every staging item of a step
+      // is a compile-time constant.
+      static_for<0, NSTEPS>([&](auto st_tag) {
+        constexpr int st = decltype(st_tag)::value;
+        if constexpr (st + 1 < NSTEPS) {
+          constexpr int i = (st + 1) / (S_ > 0 ? S_ : 1), s = (st + 1) % (S_ > 0 ? S_ : 1);
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
             b[(st + 1) & 1][nt] =
                 B[laneB[nt] + (HALO ? (i / RDIV) * plane + (i % RDIV) * p.rowst : i * plane) +
                   (s % (STR_ > 0 ? STR_ : 1)) * phst + s / (STR_ > 0 ? STR_ : 1)];
         }
-        if (st % VW == 0 && st / VW + 1 < NGRP) read_a(st / VW + 1, areg[(st / VW + 1) & 1]);
+        if constexpr (st % VW == 0 && st / VW + 1 < NGRP) read_a(st / VW + 1, areg[(st / VW + 1) & 1]);
         float a[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) a[mt] = areg[(st / VW) & 1][mt][st % VW];
         mfma_tile(a, b[st & 1]);
-        // loads in the first half of the steps, stores in the second half: the
-        // memory counter retires loads in order, so a store waits for every load
-        // issued before it except this stage's own; this way those are a full
-        // chunk old
-#pragma unroll
-        for (int q = 0; q < NL; ++q) {
-          if (q * LSTEPS / NL == st) load_item(SetLoad{}, next, q, c0, r0);
-          if (LSTEPS + q * (NSTEPS - LSTEPS) / NL == st) store_item(SetStore{}, 1 - P, q);
-        }
+        // loads in the first half of the steps, stores in the second half, both spread
+        // evenly: the memory counter retires loads in order, so a store waits for every
+        // load issued before it except this stage's own; this way those are at least
+        // PD - 1 stages old
+        constexpr int D = NSTEPS - LSTEPS;
+        constexpr int lq0 = LSTEPS ? (st < LSTEPS ? cdiv_c(st * NL, LSTEPS) : NL) : (st == 0 ? 0 : NL);
+        constexpr int lq1 = LSTEPS ? (st < LSTEPS ? cdiv_c((st + 1) * NL, LSTEPS) : NL) : NL;
+        constexpr int sq0 = st >= LSTEPS ? cdiv_c((st - LSTEPS) * NL, D) : NL;
+        constexpr int sq1 = st >= LSTEPS ? cdiv_c((st - LSTEPS + 1) * NL, D) : NL;
+        static_for<lq0, lq1>([&](auto q_tag) { load_item(SetLoad{}, next, decltype(q_tag)::value, c0, r0); });
+        static_for<sq0, sq1>([&](auto q_tag) { store_item(SetStore{}, 1 - P, decltype(q_tag)::value); });
         // keep the compiler from regrouping the staging work of different steps
         __builtin_amdgcn_sched_barrier(0);
-      }
+      });
     } else {
 #pragma unroll
       for (int q = 0; q < NL; ++q) load_item(SetLoad{}, next, q, c0, r0);
@@ -376,30 +465,62 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
       for (int q = 0; q < NL; ++q) store_item(SetStore{}, 1 - P, q);
     }
+    if (has_tail && ch + 1 == p.nchunks - 1) zero_tail(1 - P, ch + 1);
   };
 
   typedef std::integral_constant<int, 0> Zero;
-  typedef std::integral_constant<int, 1> One;
-  {
-    // prologue: chunk 0 through registers into buffer 0, chunk 1 into register set 1
-    int c0 = (ch_begin * KR) / R;
-    int r0 = ch_begin * KR - c0 * R;
+  auto prologue_load = [&](auto set_tag) {
+    constexpr int J = decltype(set_tag)::value;
+    const int c0 = ((ch_begin + J) * KR) / R;
+    const int r0 = (ch_begin + J) * KR - c0 * R;
 #pragma unroll
-    for (int q = 0; q < NL; ++q) load_item(Zero{}, ch_begin, q, c0, r0);
-    c0 = ((ch_begin + 1) * KR) / R;
-    r0 = (ch_begin + 1) * KR - c0 * R;
-#pragma unroll
-    for (int q = 0; q < NL; ++q) load_item(One{}, ch_begin + 1, q, c0, r0);
-#pragma unroll
-    for (int q = 0; q < NL; ++q) store_item(Zero{}, 0, q);
+    for (int q = 0; q < NL; ++q) load_item(set_tag, ch_begin + J, q, c0, r0);
+  };
+  // prologue: chunks 0 .. PD-1 into the register sets, chunk 0 on into buffer 0
+  prologue_load(Zero{});
+  prologue_load(std::integral_constant<int, 1>{});
+  if constexpr (PD == 4) {
+    prologue_load(std::integral_constant<int, 2>{});
+    prologue_load(std::integral_constant<int, 3>{});
   }
+#pragma unroll
+  for (int q = 0; q < NL; ++q) store_item(Zero{}, 0, q);
+  if (has_tail && ch_begin == p.nchunks - 1) zero_tail(0, ch_begin);
   __syncthreads();
-  for (int ch = ch_begin; ch < ch_end; ch += 2) {
-    stage(Zero{}, ch);
-    __syncthreads();
-    if (ch + 1 < ch_end) {
-      stage(One{}, ch + 1);
+  // The loop body runs PD stages unconditionally and the remaining 0 .. PD-1 stages
+  // follow it.  (A stage guarded by a condition inside the loop would add a path to
+  // the control flow graph that skips it and re-enters the loop; that path never
+  // runs, but on it a register set would still have loads in flight when the next
+  // stage reuses it, and the compiler would make every stage wait for them.)
+  {
+    const int nst = ch_end - ch_begin;
+    int ch = ch_begin;
+    for (int it = nst / PD; it > 0; --it, ch += PD) {
+      stage(Zero{}, ch);
       __syncthreads();
+      stage(std::integral_constant<int, 1>{}, ch + 1);
+      __syncthreads();
+      if constexpr (PD == 4) {
+        stage(std::integral_constant<int, 2>{}, ch + 2);
+        __syncthreads();
+        stage(std::integral_constant<int, 3>{}, ch + 3);
+        __syncthreads();
+      }
+    }
+    const int rem = nst % PD;
+    if (rem >= 1) {
+      stage(Zero{}, ch);
+      __syncthreads();
+    }
+    if constexpr (PD == 4) {
+      if (rem >= 2) {
+        stage(std::integral_constant<int, 1>{}, ch + 1);
+        __syncthreads();
+      }
+      if (rem >= 3) {
+        stage(std::integral_constant<int, 2>{}, ch + 2);
+        __syncthreads();
+      }
     }
   }
 

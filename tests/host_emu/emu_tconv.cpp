@@ -72,6 +72,8 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
     const int ch_begin = (int)bz * p.chunks_per_split;
     int ch_end = ch_begin + p.chunks_per_split;
     if (ch_end > p.nchunks) ch_end = p.nchunks;
+    const bool a_scalar = NA <= 12;
+    const bool has_tail = (long long)p.nchunks * KR * Sk > p.CRS;
     for (int ch = ch_begin; ch < ch_end; ++ch) {
       std::fill(As.begin(), As.end(), nanv);
       std::fill(Bs.begin(), Bs.end(), nanv);
@@ -81,16 +83,37 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
         for (int i = 0; i < NA; ++i) {
           int e = tid + i * NTHR;
           int m = e / AGRP, j = (e - m * AGRP) * AV;
-          bool ok = (m < BM) && (j < KRS) && (m0 + m < p.K) && (col0 + j < p.CRS);
-          long long gi = ok ? (long long)(m0 + m) * p.CRS + col0 + j : 0;
+          const bool in_lds = (m < BM) && (j < KRS);
+          bool ok;
+          long long gi;
+          if (a_scalar) {
+            // per-lane offset fixed before the loop plus the chunk's column offset,
+            // range-checked together against the end of the tensor
+            const bool lane_ok = in_lds && (m0 + m < p.K);
+            const long long voff = (long long)(m0 + m) * p.CRS + j;
+            ok = lane_ok && (voff + col0 + AV <= filt_elems);
+            gi = ok ? voff + col0 : 0;
+          } else {
+            ok = in_lds && (m0 + m < p.K) && (col0 + j < p.CRS);
+            gi = ok ? (long long)(m0 + m) * p.CRS + col0 + j : 0;
+          }
           if (AV == 4 && (gi % 4) != 0) oob.hit("filt alignment", gi, 4);
           for (int u = 0; u < AV; ++u) {
             if (gi + u < 0 || gi + u >= filt_elems) { oob.hit("filt", gi + u, filt_elems); continue; }
             float val = ok ? filt[gi + u] : 0.0f;
-            if ((m < BM) && (j < KRS)) {
+            if (in_lds) {
               int li = m * p.ast + j + u;
               if (li < 0 || li >= abuf) oob.hit("A lds", li, abuf); else As[li] = val;
             }
+          }
+        }
+        // words past the end of the filter row (last chunk of the reduction) are zeroed
+        if (a_scalar && has_tail && ch == p.nchunks - 1) {
+          for (int i = 0; i < NA; ++i) {
+            int e = tid + i * NTHR;
+            int m = e / AGRP, j = (e - m * AGRP) * AV;
+            if ((m < BM) && (j < KRS) && (col0 + j >= p.CRS))
+              for (int u = 0; u < AV; ++u) As[m * p.ast + j + u] = 0.0f;
           }
         }
         if (p.halo) {

@@ -97,6 +97,14 @@ CASES = [
     ("k5_64x64_k10_h", 2, 3, 11, 9, 20, 5, 5, 1, 2, 1),
     ("k5_64x128_k20_v4_h", 1, 16, 27, 27, 70, 5, 5, 1, 2, 2),
     ("k5_128x64_k20_s2_v4_h", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
+    ("pw_64x96w_k32_s2_v4", 2, 68, 14, 14, 70, 1, 1, 1, 0, 1),        # three pixel tiles per wave
+    ("pw_96x64w_k32_s4_v4", 3, 132, 7, 7, 100, 1, 1, 1, 0, 1),       # three filter tiles per wave
+    ("pw_96x32w_k16_s2", 1, 21, 6, 6, 97, 1, 1, 1, 0, 2),
+    ("pw_32x192w_k64_s4_v4", 2, 132, 14, 14, 40, 1, 1, 1, 0, 1),
+    ("pw_96x96w_k32_s2", 2, 37, 9, 9, 200, 1, 1, 1, 0, 1),
+    ("pw_64x128_k16_v4_p4", 2, 68, 14, 14, 70, 1, 1, 1, 0, 1),        # four register sets
+    ("pw_128x128_k32_s2_p4", 2, 137, 9, 9, 200, 1, 1, 1, 0, 3),
+    ("k11s4_96x128_k2_p4", 1, 3, 51, 47, 96, 11, 11, 4, 0, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 2, 4, 2, 1, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 3, 1, 1, 1, 1),            # S = 1, stride 1, R = 3: compact cells
     ("gen_64x64_k2", 1, 2, 12, 12, 5, 3, 3, 3, 2, 2),
