@@ -107,6 +107,26 @@ def recorded_traffic(prob):
     return None
 
 
+def run_sgemm(n):
+    """Square matrix product of size n through the sgemm entry point (the sizes of the
+    paper's SGEMM tables; reported as context beside the pointwise layers)."""
+    import torch
+    import workloads
+    from paper_1606_00094_amd import binding, roofline
+    from paper_1606_00094_amd.timing import graph_time_us
+    dev = torch.device("cuda:0")
+    a, b = workloads.make_sgemm_inputs(n)
+    ad, bd = torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)
+    c = torch.empty((n, n), dtype=torch.float32, device=dev)
+    need = binding.sgemm_workspace_bytes(n, n, n)
+    ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+    us = graph_time_us(lambda: binding.sgemm_ex(ad, bd, c, workspace=ws), launches=20)
+    gf = roofline.sgemm_flops(n, n, n) / us / 1e3
+    return {"size": n, "us": round(us, 2), "gflops": round(gf, 1),
+            "frac_mfma": round(gf / 1e3 / roofline.PEAK_FP32_MFMA_TFLOPS, 4),
+            "variant": binding.conv_variant_name(binding.conv_selected_variant(1, n, 1, n, n, 1, 1, 1, 0))}
+
+
 def run_stack(N, reps):
     """Five-layer stack with 3x3/s2 max pooling after the first two layers."""
     import torch
@@ -268,6 +288,10 @@ def main():
     for row in stack:
         log(json.dumps({"stack": row}))
 
+    sgemm = [] if args.no_layer_table else [run_sgemm(n) for n in workloads.SGEMM_SIZES]
+    for row in sgemm:
+        log(json.dumps({"sgemm": row}))
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(layers, args.cpu_baseline_batch)
@@ -283,7 +307,7 @@ def main():
                                if not args.layers else
                                "layers %s at batch %d, bias + ReLU fused" % (args.layers, args.batch),
                    "batch": args.batch, "gflop_per_step": round(total_flops / 1e9, 2)},
-        "roofline": roof, "cpu_baseline": cpu, "layers": table, "stack": stack,
+        "roofline": roof, "cpu_baseline": cpu, "layers": table, "stack": stack, "sgemm": sgemm,
     }), flush=True)
 
 

@@ -77,6 +77,18 @@ int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* ou
 size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
                                 int stride, int pad, int variant_id);
 
+/* Single-precision matrix multiply C = A * B on row-major matrices, A M x K,
+ * B K x N, C M x N (the SGEMM of the paper's Section V and Tables I-II, M = N = K
+ * from 128 to 2048 there).  It runs the pointwise path: rows of A are the filters,
+ * columns of B the pixels of one image, K the channels; the variant ids, the
+ * workspace rule and the error codes are those of conv_fwd_ex for the shape
+ * (N=1, C=K, H=1, W=N, K=M, 1x1, stride 1, pad 0).  No bias, no activation.
+ * sgemm uses the null stream and the library's own workspace, like conv_fwd. */
+int sgemm(const float* A, const float* B, float* C, int M, int N, int K);
+int sgemm_ex(const float* A, const float* B, float* C, int M, int N, int K, void* workspace,
+             size_t workspace_bytes, void* hip_stream, int variant_id);
+size_t sgemm_workspace_bytes(int M, int N, int K, int variant_id);
+
 /* Variant catalogue.  A variant is a kernel family + tile shape + reduction
  * split; the ids are stable within one build of the library. */
 int conv_num_variants(void);

@@ -12,4 +12,5 @@ from .conv_oracle import (  # noqa: F401
     conv_out_dims,
     maxpool_fwd,
     num_threads,
+    sgemm,
 )

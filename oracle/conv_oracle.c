@@ -27,6 +27,9 @@
  * Loop order is exactly n, k, p, q, c, r, s.  No blocking, no im2col, no
  * reordering.  OpenMP only spreads the independent (n, k) pairs over cores.
  *
+ * oracle_sgemm (further down) is the matrix product by its definition, pinned
+ * against the float64 library product, the identity and the 1x1 convolution.
+ *
  * Pins (tests/test_oracle_*.py): printed worked-example sizes, brute-force
  * im2col x matmul on tiny inputs, delta filter, linearity, exact-integer data,
  * all-ones closed form, 1x1 == library matmul, batch independence,
@@ -123,6 +126,25 @@ int oracle_maxpool_fwd(const float *in, float *out, int N, int C, int H, int W,
                     }
                 dst[(size_t)p * Q + q] = m;
             }
+        }
+    }
+    return 0;
+}
+
+/* Matrix product by its definition (the SGEMM of Section V, row-major
+ * operands): c[i][j] = sum_k a[i][k] * b[k][j], loops i, j, k in that order,
+ * accumulated in double and rounded to fp32 once.  a: M*K, b: K*N, c: M*N. */
+int oracle_sgemm(const float *a, const float *b, float *c, int M, int N, int K)
+{
+    if (!a || !b || !c || M <= 0 || N <= 0 || K <= 0)
+        return -1;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i) {
+        for (int j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += (double)a[(size_t)i * K + k] * (double)b[(size_t)k * N + j];
+            c[(size_t)i * N + j] = (float)acc;
         }
     }
     return 0;

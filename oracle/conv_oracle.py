@@ -45,6 +45,8 @@ def _load():
         lib.oracle_conv_fwd.restype = ctypes.c_int
         lib.oracle_maxpool_fwd.argtypes = [_f32p, _f32p] + [ctypes.c_int] * 6
         lib.oracle_maxpool_fwd.restype = ctypes.c_int
+        lib.oracle_sgemm.argtypes = [_f32p] * 3 + [ctypes.c_int] * 3
+        lib.oracle_sgemm.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -104,6 +106,19 @@ def maxpool_fwd(inp, ksz=3, stride=2):
     if rc != 0:
         raise ValueError("oracle_maxpool_fwd rejected its arguments")
     return out
+
+
+def sgemm(a, b):
+    """C = A * B by definition (row-major, double accumulation, one rounding)."""
+    a, b = _as_f32(a), _as_f32(b)
+    M, K = a.shape
+    K2, N = b.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ")
+    c = np.empty((M, N), dtype=np.float32)
+    if _load().oracle_sgemm(_ptr(a), _ptr(b), _ptr(c), M, N, K) != 0:
+        raise ValueError("oracle_sgemm rejected its arguments")
+    return c
 
 
 def num_threads():

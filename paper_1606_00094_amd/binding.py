@@ -20,6 +20,9 @@ EXPORTS = {
     "conv_fwd": ([_vp] * 4 + [_i] * 10, _i),
     "conv_fwd_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
     "conv_fwd_workspace_bytes": ([_i] * 10, _sz),
+    "sgemm": ([_vp] * 3 + [_i] * 3, _i),
+    "sgemm_ex": ([_vp] * 3 + [_i] * 3 + [_vp, _sz, _vp, _i], _i),
+    "sgemm_workspace_bytes": ([_i] * 4, _sz),
     "conv_num_variants": ([], _i),
     "conv_variant_name": ([_i, ctypes.c_char_p, _sz], _i),
     "conv_selected_variant": ([_i] * 9, _i),
@@ -125,6 +128,36 @@ def conv_fwd(inp, filt, bias, out, stride, pad, relu):
 
 def conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant=-1):
     return int(lib().conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, int(variant)))
+
+
+def _gemm_dims(a, b, c):
+    M, K = a.shape
+    K2, N = b.shape
+    if K != K2 or tuple(c.shape) != (M, N):
+        raise ValueError("sgemm shapes: A %s, B %s, C %s" % (tuple(a.shape), tuple(b.shape), tuple(c.shape)))
+    return M, N, K
+
+
+def sgemm(a, b, c):
+    """sgemm of the C ABI: C = A * B, row-major (null stream, library workspace)."""
+    M, N, K = _gemm_dims(a, b, c)
+    _check(lib().sgemm(_dev_ptr(a, "A"), _dev_ptr(b, "B"), _dev_ptr(c, "C"), M, N, K), "sgemm")
+    return c
+
+
+def sgemm_ex(a, b, c, workspace=None, stream=None, variant=-1):
+    """sgemm_ex of the C ABI; enqueues on `stream` (default: torch's current stream)."""
+    M, N, K = _gemm_dims(a, b, c)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib().sgemm_ex(_dev_ptr(a, "A"), _dev_ptr(b, "B"), _dev_ptr(c, "C"), M, N, K, ws_ptr,
+                          ws_bytes, _stream_handle(stream), int(variant)), "sgemm_ex")
+    return c
+
+
+def sgemm_workspace_bytes(M, N, K, variant=-1):
+    return int(lib().sgemm_workspace_bytes(M, N, K, int(variant)))
 
 
 def conv_num_variants():

@@ -337,6 +337,22 @@ size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
   return pl.ws_bytes;
 }
 
+// C[M x N] = A[M x K] * B[K x N] is the pointwise convolution of one "image" whose
+// N columns are the pixels: filters = rows of A, channels = the reduction index.
+int sgemm_ex(const float* A, const float* B, float* C, int M, int N, int K, void* workspace,
+             size_t workspace_bytes, void* hip_stream, int variant_id) {
+  return conv_fwd_ex(B, A, nullptr, C, 1, K, 1, N, M, 1, 1, 1, 0, 0, workspace, workspace_bytes,
+                     hip_stream, variant_id);
+}
+
+int sgemm(const float* A, const float* B, float* C, int M, int N, int K) {
+  return conv_fwd(B, A, nullptr, C, 1, K, 1, N, M, 1, 1, 1, 0, 0);
+}
+
+size_t sgemm_workspace_bytes(int M, int N, int K, int variant_id) {
+  return conv_fwd_workspace_bytes(1, K, 1, N, M, 1, 1, 1, 0, variant_id);
+}
+
 int conv_num_variants(void) { return kNumVariants; }
 
 int conv_variant_name(int variant_id, char* buf, size_t buflen) {

@@ -30,7 +30,7 @@ def _split_of(name):
 def sweep_layer(layer, N, check=True, max_split=32):
     dev = torch.device("cuda:0")
     x, f, b = workloads.make_layer_inputs(layer, N)
-    xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
+    xd, fd, bd = (None if a is None else torch.from_numpy(a).to(dev) for a in (x, f, b))
     dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
     P, Q = workloads.out_hw(layer)
     out = torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)
@@ -67,16 +67,20 @@ def main():
     ap.add_argument("--table", default="gpurun_out/selection_table.inc")
     ap.add_argument("--batches", default="1,5,20,32")
     ap.add_argument("--layers", default="")
+    ap.add_argument("--sgemm", action="store_true", help="also sweep the square matrix products")
     ap.add_argument("--max-split", type=int, default=0, help="largest reduction split to try (0: by batch)")
     args = ap.parse_args()
     batches = [int(t) for t in args.batches.split(",")]
     names = [t for t in args.layers.split(",") if t]
-    layers = [l for l in workloads.ALL_LAYERS if not names or l.name in names]
+    # the square matrix products (batch 1 only) are swept when named, or with --sgemm
+    pool = workloads.ALL_LAYERS + (workloads.SGEMM_LAYERS if args.sgemm or names else [])
+    layers = [l for l in pool if not names or l.name in names]
     results, table = [], []
     for layer in layers:
-        for N in batches:
+        for N in (batches if not layer.name.startswith("sgemm_") else [1]):
             # large batches have enough tiles; deep reduction splits only cost traffic there
-            rows = sweep_layer(layer, N, max_split=args.max_split or (32 if N <= 2 else 12 if N <= 8 else 6))
+            big = layer.name.startswith("sgemm_") and layer.C >= 768
+            rows = sweep_layer(layer, N, max_split=args.max_split or (4 if big else 32 if N <= 2 else 12 if N <= 8 else 6))
             good = [r for r in rows if r["ok"]]
             best = good[0] if good else None
             results.append({"layer": layer.name, "N": N, "best": best, "all": rows})

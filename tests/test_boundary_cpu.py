@@ -17,7 +17,7 @@ def _declared_functions():
     text = open(os.path.join(ROOT, "include", "bconv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
-    return sorted(set(n for n in names if n.startswith(("conv_", "bconv_", "maxpool_"))))
+    return sorted(set(n for n in names if n.startswith(("conv_", "bconv_", "maxpool_", "sgemm"))))
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -101,3 +101,13 @@ def test_workspace_query_matches_split():
     assert binding.conv_fwd_workspace_bytes(*dims, names["k3_64x64_k12/s1"]) == 0
     assert binding.conv_fwd_workspace_bytes(*dims, names["k3_64x64_k12/s4"]) == 4 * 384 * 169 * 4
     assert binding.conv_fwd_workspace_bytes(*dims, names["direct"]) == 0
+
+
+def test_sgemm_rejects_bad_arguments_without_a_gpu():
+    lib = binding.lib()
+    fake = ctypes.c_void_p(4096)   # never dereferenced: every call below fails validation
+    assert lib.sgemm(None, fake, fake, 4, 4, 4) == -2
+    assert lib.sgemm(fake, fake, None, 4, 4, 4) == -2
+    assert lib.sgemm(fake, fake, fake, 0, 4, 4) == -1
+    assert lib.sgemm_ex(fake, fake, fake, 4, 4, 4, None, 0, None, binding.conv_num_variants()) == -6
+    assert binding.sgemm_workspace_bytes(64, 64, 64, 0) == 0

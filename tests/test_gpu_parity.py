@@ -320,3 +320,50 @@ def test_five_layer_stack(N):
     assert cur.shape == (N, 256, 13, 13)
     err = np.abs(acts[-1][1] - cur)
     assert (err <= np.maximum(1e-4, 1e-3 * np.abs(cur))).all()   # five layers of propagated rounding
+
+
+# ------------------------------------------------------------------ sgemm (Section V tables)
+def _gpu_sgemm(a, b, variant=None, use_default_entry=False):
+    dev = torch.device("cuda:0")
+    ad, bd = torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)
+    M, K = a.shape
+    N = b.shape[1]
+    c = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
+    if use_default_entry:
+        binding.sgemm(ad, bd, c)
+    else:
+        v = -1 if variant is None else variant
+        need = binding.sgemm_workspace_bytes(M, N, K, v)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        binding.sgemm_ex(ad, bd, c, workspace=ws, variant=v)
+    torch.cuda.synchronize()
+    return c.cpu().numpy()
+
+
+@pytest.mark.parametrize("n", workloads.SGEMM_SIZES)
+def test_sgemm_table_sizes(n):
+    """Square products at the sizes of the paper's SGEMM tables; the whole result up to
+    512, above that 48 sampled rows and 64 sampled columns the oracle computes one block at a time."""
+    a, b = workloads.make_sgemm_inputs(n)
+    got = _gpu_sgemm(a, b)
+    assert not np.isnan(got).any()
+    if n <= 512:
+        assert_close(got, oracle.sgemm(a, b), "sgemm %d" % n)
+    else:
+        rng = np.random.default_rng(n)
+        rows = np.sort(rng.choice(n, 48, replace=False))
+        cols = np.sort(rng.choice(n, 64, replace=False))
+        assert_close(got[rows], oracle.sgemm(a[rows], b), "sgemm %d sampled rows" % n)
+        assert_close(got[:, cols], oracle.sgemm(a, np.ascontiguousarray(b[:, cols])), "sgemm %d sampled columns" % n)
+
+
+@pytest.mark.parametrize("mnk", [(70, 130, 37), (1, 5, 3), (200, 33, 129), (33, 1, 64), (96, 257, 260)])
+def test_sgemm_rectangular_exact_on_integers(mnk):
+    M, N, K = mnk
+    rng = np.random.default_rng(M * 1000 + N)
+    a = rng.integers(-2, 3, (M, K)).astype(np.float32)
+    b = rng.integers(-2, 3, (K, N)).astype(np.float32)
+    ref = oracle.sgemm(a, b)
+    assert np.array_equal(_gpu_sgemm(a, b), ref)
+    assert np.array_equal(_gpu_sgemm(a, b, use_default_entry=True), ref)
+    assert np.array_equal(_gpu_sgemm(a, b, variant=0), ref)          # direct kernel

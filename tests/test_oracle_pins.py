@@ -303,3 +303,41 @@ def test_toy_config_against_bruteforce():
     ref = bruteforce.conv_im2col(x, f, b, stride=1, pad=1, relu=True, loops=False)
     assert got.shape == (1, 16, 32, 32)
     np.testing.assert_allclose(got, ref, rtol=3e-7, atol=1e-7)
+
+
+# ------------------------------------------------------------------ sgemm (Section V)
+def test_sgemm_hand_computed_rectangular():
+    """2x3 times 3x2 worked by hand; a transposed operand or swapped index changes it."""
+    a = np.array([[1, 2, 3], [4, 5, 6]], np.float32)
+    b = np.array([[7, 8], [9, 10], [11, 12]], np.float32)
+    assert oracle.sgemm(a, b).tolist() == [[58.0, 64.0], [139.0, 154.0]]
+
+
+def test_sgemm_python_loops_on_integers():
+    rng = np.random.default_rng(3)
+    a = rng.integers(-3, 4, (5, 7)).astype(np.float32)
+    b = rng.integers(-3, 4, (7, 4)).astype(np.float32)
+    want = [[sum(float(a[i, k]) * float(b[k, j]) for k in range(7)) for j in range(4)] for i in range(5)]
+    assert oracle.sgemm(a, b).tolist() == want
+
+
+def test_sgemm_identity_and_library_product():
+    rng = np.random.default_rng(4)
+    a = rng.standard_normal((33, 65)).astype(np.float32)
+    b = rng.standard_normal((65, 47)).astype(np.float32)
+    assert np.array_equal(oracle.sgemm(a, np.eye(65, dtype=np.float32)), a)
+    assert np.array_equal(oracle.sgemm(np.eye(65, dtype=np.float32), b), b)
+    # float64 library product, rounded once: equal up to the double rounding of a 65-term sum
+    want = (a.astype(np.float64) @ b.astype(np.float64)).astype(np.float32)
+    got = oracle.sgemm(a, b)
+    assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.maximum(1.0, np.abs(want)))
+
+
+def test_sgemm_is_the_pointwise_convolution_of_one_image():
+    """C = A*B equals the 1x1 convolution with filters A (M x K) on the image B (K channels,
+    1 x N pixels): ties the two oracle functions to each other bit for bit."""
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal((9, 21)).astype(np.float32)
+    b = rng.standard_normal((21, 30)).astype(np.float32)
+    conv = oracle.conv_fwd(b.reshape(1, 21, 1, 30), a.reshape(9, 21, 1, 1))
+    assert np.array_equal(conv.reshape(9, 30), oracle.sgemm(a, b))

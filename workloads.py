@@ -37,7 +37,15 @@ CONFIG_POINTWISE = [PW_A, PW_B, PW_C, RED3, RED5]
 STACK = [CONV1, CONV2, CONV3, CONV4, CONV5]   # 3x3/s2 max-pool after conv1 and conv2
 STACK_POOL_AFTER = (0, 1)
 ALL_LAYERS = CONFIG_TOY + CONFIG_FIRST + CONFIG_MIDDLE + CONFIG_POINTWISE
-BY_NAME = {l.name: l for l in ALL_LAYERS}
+
+# Square single-precision matrix products at the sizes of the paper's two SGEMM
+# tables (Section V), each written as the pointwise layer it runs as:
+# C[M x N] = A[M x K] * B[K x N]  <->  filters A, one image B of K channels, 1 x N pixels.
+SGEMM_SIZES = (128, 256, 384, 512, 768, 1024, 1536, 2048)
+# A is drawn like filters (normal, std 0.01) and B like activations (uniform[0,1)), so that
+# the convolution tolerance, which is absolute near zero, means the same thing here.
+SGEMM_LAYERS = [Layer("sgemm_%d" % n, n, 1, n, n, 1, 1, 1, 0, "u01", "n001", "none") for n in SGEMM_SIZES]
+BY_NAME = {l.name: l for l in ALL_LAYERS + SGEMM_LAYERS}
 
 
 def out_hw(layer):
@@ -64,7 +72,7 @@ def _draw(rng, dist, shape):
 
 def layer_seed(layer, N):
     """Seed of one (layer, batch) problem: base + 1000*index + N."""
-    idx = [l.name for l in ALL_LAYERS].index(layer.name)
+    idx = [l.name for l in ALL_LAYERS + SGEMM_LAYERS].index(layer.name)
     return BASE_SEED + 1000 * idx + N
 
 
@@ -94,6 +102,13 @@ def make_integer_problem(seed, N, C, H, W, K, R, S, lo=-2, hi=2, with_bias=True)
     f = rng.integers(lo, hi + 1, size=(K, C, R, S)).astype(np.float32)
     b = rng.integers(-3, 4, size=(K,)).astype(np.float32) if with_bias else None
     return x, f, b
+
+
+def make_sgemm_inputs(n, seed=None):
+    """(A[n x n] normal(0, 0.01), B[n x n] uniform[0,1)) for the square product of size n."""
+    layer = BY_NAME["sgemm_%d" % n]
+    x, f, _ = make_layer_inputs(layer, 1, seed)
+    return f.reshape(n, n), x.reshape(n, n)
 
 
 def make_stack_inputs(N, seed=None):
