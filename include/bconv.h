@@ -109,6 +109,13 @@ int conv_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int
 long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int stride,
                             int pad, int variant_id);
 
+/* Host-only diagnostic: the time estimate (arbitrary units, lower is better) that
+ * the selection heuristic gives (shape, variant) when the shape is not in the
+ * table; negative if the variant cannot run the shape.  Lets a tuning sweep
+ * compare the heuristic's ranking with measured times. */
+double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              int variant_id);
+
 /* Max pooling over ksz x ksz windows stepped by `stride`, no padding, floor
  * extents (the pooling primitive the paper names in Section I-A among the
  * deployment operations; used to chain the five-layer stack).

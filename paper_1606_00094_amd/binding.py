@@ -28,6 +28,7 @@ EXPORTS = {
     "conv_selected_variant": ([_i] * 9, _i),
     "conv_variant_applicable": ([_i] * 10, _i),
     "bconv_debug_audit": ([_i] * 10, ctypes.c_longlong),
+    "bconv_debug_model_cost": ([_i] * 10, ctypes.c_double),
     "maxpool_fwd": ([_vp] * 2 + [_i] * 6 + [_vp], _i),
     "bconv_strerror": ([_i], ctypes.c_char_p),
 }
@@ -158,6 +159,10 @@ def sgemm_ex(a, b, c, workspace=None, stream=None, variant=-1):
 
 def sgemm_workspace_bytes(M, N, K, variant=-1):
     return int(lib().sgemm_workspace_bytes(M, N, K, int(variant)))
+
+
+def bconv_debug_model_cost(N, C, H, W, K, R, S, stride, pad, variant):
+    return float(lib().bconv_debug_model_cost(N, C, H, W, K, R, S, stride, pad, int(variant)))
 
 
 def conv_num_variants():

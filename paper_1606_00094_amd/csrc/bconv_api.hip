@@ -4,6 +4,7 @@
 // is done on the host.
 #include <cstdint>
 #include <cstdio>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 
@@ -69,24 +70,57 @@ static int find_variant(const char* tile, int nsplit) {
   return -1;
 }
 
-// Rough time model used for shapes the table does not list: MFMA work of the
-// busiest compute unit (two resident workgroups share a unit's matrix pipes)
-// plus a fixed per-chunk and per-launch cost and the split-K round trip.
+// Time model (in clock cycles) used for shapes the table does not list.  The busiest
+// compute unit runs ceil(tiles / 256) workgroups, `resident` of them at a time;
+// each of its four matrix pipes executes its share of the waves' MFMAs back to back
+// (64 cycles each), less efficiently when a single wave has nothing to overlap its
+// own staging with; a workgroup's prologue, per-chunk barriers and epilogue are
+// hidden behind other workgroups only when several are resident.  A split reduction
+// pays a second launch and the round trip of the partial sums.
 static double model_cost(const TileDesc& v, const Plan& pl) {
   const TconvParams& p = pl.p;
-  const double cus = 256.0;
-  double tiles = (double)pl.gx * pl.gy * pl.gz;
-  int per_cu = (int)(kLdsLimitBytes / pl.lds_bytes);
-  if (per_cu > 2) per_cu = 2;
-  if (per_cu < 1) per_cu = 1;
-  double rounds = (double)(long long)((tiles + cus * per_cu - 1) / (cus * per_cu));
-  double busiest = tiles <= cus ? 1.0 : (tiles <= cus * per_cu ? (double)per_cu : rounds * per_cu);
-  double rows = (double)p.chunks_per_split * v.KR;
-  double wg_cycles = (double)v.BM() * v.BN() * rows * p.S * 2.0 / 256.0;   // at full unit rate
-  double chunk_over = 400.0 * p.chunks_per_split;
-  double t = busiest * (wg_cycles + chunk_over / per_cu) + 6000.0;
-  if (p.nsplit > 1) t += 8000.0 + (double)p.nsplit * p.out_elems * 8.0 / 2000.0;
+  const int nw = v.WM * v.WN * v.KS;
+  const int S = p.S;
+  const double steps = (double)(v.KR / 2 / v.KS) * S;                 // MFMA steps per chunk and wave
+  const double wave_mfma = (double)p.chunks_per_split * steps * v.MT * v.NT * 64.0;
+  const double tiles = (double)pl.gx * pl.gy * pl.gz;
+  // residency: LDS, wave slots, registers (accumulators + PD staging sets + addressing)
+  const int agrp = v.KR * (v.S ? v.S : kSmaxGeneric) / v.AV;
+  const int na = (v.BM() * agrp + v.NTHR() - 1) / v.NTHR();
+  const int npl = p.halo ? v.KR / p.R : v.KR;
+  const int regs = v.MT * v.NT * 16 + v.PD * (na * v.AV + npl * v.EPT) + 72;
+  int resident = (int)(kLdsLimitBytes / pl.lds_bytes);
+  const int by_regs = (512 / regs) * 4 / nw, by_waves = 32 / nw;
+  if (by_regs < resident) resident = by_regs;
+  if (by_waves < resident) resident = by_waves;
+  if (resident < 1) resident = 1;
+  const double per_cu = std::ceil(tiles / 256.0);                     // workgroups of the busiest unit
+  const double conc = std::min((double)resident, per_cu);             // of them, running together
+  const double simd_waves = std::ceil(per_cu * nw / 4.0);
+  const double depth = conc * nw / 4.0;                               // waves sharing a matrix pipe
+  const double eff = depth >= 2.0 ? 0.88 : (depth > 1.0 ? 0.82 : 0.74);
+  // every chunk ends in a barrier; the bubble is filled by other workgroups only
+  const double chunk_sync = (v.KS > 1 ? 700.0 : 450.0) / std::min(conc, 2.0);
+  const double wave_time = wave_mfma / eff + p.chunks_per_split * chunk_sync;
+  const double wg_fixed = 3500.0 + 1200.0 * v.MT * v.NT / 2.0 + (v.KS > 1 ? 3000.0 * (v.KS - 1) : 0.0);
+  const double rounds = std::ceil(per_cu / resident);
+  const double hidden = depth >= 2.0 ? 0.35 : 1.0;
+  // operand traffic from L2 into LDS, all workgroups together (bytes per cycle it can
+  // sustain, found by fitting the sweeps); part of it hides behind the MFMAs
+  const double in_words = p.halo ? (double)npl * p.plane : (double)v.KR * p.plane;
+  const double wg_bytes = (double)p.chunks_per_split * ((double)v.BM() * v.KR * S + in_words) * 4.0;
+  const double t_mem = tiles * wg_bytes / 4000.0;
+  double t = simd_waves * wave_time + 0.6 * t_mem + rounds * wg_fixed * hidden + 9000.0;
+  if (p.nsplit > 1) t += 10000.0 + 150.0 * p.nsplit + (double)(2 * p.nsplit + 2) * p.out_elems * 4.0 / 1400.0;
   return t;
+}
+
+static double variant_cost(const TileDesc& v, const Plan& pl) {
+  double c = model_cost(v, pl);
+  if (!v.S) c *= 3.0;                                   // a tile compiled for this kernel size beats the generic one
+  if (v.AV == 1) c *= 1.04;                             // four times the filter load instructions
+  if (v.BV == kModeSlots && v.R > 1 && v.S > 1 && v.STR == 1) c *= 1.12;   // an input row copy per kernel row
+  return c;
 }
 
 static int select_variant(const Shape& s, bool filt_aligned16 = true, bool in_aligned16 = true) {
@@ -110,9 +144,7 @@ static int select_variant(const Shape& s, bool filt_aligned16 = true, bool in_al
     for (int i = 0; i < kNumSplits; ++i) {
       Plan pl;
       if (!plan_tconv(s, kTiles[t], kSplits[i], &pl)) continue;
-      double c = model_cost(kTiles[t], pl);
-      if (!kTiles[t].S) c *= 3.0;          // a tile compiled for this kernel size beats the generic one
-      if (kTiles[t].AV == 4) c *= 0.97;    // wider filter loads, otherwise the same tile
+      double c = variant_cost(kTiles[t], pl);
       if (best == 0 || c < best_cost) {
         best = 1 + t * kNumSplits + i;
         best_cost = c;
@@ -397,6 +429,16 @@ long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
   if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
   return audit(s, kTiles[t], pl);
+}
+
+double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              int variant_id) {
+  Shape s;
+  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return -1.0;
+  int t, nsplit;
+  Plan pl;
+  if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return -1.0;
+  return variant_cost(kTiles[t], pl);
 }
 
 int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz, int stride,

@@ -67,13 +67,16 @@ def main():
     ap.add_argument("--table", default="gpurun_out/selection_table.inc")
     ap.add_argument("--batches", default="1,5,20,32")
     ap.add_argument("--layers", default="")
+    ap.add_argument("--extra", action="store_true",
+                    help="also sweep the shapes kept out of the table (heuristic quality check)")
     ap.add_argument("--sgemm", action="store_true", help="also sweep the square matrix products")
     ap.add_argument("--max-split", type=int, default=0, help="largest reduction split to try (0: by batch)")
     args = ap.parse_args()
     batches = [int(t) for t in args.batches.split(",")]
     names = [t for t in args.layers.split(",") if t]
     # the square matrix products (batch 1 only) are swept when named, or with --sgemm
-    pool = workloads.ALL_LAYERS + (workloads.SGEMM_LAYERS if args.sgemm or names else [])
+    pool = workloads.ALL_LAYERS + (workloads.SGEMM_LAYERS if args.sgemm or names else []) + \
+        (workloads.EXTRA_LAYERS if args.extra or names else [])
     layers = [l for l in pool if not names or l.name in names]
     results, table = [], []
     for layer in layers:
@@ -83,10 +86,18 @@ def main():
             rows = sweep_layer(layer, N, max_split=args.max_split or (4 if big else 32 if N <= 2 else 12 if N <= 8 else 6))
             good = [r for r in rows if r["ok"]]
             best = good[0] if good else None
-            results.append({"layer": layer.name, "N": N, "best": best, "all": rows})
+            # what the library would run for this shape (table row, else the heuristic)
+            dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+            chosen = binding.conv_variant_name(binding.conv_selected_variant(*dims))
+            chosen_us = next((r["us"] for r in rows if r["variant"] == chosen), None)
+            results.append({"layer": layer.name, "N": N, "best": best, "all": rows,
+                            "selected": chosen, "selected_us": chosen_us})
             print("%-18s N=%-3d best %-24s %9.2f us %7.2f TFLOP/s  (%d candidates, %d failed check)"
+                  "  selected %s %s"
                   % (layer.name, N, best["variant"] if best else "-", best["us"] if best else 0,
-                     best["tflops"] if best else 0, len(rows), len(rows) - len(good)), flush=True)
+                     best["tflops"] if best else 0, len(rows), len(rows) - len(good), chosen,
+                     "%.2f us (x%.2f)" % (chosen_us, chosen_us / best["us"]) if chosen_us and best else "-"),
+                  flush=True)
             if best:
                 tile, split = best["variant"].split("/s")
                 table.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, "%s", %s},  // %s N=%d: %.1f us'

@@ -115,6 +115,7 @@ FAMILY_SHAPES = {
     (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2), (1, 8, 27, 27, 70, 2)],
     (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0), (5, 8, 6, 6, 33, 0)],
     (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
+    (7, 7, 2): [(2, 3, 37, 41, 70, 3), (1, 3, 224, 224, 64, 3), (1, 2, 30, 29, 33, 0)],
     (0, 0, 0): [(2, 3, 9, 10, 7, 1, 2, 4, 2), (1, 5, 20, 17, 40, 3, 7, 7, 2),
                 (1, 4, 8, 8, 6, 0, 1, 1, 2), (2, 3, 12, 12, 130, 2, 3, 3, 3),
                 (1, 2, 6, 40, 3, 0, 1, 16, 1)],
@@ -139,6 +140,8 @@ def _family_of(tile):
         return (1, 1, 1)
     if tile.startswith("k11s4_"):
         return (11, 11, 4)
+    if tile.startswith("k7s2_"):
+        return (7, 7, 2)
     if tile.startswith("gen_"):
         return (0, 0, 0)
     raise KeyError(tile)
@@ -367,3 +370,18 @@ def test_sgemm_rectangular_exact_on_integers(mnk):
     assert np.array_equal(_gpu_sgemm(a, b), ref)
     assert np.array_equal(_gpu_sgemm(a, b, use_default_entry=True), ref)
     assert np.array_equal(_gpu_sgemm(a, b, variant=0), ref)          # direct kernel
+
+
+# ------------------------------------------------------------------ shapes outside the selection table
+@pytest.mark.parametrize("layer", workloads.EXTRA_LAYERS, ids=lambda l: l.name)
+def test_unlisted_shapes_heuristic_choice(layer):
+    """Layer shapes the selection table does not list (variant chosen by the heuristic),
+    batch 3, with and without ReLU, plus exact-integer data through the same variant."""
+    N = 3
+    x, f, b = workloads.make_layer_inputs(layer, N)
+    ref = oracle.conv_fwd(x, f, b, stride=layer.stride, pad=layer.pad, relu=False)
+    assert_close(gpu_conv(x, f, b, layer.stride, layer.pad, False), ref, layer.name)
+    assert_close(gpu_conv(x, f, b, layer.stride, layer.pad, True), np.maximum(ref, 0), layer.name + " relu")
+    xi, fi, bi = workloads.make_integer_problem(11, 2, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S)
+    refi = oracle.conv_fwd(xi, fi, bi, stride=layer.stride, pad=layer.pad, relu=False)
+    assert np.array_equal(gpu_conv(xi, fi, bi, layer.stride, layer.pad, False), refi)

@@ -69,22 +69,20 @@ CASES = [
     ("k11s4_96x128_k4", 2, 3, 43, 43, 96, 11, 11, 4, 0, 3),
     ("k11s4_96x64_k4", 1, 3, 51, 47, 10, 11, 11, 4, 2, 1),
     ("k3_64x64_k12_v4", 2, 8, 13, 13, 40, 3, 3, 1, 1, 1),
-    ("k3_128x256_k12_v4", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),
-    ("k3_64x256_k12", 2, 5, 13, 13, 40, 3, 3, 1, 1, 1),
+    ("k3_128x128_k12_v4", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),
+    ("k3_64x128_k12", 2, 5, 13, 13, 40, 3, 3, 1, 1, 1),
     ("k5_128x64_k8_v4", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
-    ("k5_256x128_k8", 1, 3, 27, 27, 260, 5, 5, 1, 2, 1),
+    ("k5_128x64_k8", 1, 3, 27, 27, 260, 5, 5, 1, 2, 1),
     ("pw_64x256_k16_v4", 2, 20, 14, 14, 70, 1, 1, 1, 0, 1),
     ("pw_64x256_k32_v4", 3, 68, 7, 7, 130, 1, 1, 1, 0, 2),
     ("pw_64x128_k16", 2, 6, 5, 9, 40, 1, 1, 1, 1, 1),           # pointwise with padding
     ("pw_64x128_k16_v4b4", 3, 20, 14, 14, 70, 1, 1, 1, 0, 1),   # 16-byte input loads
-    ("pw_128x128_k64_s2_v4b4", 2, 132, 6, 6, 130, 1, 1, 1, 0, 2),
-    ("k11s4_96x256_k4", 2, 3, 67, 71, 96, 11, 11, 4, 0, 1),
+    ("k11s4_96x64_k4", 2, 3, 67, 71, 96, 11, 11, 4, 0, 1),
     ("k11s4_32x128_k2", 1, 3, 51, 47, 10, 11, 11, 4, 2, 2),
-    ("k3_128x64_k12_s3_v4", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),   # reduction split inside the workgroup
-    ("k3_64x64_k12_s2", 2, 7, 13, 13, 40, 3, 3, 1, 1, 2),
-    ("k5_128x64_k20_s2_v4", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
-    ("pw_128x128_k32_s4_v4", 2, 68, 14, 14, 130, 1, 1, 1, 0, 1),
-    ("k11s4_96x128_k6_s3", 1, 3, 67, 71, 96, 11, 11, 4, 0, 1),
+    ("k3_128x64_k12_s2_v4_h", 2, 12, 13, 13, 130, 3, 3, 1, 1, 1),   # reduction split inside the workgroup
+    ("k3_64x64_k12_s2_h", 2, 7, 13, 13, 40, 3, 3, 1, 1, 2),
+    ("pw_128x128_k16_s2_v4", 2, 68, 14, 14, 130, 1, 1, 1, 0, 1),
+    ("k11s4_32x256_k6_s3", 1, 3, 67, 71, 96, 11, 11, 4, 0, 1),
     ("k3_64x64_k12_h", 2, 5, 13, 13, 40, 3, 3, 1, 1, 1),          # halo staging: one copy of the input rows
     ("k3_64x64_k12_h", 3, 13, 13, 13, 70, 3, 3, 1, 1, 2),
     ("k3_128x128_k12_v4_h", 2, 8, 13, 13, 130, 3, 3, 1, 1, 1),
@@ -97,14 +95,16 @@ CASES = [
     ("k5_64x64_k10_h", 2, 3, 11, 9, 20, 5, 5, 1, 2, 1),
     ("k5_64x128_k20_v4_h", 1, 16, 27, 27, 70, 5, 5, 1, 2, 2),
     ("k5_128x64_k20_s2_v4_h", 1, 4, 27, 27, 130, 5, 5, 1, 2, 1),
-    ("pw_64x96w_k32_s2_v4", 2, 68, 14, 14, 70, 1, 1, 1, 0, 1),        # three pixel tiles per wave
-    ("pw_96x64w_k32_s4_v4", 3, 132, 7, 7, 100, 1, 1, 1, 0, 1),       # three filter tiles per wave
-    ("pw_96x32w_k16_s2", 1, 21, 6, 6, 97, 1, 1, 1, 0, 2),
-    ("pw_32x192w_k64_s4_v4", 2, 132, 14, 14, 40, 1, 1, 1, 0, 1),
-    ("pw_96x96w_k32_s2", 2, 37, 9, 9, 200, 1, 1, 1, 0, 1),
+    ("pw_64x96w_k16_s2_v4", 2, 68, 14, 14, 70, 1, 1, 1, 0, 1),        # three pixel tiles per wave
+    ("pw_64x192w_k16_s2_v4", 3, 132, 7, 7, 100, 1, 1, 1, 0, 1),       # three filter tiles per wave
+    ("pw_64x96w_k16_s2", 1, 21, 6, 6, 97, 1, 1, 1, 0, 1),
+    ("pw_32x192w_k16_s2_v4", 2, 132, 14, 14, 40, 1, 1, 1, 0, 1),
     ("pw_64x128_k16_v4_p4", 2, 68, 14, 14, 70, 1, 1, 1, 0, 1),        # four register sets
-    ("pw_128x128_k32_s2_p4", 2, 137, 9, 9, 200, 1, 1, 1, 0, 3),
+    ("pw_64x128_k16_p4", 2, 137, 9, 9, 200, 1, 1, 1, 0, 3),
     ("k11s4_96x128_k2_p4", 1, 3, 51, 47, 96, 11, 11, 4, 0, 1),
+    ("k7s2_64x128_k2", 2, 3, 37, 41, 70, 7, 7, 2, 3, 1),            # 7x7 stride 2 with padding
+    ("k7s2_64x256_k2", 1, 3, 64, 64, 64, 7, 7, 2, 3, 2),
+    ("k7s2_64x128_k6_s3", 1, 2, 30, 29, 33, 7, 7, 2, 0, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 2, 4, 2, 1, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 3, 1, 1, 1, 1),            # S = 1, stride 1, R = 3: compact cells
     ("gen_64x64_k2", 1, 2, 12, 12, 5, 3, 3, 3, 2, 2),

@@ -45,7 +45,31 @@ SGEMM_SIZES = (128, 256, 384, 512, 768, 1024, 1536, 2048)
 # A is drawn like filters (normal, std 0.01) and B like activations (uniform[0,1)), so that
 # the convolution tolerance, which is absolute near zero, means the same thing here.
 SGEMM_LAYERS = [Layer("sgemm_%d" % n, n, 1, n, n, 1, 1, 1, 0, "u01", "n001", "none") for n in SGEMM_SIZES]
-BY_NAME = {l.name: l for l in ALL_LAYERS + SGEMM_LAYERS}
+
+# Further layer shapes of the same three networks (and a few shapes outside them:
+# stride-2 pointwise, non-square kernels) that the selection table does NOT list.
+# They exercise the selection heuristic and the generic tiles on unseen shapes.
+_E = lambda name, C, H, K, R, S, stride, pad, W=None: Layer(name, C, H, W or H, K, R, S, stride, pad,
+                                                            "u01", "n001", "u01b")
+EXTRA_LAYERS = [
+    _E("x_1x1_192x28_96", 192, 28, 96, 1, 1, 1, 0),
+    _E("x_3x3_128x28_192", 128, 28, 192, 3, 3, 1, 1),
+    _E("x_5x5_32x28_96", 32, 28, 96, 5, 5, 1, 2),
+    _E("x_3x3_112x14_224", 112, 14, 224, 3, 3, 1, 1),
+    _E("x_5x5_32x14_128", 32, 14, 128, 5, 5, 1, 2),
+    _E("x_3x3_192x7_384", 192, 7, 384, 3, 3, 1, 1),
+    _E("x_1x1_96x55_96", 96, 55, 96, 1, 1, 1, 0),
+    _E("x_3x3_384x13_1024", 384, 13, 1024, 3, 3, 1, 1),
+    _E("x_1x1_1024x6_1000", 1024, 6, 1000, 1, 1, 1, 0),
+    _E("x_7x7s2_3x224_64", 3, 224, 64, 7, 7, 2, 3),
+    _E("x_3x3_64x56_192", 64, 56, 192, 3, 3, 1, 1),
+    _E("x_1x1s2_256x28_512", 256, 28, 512, 1, 1, 2, 0),
+    _E("x_1x7_128x17_128", 128, 17, 128, 1, 7, 1, 0),
+    _E("x_7x1_128x17_128", 128, 17, 128, 7, 1, 1, 0),
+    _E("x_3x3s2_96x27_160", 96, 27, 160, 3, 3, 2, 0),
+    _E("x_5x5_13x20x31_50", 13, 20, 50, 5, 5, 1, 2, W=31),
+]
+BY_NAME = {l.name: l for l in ALL_LAYERS + SGEMM_LAYERS + EXTRA_LAYERS}
 
 
 def out_hw(layer):
@@ -72,7 +96,7 @@ def _draw(rng, dist, shape):
 
 def layer_seed(layer, N):
     """Seed of one (layer, batch) problem: base + 1000*index + N."""
-    idx = [l.name for l in ALL_LAYERS + SGEMM_LAYERS].index(layer.name)
+    idx = [l.name for l in ALL_LAYERS + SGEMM_LAYERS + EXTRA_LAYERS].index(layer.name)
     return BASE_SEED + 1000 * idx + N
 
 
