@@ -50,6 +50,29 @@ struct TconvParams {
   int out_elems;                       // N*K*P*Q
 };
 
+// Which tile a workgroup computes, from its position in dispatch order (x fastest, then
+// y, then z).  Consecutive workgroups go to the eight accelerator dies in turn, and each
+// die has its own L2; this map hands each die one contiguous run of the tile list
+// ordered (reduction split, pixel tile, filter tile), so that the workgroups that
+// share an input tile, and the filter slices of one reduction split, meet in one L2
+// instead of being fetched by all eight.  It is a bijection on the grid.
+struct BlockTile {
+  int x, y, z;        // pixel tile, filter tile, reduction split
+};
+
+BCONV_HD BlockTile xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz) {
+  const unsigned kDies = 8;
+  const unsigned total = gx * gy * gz;
+  const unsigned die = lin % kDies, slot = lin / kDies;
+  const unsigned q = total / kDies, r = total % kDies;
+  const unsigned n = die * q + (die < r ? die : r) + slot;   // position in the tile list
+  BlockTile b;
+  b.y = (int)(n % gy);
+  b.x = (int)((n / gy) % gx);
+  b.z = (int)(n / (gx * gy));
+  return b;
+}
+
 struct PixTile {
   int g0, cnt;        // first flattened pixel and number of valid pixels
   int rho0, q00;      // output row / column of the first pixel

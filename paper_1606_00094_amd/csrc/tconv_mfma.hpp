@@ -130,9 +130,11 @@ void tconv_mfma_kernel(const TconvParams p) {
   const int wm = wv / WN, wn = wv % WN;
   const int l32 = lane & 31, h = lane >> 5;
 
-  const PixTile t = pix_tile(blockIdx.x, BN, p.NPQ, p.Q);
+  const BlockTile bt = xcd_tile(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), gridDim.x,
+                                gridDim.y, gridDim.z);
+  const PixTile t = pix_tile(bt.x, BN, p.NPQ, p.Q);
   const HaloTile ht = HALO ? halo_tile(p, t) : HaloTile{0, 0};
-  const int m0 = blockIdx.y * BM;
+  const int m0 = bt.y * BM;
 
   // ---- per-thread staging cells of the input tile (fixed for the whole loop)
   int c_lds[EPT], c_pl[EPT], c_goff[EPT], c_ih0[EPT];
@@ -173,7 +175,7 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
 
-  const int z = blockIdx.z;
+  const int z = bt.z;
   const int ch_begin = z * p.chunks_per_split;
   int ch_end = ch_begin + p.chunks_per_split;
   if (ch_end > p.nchunks) ch_end = p.nchunks;

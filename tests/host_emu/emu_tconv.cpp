@@ -59,9 +59,9 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
   std::vector<float> As(abuf), Bs(bbuf);
   const int ncell = p.nrows * p.rowst;
 
-  for (unsigned bz = 0; bz < pl.gz; ++bz)
-  for (unsigned by = 0; by < pl.gy; ++by)
-  for (unsigned bx = 0; bx < pl.gx; ++bx) {
+  for (unsigned lin = 0; lin < pl.gx * pl.gy * pl.gz; ++lin) {
+    const BlockTile bt = xcd_tile(lin, pl.gx, pl.gy, pl.gz);
+    const unsigned bx = (unsigned)bt.x, by = (unsigned)bt.y, bz = (unsigned)bt.z;
     const PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
     const HaloTile ht = p.halo ? halo_tile(p, t) : HaloTile{0, 0};
     if (p.halo && ht.vr > p.vr) oob.hit("halo rows", ht.vr, p.vr);
@@ -224,4 +224,9 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
     out[i] = val;
   }
   return oob.count ? 2 + oob.count : 0;
+}
+
+extern "C" void emu_xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz, int* x, int* y, int* z) {
+  bconv::BlockTile b = bconv::xcd_tile(lin, gx, gy, gz);
+  *x = b.x; *y = b.y; *z = b.z;
 }

@@ -140,3 +140,22 @@ def test_tile_that_does_not_apply_is_refused(emu):
     x, f, b = workloads.make_integer_problem(1, 1, 2, 8, 8, 4, 5, 5)
     rc, _ = _run(emu, tile, 1, x, f, b, 1, 2, False)
     assert rc == 1
+
+
+@pytest.mark.parametrize("grid", [(183, 8, 1), (85, 6, 1), (3, 6, 8), (1, 1, 1), (5, 3, 4), (757, 1, 1), (7, 11, 3)])
+def test_block_to_tile_map_is_a_bijection_that_groups_tiles_by_die(emu, grid):
+    """Every tile of the grid is computed exactly once, and the workgroups of one die
+    (dispatch position mod 8) cover one contiguous run of the (split, pixel, filter) list."""
+    gx, gy, gz = grid
+    emu.emu_xcd_tile.argtypes = [ctypes.c_uint] * 4 + [ctypes.POINTER(ctypes.c_int)] * 3
+    emu.emu_xcd_tile.restype = None
+    seen, by_die = set(), {}
+    for lin in range(gx * gy * gz):
+        x, y, z = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        emu.emu_xcd_tile(lin, gx, gy, gz, ctypes.byref(x), ctypes.byref(y), ctypes.byref(z))
+        assert 0 <= x.value < gx and 0 <= y.value < gy and 0 <= z.value < gz
+        seen.add((x.value, y.value, z.value))
+        by_die.setdefault(lin % 8, []).append((z.value * gx + x.value) * gy + y.value)
+    assert len(seen) == gx * gy * gz
+    for die, idx in by_die.items():
+        assert idx == list(range(idx[0], idx[0] + len(idx)))
