@@ -1,7 +1,7 @@
 // Tiled MFMA forward convolution for gfx950 (CDNA4), fp32 in / fp32 accumulate.
 //
 // One workgroup computes BM filters x BN consecutive output pixels.  The main
-// loop has the shape of the paper's SGEMM template (Listing 1: barrier,
+// loop has the shape of the paper's SGEMM template (Section V: barrier,
 // cooperative global->local loads, barrier, unrolled local->register loads and
 // multiply-adds) with the register-tile FMAs replaced by
 // v_mfma_f32_32x32x2_f32 and the right-hand operand never materialised: as in
@@ -24,10 +24,13 @@
 // whose out-of-range lanes return zero (no selects for padding and tails), wide
 // LDS accesses for the filter operand, tap offsets as immediates, (c, r) of a
 // reduction row resolved at compile time where the chunk holds whole channels,
-// and a hand-made software pipeline: while chunk i is consumed from one LDS
-// buffer, the global loads of chunk i+1 are issued between the MFMAs of the first
-// steps and their LDS stores (into the other buffer) between the MFMAs of the
-// last steps; one barrier per chunk.
+// scalar addressing of the loads (per-lane offsets fixed before the loop), and a
+// hand-made software pipeline: while chunk i is consumed from one LDS buffer, the
+// global loads of chunk i+PD are issued between the MFMAs of the first steps and
+// the LDS stores of chunk i+1 (into the other buffer) between the MFMAs of the
+// last steps; one barrier per chunk.  BV selects how the input is staged (row
+// slots, one cell per pixel for S = 1 stride 1, or halo: each input row of a
+// channel once, shared by all kernel rows); PD is the number of register sets.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -46,15 +49,6 @@ template <> struct VecOf<1> { typedef float type; };
 template <> struct VecOf<2> { typedef floatx2 type; };
 template <> struct VecOf<4> { typedef floatx4 type; };
 
-// R_/S_/STR_ > 0: compile-time kernel height / width / stride (tap offsets become
-// instruction immediates); 0: taken from the argument block at run time, with
-// S <= kSmaxGeneric.  AV = 4: filter rows are fetched with 16-byte loads (the host
-// guarantees CRS % 4 == 0 and a 16-byte aligned filter pointer; KR*S % 4 == 0
-// holds by construction); AV = 1: 4-byte loads, no alignment demand.
-//
-// KS > 1 splits the reduction inside the workgroup: KS groups of WM*WN waves share
-// the staged tiles, group g consuming row pairs [g*NPAIR, (g+1)*NPAIR) of every
-// chunk, and their accumulators are summed through LDS before the epilogue.
 // Calls f(std::integral_constant<int, I>{}) for I = BEGIN .. END-1, each call its own
 // instantiation.
 template <int BEGIN, int END, class F>
@@ -66,6 +60,15 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 constexpr int cdiv_c(int a, int b) { return (a + b - 1) / b; }
 
+// R_/S_/STR_ > 0: compile-time kernel height / width / stride (tap offsets become
+// instruction immediates); 0: taken from the argument block at run time, with
+// S <= kSmaxGeneric.  AV = 4: filter rows are fetched with 16-byte loads (the host
+// guarantees CRS % 4 == 0 and a 16-byte aligned filter pointer; KR*S % 4 == 0
+// holds by construction); AV = 1: 4-byte loads, no alignment demand.
+//
+// KS > 1 splits the reduction inside the workgroup: KS groups of WM*WN waves share
+// the staged tiles, group g consuming row pairs [g*NPAIR, (g+1)*NPAIR) of every
+// chunk, and their accumulators are summed through LDS before the epilogue.
 template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV, int PD>
 __global__ __launch_bounds__(WM * WN * KS * 64)
 void tconv_mfma_kernel(const TconvParams p) {

@@ -385,3 +385,17 @@ def test_unlisted_shapes_heuristic_choice(layer):
     xi, fi, bi = workloads.make_integer_problem(11, 2, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S)
     refi = oracle.conv_fwd(xi, fi, bi, stride=layer.stride, pad=layer.pad, relu=False)
     assert np.array_equal(gpu_conv(xi, fi, bi, layer.stride, layer.pad, False), refi)
+
+
+@pytest.mark.parametrize("guard", [64, 61])
+@pytest.mark.parametrize("shape", [(2, 24, 13, 13, 40), (1, 24, 7, 9, 33)])
+def test_split_reduction_both_store_widths(shape, guard):
+    """The reduction of split partial sums runs 16 bytes wide when the output count is a
+    multiple of four and the output is 16-byte aligned, else 4 bytes wide: both are exact."""
+    N, C, H, W, K = shape
+    x, f, b = workloads.make_integer_problem(77, N, C, H, W, K, 3, 3)
+    ids = binding.variant_ids_by_name()
+    for relu in (False, True):
+        ref = oracle.conv_fwd(x, f, b, stride=1, pad=1, relu=relu)
+        for name in ("k3_64x64_k12_h/s2", "k3_64x64_k12_v4_h/s3", "k3_32x128_k12/s3"):
+            assert np.array_equal(gpu_conv(x, f, b, 1, 1, relu, variant=ids[name], guard=guard), ref), name
