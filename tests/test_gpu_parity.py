@@ -399,3 +399,36 @@ def test_split_reduction_both_store_widths(shape, guard):
         ref = oracle.conv_fwd(x, f, b, stride=1, pad=1, relu=relu)
         for name in ("k3_64x64_k12_h/s2", "k3_64x64_k12_v4_h/s3", "k3_32x128_k12/s3"):
             assert np.array_equal(gpu_conv(x, f, b, 1, 1, relu, variant=ids[name], guard=guard), ref), name
+
+
+def test_fuzz_random_variants_exact_on_integers():
+    """Seeded random (variant, shape) draws over the whole catalogue: where the variant applies,
+    the host audit is clean and the result is bitwise equal to the oracle."""
+    rng = np.random.default_rng(9416)
+    nv = binding.conv_num_variants()
+    fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2)}
+    ran = 0
+    for it in range(500):
+        v = int(rng.integers(1, nv))
+        name = binding.conv_variant_name(v)
+        prefix = name.split("_")[0]
+        if prefix == "gen":
+            R, S, stride = int(rng.integers(1, 6)), int(rng.integers(1, 6)), int(rng.integers(1, 4))
+        else:
+            R, S, stride = fam[prefix]
+        pad = int(rng.integers(0, R + 1))
+        H = int(rng.integers(max(1, R - 2 * pad), max(1, R - 2 * pad) + 16 * stride))
+        W = int(rng.integers(max(1, S - 2 * pad), max(1, S - 2 * pad) + 20 * stride))
+        N, K, C = int(rng.integers(1, 5)), int(rng.integers(1, 200)), int(rng.integers(1, 70))
+        if "_v4" in name:
+            C = 4 * max(1, C // 4)
+        if not binding.conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+            continue
+        what = "%s N%d C%d H%d W%d K%d R%d S%d s%d p%d" % (name, N, C, H, W, K, R, S, stride, pad)
+        assert binding.bconv_debug_audit(N, C, H, W, K, R, S, stride, pad, v) == 0, what
+        x, f, b = workloads.make_integer_problem(5000 + it, N, C, H, W, K, R, S)
+        relu = bool(it & 1)
+        ref = oracle.conv_fwd(x, f, b, stride=stride, pad=pad, relu=relu)
+        assert np.array_equal(gpu_conv(x, f, b, stride, pad, relu, variant=v), ref), what
+        ran += 1
+    assert ran >= 100

@@ -159,3 +159,39 @@ def test_block_to_tile_map_is_a_bijection_that_groups_tiles_by_die(emu, grid):
     assert len(seen) == gx * gy * gz
     for die, idx in by_die.items():
         assert idx == list(range(idx[0], idx[0] + len(idx)))
+
+
+def test_emulated_kernel_fuzz_over_tiles_and_shapes(emu):
+    """Seeded random (tile, shape, split) draws: whenever the planner accepts the combination
+    the emulated kernel must be free of out-of-range accesses and bitwise equal to the oracle."""
+    rng = np.random.default_rng(160600094)
+    tiles = _tiles(emu)
+    names = sorted(tiles)
+    fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2)}
+    ran = 0
+    for it in range(400):
+        name = names[int(rng.integers(len(names)))]
+        prefix = name.split("_")[0]
+        if prefix == "gen":
+            R, S, stride = int(rng.integers(1, 5)), int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        else:
+            R, S, stride = fam[prefix]
+        pad = int(rng.integers(0, R + 1))
+        lo = max(1, R - 2 * pad)
+        H = int(rng.integers(lo, lo + 12 * stride))
+        W = int(rng.integers(max(1, S - 2 * pad), max(1, S - 2 * pad) + 14 * stride))
+        N, K = int(rng.integers(1, 4)), int(rng.integers(1, 140))
+        C = int(rng.integers(1, 40))
+        if name.endswith(("_v4", "_v4_h", "_v4_p4", "_v4b4")) or "_v4" in name:
+            C = 4 * max(1, C // 4)            # 16-byte filter loads need C*R*S % 4 == 0
+        nsplit = int(rng.choice([1, 1, 2, 3, 4]))
+        x, f, b = workloads.make_integer_problem(it, N, C, H, W, K, R, S)
+        rc, got = _run(emu, tiles[name], nsplit, x, f, b, stride, pad, bool(it & 1))
+        if rc == 1:
+            continue                           # tile does not apply to this shape
+        what = "%s N%d C%d H%d W%d K%d R%d S%d s%d p%d split %d" % (name, N, C, H, W, K, R, S, stride, pad, nsplit)
+        assert rc == 0, what
+        ref = oracle.conv_fwd(x, f, b, stride=stride, pad=pad, relu=bool(it & 1))
+        assert np.array_equal(got, ref), what
+        ran += 1
+    assert ran >= 120
