@@ -116,6 +116,10 @@ FAMILY_SHAPES = {
     (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0), (5, 8, 6, 6, 33, 0)],
     (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
     (7, 7, 2): [(2, 3, 37, 41, 70, 3), (1, 3, 224, 224, 64, 3), (1, 2, 30, 29, 33, 0)],
+    (1, 1, 2): [(2, 20, 14, 14, 70, 0), (1, 36, 28, 27, 130, 0), (3, 8, 7, 9, 33, 1)],
+    (3, 3, 2): [(2, 12, 27, 27, 70, 0), (1, 8, 28, 30, 130, 1), (3, 4, 9, 7, 33, 2)],
+    (1, 7, 1): [(2, 12, 17, 17, 70, 0), (1, 8, 9, 30, 130, 3), (2, 4, 5, 11, 33, 1)],
+    (7, 1, 1): [(2, 12, 17, 17, 70, 0), (1, 6, 30, 9, 130, 3), (2, 5, 11, 5, 33, 1)],
     (0, 0, 0): [(2, 3, 9, 10, 7, 1, 2, 4, 2), (1, 5, 20, 17, 40, 3, 7, 7, 2),
                 (1, 4, 8, 8, 6, 0, 1, 1, 2), (2, 3, 12, 12, 130, 2, 3, 3, 3),
                 (1, 2, 6, 40, 3, 0, 1, 16, 1)],
@@ -142,6 +146,14 @@ def _family_of(tile):
         return (11, 11, 4)
     if tile.startswith("k7s2_"):
         return (7, 7, 2)
+    if tile.startswith("pws2_"):
+        return (1, 1, 2)
+    if tile.startswith("k3s2_"):
+        return (3, 3, 2)
+    if tile.startswith("k1x7_"):
+        return (1, 7, 1)
+    if tile.startswith("k7x1_"):
+        return (7, 1, 1)
     if tile.startswith("gen_"):
         return (0, 0, 0)
     raise KeyError(tile)
@@ -406,7 +418,8 @@ def test_fuzz_random_variants_exact_on_integers():
     the host audit is clean and the result is bitwise equal to the oracle."""
     rng = np.random.default_rng(9416)
     nv = binding.conv_num_variants()
-    fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2)}
+    fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2),
+           "pws2": (1, 1, 2), "k3s2": (3, 3, 2), "k1x7": (1, 7, 1), "k7x1": (7, 1, 1)}
     ran = 0
     for it in range(500):
         v = int(rng.integers(1, nv))

@@ -105,6 +105,14 @@ CASES = [
     ("k7s2_64x128_k2", 2, 3, 37, 41, 70, 7, 7, 2, 3, 1),            # 7x7 stride 2 with padding
     ("k7s2_64x256_k2", 1, 3, 64, 64, 64, 7, 7, 2, 3, 2),
     ("k7s2_64x128_k6_s3", 1, 2, 30, 29, 33, 7, 7, 2, 0, 1),
+    ("pws2_64x128_k16_v4", 2, 20, 14, 14, 70, 1, 1, 2, 0, 1),       # stride-2 pointwise
+    ("pws2_32x128_k16", 1, 37, 28, 27, 40, 1, 1, 2, 1, 2),
+    ("k3s2_64x64_k12_v4", 2, 12, 27, 27, 70, 3, 3, 2, 0, 1),        # 3x3 stride 2
+    ("k3s2_128x128_k12", 1, 7, 28, 30, 130, 3, 3, 2, 1, 1),
+    ("k1x7_64x128_k8_v4", 2, 12, 17, 17, 70, 1, 7, 1, 0, 1),        # one-row and one-column kernels
+    ("k1x7_32x128_k8", 1, 5, 9, 30, 20, 1, 7, 1, 3, 1),
+    ("k7x1_64x64_k14", 2, 12, 17, 17, 70, 7, 1, 1, 0, 1),
+    ("k7x1_128x128_k14", 1, 5, 30, 9, 130, 7, 1, 1, 3, 2),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 2, 4, 2, 1, 1),
     ("gen_64x64_k2", 2, 3, 9, 10, 7, 3, 1, 1, 1, 1),            # S = 1, stride 1, R = 3: compact cells
     ("gen_64x64_k2", 1, 2, 12, 12, 5, 3, 3, 3, 2, 2),
@@ -167,7 +175,8 @@ def test_emulated_kernel_fuzz_over_tiles_and_shapes(emu):
     rng = np.random.default_rng(160600094)
     tiles = _tiles(emu)
     names = sorted(tiles)
-    fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2)}
+    fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2),
+           "pws2": (1, 1, 2), "k3s2": (3, 3, 2), "k1x7": (1, 7, 1), "k7x1": (7, 1, 1)}
     ran = 0
     for it in range(400):
         name = names[int(rng.integers(len(names)))]
