@@ -15,7 +15,7 @@ namespace bconv {
 
 // ------------------------------------------------------------------ catalogue
 static const TileLaunchFn kLaunch[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD) launch_##name,
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) launch_##name,
 #include "variants.def"
 #undef X
 };

@@ -9,7 +9,7 @@ namespace bconv {
 typedef hipError_t (*TileLaunchFn)(const TconvParams& p, dim3 grid, size_t lds_bytes,
                                    hipStream_t st);
 
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD) \
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) \
   hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st);
 #include "variants.def"
 #undef X

@@ -19,14 +19,15 @@ struct TileDesc {
   int R, S, STR;            // 0 = run-time value
   int WM, WN, MT, NT, KR, EPT, AV, KS, BV;
   int PD;                   // register sets of the software pipeline (chunks in flight + 1)
+  int WPE;                  // waves per SIMD the compiler is asked to make room for (1: no demand)
   int BM() const { return WM * MT * 32; }
   int BN() const { return WN * NT * 32; }
   int NTHR() const { return WM * WN * KS * 64; }
 };
 
 static const TileDesc kTileDescs[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD) \
-  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD},
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) \
+  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE},
 #include "variants.def"
 #undef X
 };

@@ -33,10 +33,10 @@ static hipError_t launch_tile_kernel(KernelT kernel, int nthr, const TconvParams
   return e;
 }
 
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD)                                          \
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE)                                          \
   hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st) { \
     static size_t lds_allowed[64] = {0};                                                       \
-    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD>,  \
+    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE>,  \
                               WM * WN * KS * 64, p, grid, lds_bytes, st, lds_allowed);                \
   }
 #include "variants.def"

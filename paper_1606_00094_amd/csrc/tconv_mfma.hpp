@@ -66,11 +66,15 @@ constexpr int cdiv_c(int a, int b) { return (a + b - 1) / b; }
 // guarantees CRS % 4 == 0 and a 16-byte aligned filter pointer; KR*S % 4 == 0
 // holds by construction); AV = 1: 4-byte loads, no alignment demand.
 //
+// WPE > 1 asks the compiler to fit the kernel's registers for that many waves per
+// SIMD (a first-layer tile that just misses three waves otherwise runs its
+// workgroups in one and a half rounds).
+//
 // KS > 1 splits the reduction inside the workgroup: KS groups of WM*WN waves share
 // the staged tiles, group g consuming row pairs [g*NPAIR, (g+1)*NPAIR) of every
 // chunk, and their accumulators are summed through LDS before the epilogue.
-template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV, int PD>
-__global__ __launch_bounds__(WM * WN * KS * 64)
+template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV, int PD, int WPE>
+__global__ __launch_bounds__(WM * WN * KS * 64, WPE)
 void tconv_mfma_kernel(const TconvParams p) {
   constexpr int NW = WM * WN;              // waves per reduction group
   constexpr int NTHR = NW * KS * 64;
