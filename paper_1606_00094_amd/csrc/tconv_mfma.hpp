@@ -97,7 +97,14 @@ void tconv_mfma_kernel(const TconvParams p) {
                 "halo staging needs whole channels per half-chunk and reduction group");
   constexpr int RDIV = R_ > 0 ? R_ : 1;
   constexpr int NPL = HALO ? KR / RDIV : KR;           // LDS planes per input buffer
-  constexpr int NB = NPL * EPT;                        // input load items per thread (BVW words each)
+  // Flat staging (pointwise tiles whose pixel tile has fewer cells than the workgroup
+  // has threads): every thread owns one cell and stages it for the planes
+  // kl0, kl0 + PSTEP, ... with kl0 = tid / CPP, so that no thread issues masked loads.
+  constexpr int CPP = BN / BVW;                        // cells per plane of a pointwise tile
+  constexpr bool FLAT = !HALO && R_ == 1 && S_ == 1 && STR_ == 1 && CPP < NTHR && NTHR % CPP == 0 &&
+                        KR % (NTHR / CPP) == 0;
+  constexpr int PSTEP = FLAT ? NTHR / CPP : 1;
+  constexpr int NB = FLAT ? KR / PSTEP : NPL * EPT;    // input load items per thread (BVW words each)
   constexpr int NL = NA + NB;
   constexpr int VW = a_read_width(KR, S_, KS);         // words per LDS read of the filter operand
   constexpr int SW = (AV == 4) ? VW : 1;               // words per LDS store of the filter operand
@@ -146,9 +153,10 @@ void tconv_mfma_kernel(const TconvParams p) {
   // ---- per-thread staging cells of the input tile (fixed for the whole loop)
   int c_lds[EPT], c_pl[EPT], c_goff[EPT], c_ih0[EPT];
   const int ncell = p.nrows * p.rowst;
+  const int kl0 = FLAT ? tid / CPP : 0;
 #pragma unroll
   for (int i = 0; i < EPT; ++i) {
-    int e = tid + i * NTHR;
+    int e = FLAT ? tid - kl0 * CPP : tid + i * NTHR;
     const bool in_tile = e * BVW < ncell;
     BCell c = HALO ? h_cell(p, ht, in_tile ? e : 0, STR) : b_cell(p, t, in_tile ? e : 0, S, STR);
     // LDS word offset from Bs of the cell in plane 0 and the plane stride to add per
@@ -161,6 +169,11 @@ void tconv_mfma_kernel(const TconvParams p) {
     const bool never = HALO ? (c_ih0[i] == kNeverValid)
                             : (B_SCALAR && (unsigned)c_ih0[i] >= (unsigned)p.H);
     c_goff[i] = never ? (int)0x80000000u : (c.goff + p.gbias) * 4;
+    if constexpr (FLAT) {
+      // this thread's first plane folded into both offsets (the marker stays out of range)
+      c_goff[i] += kl0 * p.HW * 4;
+      c_lds[i] += kl0 * c_pl[i];
+    }
   }
 
   // ---- per-lane operand bases
@@ -282,7 +295,7 @@ void tconv_mfma_kernel(const TconvParams p) {
                                    __builtin_amdgcn_raw_buffer_load_b32(rsrc_a, voff, col0 * 4, kLoadPolicy));
       }
     } else {
-      const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
+      const int kl = FLAT ? (q - NA) * PSTEP : (q - NA) / EPT, i = FLAT ? 0 : (q - NA) % EPT;
       int c, r;
       bool ok;
       if constexpr (HALO) {
@@ -298,6 +311,8 @@ void tconv_mfma_kernel(const TconvParams p) {
       __amdgpu_buffer_rsrc_t rsrc_b;
       if constexpr (B_SCALAR) {
         // what is left of ok is the same for every lane: switch the descriptor off
+        // (flat staging: the thread's own plane offset may carry it past the last
+        // channel in the last chunk; those cells are zeroed in LDS after the store)
         const bool sok = HALO ? ok : (chok && (kk0 + kl < p.CRrows));
         voff = (unsigned)c_goff[i];
         rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.in) - p.gbias, 0, sok ? in_bytes : 0u,
@@ -342,7 +357,7 @@ void tconv_mfma_kernel(const TconvParams p) {
       }
     } else {
       float* B = Bs + buf * bbuf;
-      const int kl = (q - NA) / EPT, i = (q - NA) % EPT;
+      const int kl = FLAT ? (q - NA) * PSTEP : (q - NA) / EPT, i = FLAT ? 0 : (q - NA) % EPT;
       if constexpr (BVW == 4) {
         floatx4 v;
 #pragma unroll
@@ -357,6 +372,17 @@ void tconv_mfma_kernel(const TconvParams p) {
   // zero the filter words of chunk ch in LDS buffer buf that lie past the end of the
   // filter row (scalar addressing loads them from the next row)
   auto zero_tail = [&](int buf, int ch) {
+    if constexpr (FLAT) {
+      // flat staging: planes past the last channel were loaded from the next image
+      float* B = Bs + buf * bbuf;
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        if (ch * KR + kl0 + j * PSTEP >= p.CRrows) {
+#pragma unroll
+          for (int u = 0; u < BVW; ++u) B[j * PSTEP * c_pl[0] + c_lds[0] + u] = 0.0f;
+        }
+      }
+    }
     if constexpr (A_SCALAR) {
       float* A = As + buf * abuf;
       const int col0 = ch * KR * S;

@@ -73,6 +73,11 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
     int ch_end = ch_begin + p.chunks_per_split;
     if (ch_end > p.nchunks) ch_end = p.nchunks;
     const bool a_scalar = NA <= 12;
+    const int BVWc = (v.BV == kModeCompact4) ? 4 : 1;
+    const int CPP = BN / BVWc;
+    const bool flat = !p.halo && v.R == 1 && v.S == 1 && v.STR == 1 && CPP < NTHR && NTHR % CPP == 0 &&
+                      KR % (NTHR / CPP) == 0;
+    const int PSTEP = flat ? NTHR / CPP : 1;
     const bool has_tail = (long long)p.nchunks * KR * Sk > p.CRS;
     for (int ch = ch_begin; ch < ch_end; ++ch) {
       std::fill(As.begin(), As.end(), nanv);
@@ -129,6 +134,28 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
               float val = ok ? in[gi] : 0.0f;
               if (cell.lds < 0 || cell.lds >= p.plane) oob.hit("B lds", cell.lds, p.plane);
               else Bs[(long long)j * p.plane + cell.lds] = val;
+            }
+          }
+        } else if (flat) {
+          // flat pointwise staging: one cell per thread, planes kl0, kl0 + PSTEP, ...; the
+          // range check sees only the end of the tensor, planes past the last channel are
+          // zeroed after the store
+          const int kl0 = tid / CPP, e = tid - kl0 * CPP;
+          BCell cell = b_cell(p, t, e, Sk, STR);
+          const bool cell_ok = (unsigned)cell.ih0 < (unsigned)p.H;
+          for (int j = 0; j < KR / PSTEP; ++j) {
+            const int kl = kl0 + j * PSTEP;
+            const bool sok = (kk0 + j * PSTEP) < p.CRrows;     // the scalar part of the test
+            for (int u = 0; u < p.bv; ++u) {
+              long long gi = (long long)cell.goff + (long long)(kk0 + kl) * p.HW + u;
+              const bool ok = cell_ok && sok && gi + (p.bv - 1 - u) < in_elems;
+              if (ok && (gi < 0 || gi >= in_elems)) { oob.hit("in", gi, in_elems); continue; }
+              if (p.bv == 4 && u == 0 && ok && (gi % 4) != 0) oob.hit("in alignment", gi, 4);
+              float val = ok ? in[gi] : 0.0f;
+              if (kk0 + kl >= p.CRrows) val = 0.0f;           // tail cleanup
+              long long li = (long long)kl * p.plane + cell.lds + u;
+              if (cell.lds + u < 0 || cell.lds + u >= p.plane || kl >= KR) oob.hit("B lds", cell.lds + u, p.plane);
+              else Bs[li] = val;
             }
           }
         } else {
