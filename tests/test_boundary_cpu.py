@@ -111,3 +111,16 @@ def test_sgemm_rejects_bad_arguments_without_a_gpu():
     assert lib.sgemm(fake, fake, fake, 0, 4, 4) == -1
     assert lib.sgemm_ex(fake, fake, fake, 4, 4, 4, None, 0, None, binding.conv_num_variants()) == -6
     assert binding.sgemm_workspace_bytes(64, 64, 64, 0) == 0
+
+
+def test_every_selection_table_row_resolves_to_its_variant():
+    """A row whose tile name is missing from the catalogue, or which cannot run its shape,
+    would silently fall back to the heuristic: each row must come back as written."""
+    path = os.path.join(ROOT, "paper_1606_00094_amd", "csrc", "selection_table.inc")
+    rows = re.findall(r'\{(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), "(\w+)", (\d+)\}',
+                      open(path).read())
+    assert len(rows) >= 44
+    for row in rows:
+        dims = tuple(int(v) for v in row[:9])
+        want = "%s/s%s" % (row[9], row[10])
+        assert binding.conv_variant_name(binding.conv_selected_variant(*dims)) == want, (dims, want)
