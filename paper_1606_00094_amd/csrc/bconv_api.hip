@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <unordered_map>
 
 #include "../../include/bconv.h"
 #include "bconv_internal.h"
@@ -124,7 +125,41 @@ static double variant_cost(const TileDesc& v, const Plan& pl) {
   return c;
 }
 
+static int select_variant_uncached(const Shape& s, bool filt_aligned16, bool in_aligned16);
+
+// The choice depends only on the shape and the two alignment flags; the heuristic
+// plans every tile and split for a shape the table does not list (about a
+// millisecond for a halo family), so the answers are remembered.
+struct SelectKey {
+  int v[11];
+  bool operator==(const SelectKey& o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
+};
+struct SelectKeyHash {
+  size_t operator()(const SelectKey& k) const {
+    uint64_t h = 1469598103934665603ull;
+    for (int i = 0; i < 11; ++i) h = (h ^ (uint32_t)k.v[i]) * 1099511628211ull;
+    return (size_t)h;
+  }
+};
+static std::unordered_map<SelectKey, int, SelectKeyHash> g_select_cache;
+static std::mutex g_select_mutex;
+
 static int select_variant(const Shape& s, bool filt_aligned16 = true, bool in_aligned16 = true) {
+  const SelectKey key = {{s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, filt_aligned16 ? 1 : 0,
+                          in_aligned16 ? 1 : 0}};
+  {
+    std::lock_guard<std::mutex> lock(g_select_mutex);
+    auto it = g_select_cache.find(key);
+    if (it != g_select_cache.end()) return it->second;
+  }
+  const int id = select_variant_uncached(s, filt_aligned16, in_aligned16);
+  std::lock_guard<std::mutex> lock(g_select_mutex);
+  if (g_select_cache.size() > 4096) g_select_cache.clear();
+  g_select_cache[key] = id;
+  return id;
+}
+
+static int select_variant_uncached(const Shape& s, bool filt_aligned16, bool in_aligned16) {
   for (const TableRow* r = kTable; r->tile; ++r) {
     if (r->N == s.N && r->C == s.C && r->H == s.H && r->W == s.W && r->K == s.K && r->R == s.R &&
         r->S == s.S && r->stride == s.stride && r->pad == s.pad) {
