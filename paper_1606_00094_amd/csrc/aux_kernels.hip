@@ -115,33 +115,33 @@ hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* 
   return hipGetLastError();
 }
 
+// One (image, channel) plane per blockIdx.y (strided when there are more planes than the
+// grid allows), 256 output points of the plane per block: 32-bit index math, one division.
 __global__ __launch_bounds__(256)
 void maxpool_kernel(const float* __restrict__ in, float* __restrict__ out, int H, int W, int ksz,
-                    int stride, int P, int Q, long long total) {
-  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-       idx += (long long)gridDim.x * blockDim.x) {
-    int q = (int)(idx % Q);
-    long long t = idx / Q;
-    int p = (int)(t % P);
-    long long nc = t / P;
-    const float* src = in + nc * H * W + (long long)(p * stride) * W + q * stride;
+                    int stride, int P, int Q, int planes) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= P * Q) return;
+  const int p = o / Q, q = o - p * Q;
+  for (int nc = blockIdx.y; nc < planes; nc += gridDim.y) {
+    const float* src = in + (size_t)nc * H * W + (size_t)(p * stride) * W + q * stride;
     float m = src[0];
     for (int r = 0; r < ksz; ++r)
       for (int s = 0; s < ksz; ++s) {
         float v = src[r * W + s];
         m = v > m ? v : m;
       }
-    out[idx] = m;
+    out[(size_t)nc * P * Q + o] = m;
   }
 }
 
 hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int W, int ksz,
                           int stride, int P, int Q, hipStream_t st) {
-  long long total = (long long)N * C * P * Q;
-  long long blocks = (total + 255) / 256;
-  if (blocks > 65536 * 16) blocks = 65536 * 16;
-  hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, out, H, W, ksz,
-                     stride, P, Q, total);
+  const long long planes = (long long)N * C;
+  const unsigned gx = (unsigned)(((long long)P * Q + 255) / 256);
+  const unsigned gy = (unsigned)(planes < 65535 ? planes : 65535);
+  hipLaunchKernelGGL(maxpool_kernel, dim3(gx, gy), dim3(256), 0, st, in, out, H, W, ksz, stride, P,
+                     Q, (int)planes);
   return hipGetLastError();
 }
 

@@ -481,6 +481,7 @@ int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz
                 void* hip_stream) {
   if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || ksz <= 0 || stride <= 0) return BCONV_EINVAL;
   if (H < ksz || W < ksz) return BCONV_ESHAPE;
+  if ((long long)N * C > 0x7fffffffLL || (long long)H * W > 0x7fffffffLL) return BCONV_ESHAPE;
   if (!in || !out) return BCONV_ENULL;
   int P = (H - ksz) / stride + 1, Q = (W - ksz) / stride + 1;
   return launch_maxpool(in, out, N, C, H, W, ksz, stride, P, Q,
