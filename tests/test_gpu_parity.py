@@ -445,3 +445,32 @@ def test_fuzz_random_variants_exact_on_integers():
         assert np.array_equal(gpu_conv(x, f, b, stride, pad, relu, variant=v), ref), what
         ran += 1
     assert ran >= 100
+
+
+def test_input_beyond_two_gib_falls_back_to_64_bit_indexing():
+    """An input tensor larger than 2^31 bytes cannot use the tiled kernels' 32-bit buffer
+    offsets: the library must still compute it (direct kernel, 64-bit indexing).  The oracle
+    checks sampled outputs one window at a time."""
+    N, C, H, W, K, R, S, stride, pad = 1, 16, 6000, 6000, 2, 3, 3, 1, 0
+    assert N * C * H * W * 4 > 2 ** 31
+    assert binding.conv_variant_name(binding.conv_selected_variant(N, C, H, W, K, R, S, stride, pad)) \
+        .startswith("direct")
+    rng = np.random.default_rng(31)
+    x = rng.random((N, C, H, W), dtype=np.float32)
+    f = (rng.standard_normal((K, C, R, S), dtype=np.float32) * np.float32(0.1)).astype(np.float32)
+    b = rng.random(K, dtype=np.float32)
+    dev = torch.device("cuda:0")
+    xd, fd, bd = torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev)
+    P, Q = binding.conv_out_dims(H, W, R, S, stride, pad)
+    out = torch.full((N, K, P, Q), float("nan"), dtype=torch.float32, device=dev)
+    binding.conv_fwd(xd, fd, bd, out, stride, pad, True)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    del xd, out
+    assert not np.isnan(got).any()
+    pts = [(0, 0, 0), (K - 1, P - 1, Q - 1), (1, P - 1, 0), (0, 0, Q - 1)] + \
+          [(int(rng.integers(K)), int(rng.integers(P)), int(rng.integers(Q))) for _ in range(60)]
+    for k, p, q in pts:
+        win = np.ascontiguousarray(x[:, :, p:p + R, q:q + S])
+        ref = oracle.conv_fwd(win, f[k:k + 1], b[k:k + 1], stride=1, pad=0, relu=True)[0, 0, 0, 0]
+        assert abs(float(got[0, k, p, q]) - float(ref)) <= max(ATOL, RTOL * abs(float(ref))), (k, p, q)
