@@ -6,8 +6,7 @@ This plays the role the paper gives to its per-operation choice of variant and
 blocking constants (Section V: blocking chosen by heuristics and manual tuning,
 automated tuning named as future work; Section VI: variant per convolution).
 
-    python -m paper_1606_00094_amd.tune --out gpurun_out/tune.json \
-        --table gpurun_out/selection_table.inc
+    python -m paper_1606_00094_amd.tune --out tune.json --table selection_table.inc
 
 Each candidate is timed as a HIP graph of back-to-back launches (no host launch
 overhead in the figure) and its output is compared with the direct kernel's.
@@ -63,8 +62,8 @@ def sweep_layer(layer, N, check=True, max_split=32):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--out", default="gpurun_out/tune.json")
-    ap.add_argument("--table", default="gpurun_out/selection_table.inc")
+    ap.add_argument("--out", default="tune.json")
+    ap.add_argument("--table", default="selection_table.inc")
     ap.add_argument("--batches", default="1,5,20,32")
     ap.add_argument("--layers", default="")
     ap.add_argument("--extra", action="store_true",
