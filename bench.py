@@ -292,6 +292,21 @@ def main():
     for row in sgemm:
         log(json.dumps({"sgemm": row}))
 
+    # what the machine at hand sustains, beside the published peaks: a register-only MFMA
+    # loop through the library, and a large device-to-device copy
+    measured = None
+    if not args.no_layer_table:
+        buf = torch.empty(512 * 256, dtype=torch.float32, device="cuda:0")
+        flops = binding.bconv_debug_mfma_loop(buf, 512, 500)
+        us = graph_time_us(lambda: binding.bconv_debug_mfma_loop(buf, 512, 500), launches=4)
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        cus = graph_time_us(lambda: dst.copy_(src), launches=4)
+        measured = {"mfma_loop_tflops": round(flops / us / 1e6, 1),
+                    "copy_256mib_gbps_read_plus_write": round(2 * src.numel() * 4 / cus / 1e3, 1)}
+        del src, dst
+        log(json.dumps({"measured_peaks": measured}))
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(layers, args.cpu_baseline_batch)
@@ -307,7 +322,7 @@ def main():
                                if not args.layers else
                                "layers %s at batch %d, bias + ReLU fused" % (args.layers, args.batch),
                    "batch": args.batch, "gflop_per_step": round(total_flops / 1e9, 2)},
-        "roofline": roof, "cpu_baseline": cpu, "layers": table, "stack": stack, "sgemm": sgemm,
+        "roofline": roof, "cpu_baseline": cpu, "layers": table, "stack": stack, "sgemm": sgemm, "measured_peaks": measured,
     }), flush=True)
 
 

@@ -116,6 +116,13 @@ long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int
 double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                               int variant_id);
 
+/* Measurement aid: launches `workgroups` workgroups of 256 threads that each issue
+ * iters * 16 fp32 32x32x2 MFMAs per wave from registers only (iters * 16 * 4096 flops per
+ * wave, four waves per workgroup) and write one float per thread to `out`
+ * (workgroups * 256 floats, device memory).  Timing it gives the rate the matrix
+ * pipes sustain on the machine at hand, to put beside the published peak. */
+int bconv_debug_mfma_loop(float* out, int workgroups, int iters, void* hip_stream);
+
 /* Max pooling over ksz x ksz windows stepped by `stride`, no padding, floor
  * extents (the pooling primitive the paper names in Section I-A among the
  * deployment operations; used to chain the five-layer stack).

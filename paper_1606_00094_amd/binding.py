@@ -29,6 +29,7 @@ EXPORTS = {
     "conv_variant_applicable": ([_i] * 10, _i),
     "bconv_debug_audit": ([_i] * 10, ctypes.c_longlong),
     "bconv_debug_model_cost": ([_i] * 10, ctypes.c_double),
+    "bconv_debug_mfma_loop": ([_vp, _i, _i, _vp], _i),
     "maxpool_fwd": ([_vp] * 2 + [_i] * 6 + [_vp], _i),
     "bconv_strerror": ([_i], ctypes.c_char_p),
 }
@@ -163,6 +164,15 @@ def sgemm_workspace_bytes(M, N, K, variant=-1):
 
 def bconv_debug_model_cost(N, C, H, W, K, R, S, stride, pad, variant):
     return float(lib().bconv_debug_model_cost(N, C, H, W, K, R, S, stride, pad, int(variant)))
+
+
+def bconv_debug_mfma_loop(out, workgroups, iters, stream=None):
+    """Register-only MFMA loop; returns the flops it executes."""
+    if out.numel() < workgroups * 256:
+        raise ValueError("out needs workgroups * 256 floats")
+    _check(lib().bconv_debug_mfma_loop(_dev_ptr(out, "out"), int(workgroups), int(iters),
+                                       _stream_handle(stream)), "bconv_debug_mfma_loop")
+    return workgroups * 4 * iters * 16 * 4096
 
 
 def conv_num_variants():

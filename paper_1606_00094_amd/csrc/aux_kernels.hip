@@ -145,4 +145,30 @@ hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int 
   return hipGetLastError();
 }
 
+// Register-only MFMA loop (no memory traffic in the loop): each wave issues
+// iters * 16 v_mfma_f32_32x32x2_f32 on two independent accumulator tiles.  Used by the
+// benchmark to report what the matrix pipes sustain on the machine at hand.
+typedef float mfma_acc_t __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256)
+void mfma_loop_kernel(float* __restrict__ out, int iters) {
+  mfma_acc_t acc0, acc1;
+  for (int i = 0; i < 16; ++i) { acc0[i] = 0.0f; acc1[i] = 0.0f; }
+  const float a = 1.0f + (float)(threadIdx.x & 7), b = 0.5f + (float)(threadIdx.x & 3);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(b, a, acc1, 0, 0, 0);
+    }
+  }
+  float s = 0.0f;
+  for (int i = 0; i < 16; ++i) s += acc0[i] + acc1[i];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+hipError_t launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_loop_kernel, dim3(workgroups), dim3(256), 0, st, out, iters);
+  return hipGetLastError();
+}
+
 }  // namespace bconv

@@ -490,6 +490,14 @@ int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz
              : BCONV_ELAUNCH;
 }
 
+int bconv_debug_mfma_loop(float* out, int workgroups, int iters, void* hip_stream) {
+  if (!out) return BCONV_ENULL;
+  if (workgroups <= 0 || workgroups > 65536 || iters <= 0) return BCONV_EINVAL;
+  return launch_mfma_loop(out, workgroups, iters, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
 const char* bconv_strerror(int status) { return status_text(status); }
 
 }  // extern "C"

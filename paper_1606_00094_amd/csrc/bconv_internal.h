@@ -22,4 +22,6 @@ hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* 
 hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int W, int ksz,
                           int stride, int P, int Q, hipStream_t st);
 
+hipError_t launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st);
+
 }  // namespace bconv
