@@ -474,3 +474,15 @@ def test_input_beyond_two_gib_falls_back_to_64_bit_indexing():
         win = np.ascontiguousarray(x[:, :, p:p + R, q:q + S])
         ref = oracle.conv_fwd(win, f[k:k + 1], b[k:k + 1], stride=1, pad=0, relu=True)[0, 0, 0, 0]
         assert abs(float(got[0, k, p, q]) - float(ref)) <= max(ATOL, RTOL * abs(float(ref))), (k, p, q)
+
+
+def test_mfma_loop_measurement_aid_runs_and_validates_arguments():
+    buf = torch.zeros(8 * 256, dtype=torch.float32, device="cuda:0")
+    assert binding.bconv_debug_mfma_loop(buf, 8, 3) == 8 * 4 * 3 * 16 * 4096
+    torch.cuda.synchronize()
+    vals = buf.cpu().numpy()
+    assert np.isfinite(vals).all() and (vals > 0).all()
+    with pytest.raises(binding.BconvError):
+        binding.bconv_debug_mfma_loop(buf, 0, 3)
+    with pytest.raises(ValueError):
+        binding.bconv_debug_mfma_loop(buf, 9, 3)
