@@ -72,18 +72,22 @@ static int find_variant(const char* tile, int nsplit) {
 }
 
 // Time model (in clock cycles) used for shapes the table does not list.  The busiest
-// compute unit runs ceil(tiles / 256) workgroups, `resident` of them at a time;
-// each of its four matrix pipes executes its share of the waves' MFMAs back to back
-// (64 cycles each), less efficiently when a single wave has nothing to overlap its
-// own staging with; a workgroup's prologue, per-chunk barriers and epilogue are
-// hidden behind other workgroups only when several are resident.  A split reduction
-// pays a second launch and the round trip of the partial sums.
+// compute unit runs ceil(tiles / 256) workgroups, `resident` of them at a time, in
+// rounds.  The workgroups of a round advance chunk by chunk together: a chunk takes
+// the longer of its barrier-to-barrier latency and the MFMAs of the waves that share
+// one matrix pipe (64 cycles each; a lone wave cannot overlap its own operand reads),
+// plus the issue slots of its staging instructions.  The epilogue costs per
+// accumulator tile, and per tile and extra wave group when the reduction is split
+// inside the workgroup.  A reduction split over the grid pays a second launch and the
+// round trip of the partial sums.  The constants were fitted to the tuning sweeps of
+// the benchmark layers, the square matrix products and a set of shapes kept out of
+// the table (two-fold cross-validated between the listed and the unlisted shapes).
 static double model_cost(const TileDesc& v, const Plan& pl) {
   const TconvParams& p = pl.p;
   const int nw = v.WM * v.WN * v.KS;
   const int S = p.S;
   const double steps = (double)(v.KR / 2 / v.KS) * S;                 // MFMA steps per chunk and wave
-  const double wave_mfma = (double)p.chunks_per_split * steps * v.MT * v.NT * 64.0;
+  const double chunk_mfma = steps * v.MT * v.NT * 64.0;
   const double tiles = (double)pl.gx * pl.gy * pl.gz;
   // residency: LDS, wave slots, registers (accumulators + PD staging sets + addressing)
   const int agrp = v.KR * (v.S ? v.S : kSmaxGeneric) / v.AV;
@@ -97,31 +101,24 @@ static double model_cost(const TileDesc& v, const Plan& pl) {
   if (resident < 1) resident = 1;
   const double per_cu = std::ceil(tiles / 256.0);                     // workgroups of the busiest unit
   const double conc = std::min((double)resident, per_cu);             // of them, running together
-  const double simd_waves = std::ceil(per_cu * nw / 4.0);
-  const double depth = conc * nw / 4.0;                               // waves sharing a matrix pipe
-  const double eff = depth >= 2.0 ? 0.88 : (depth > 1.0 ? 0.82 : 0.74);
-  // every chunk ends in a barrier; the bubble is filled by other workgroups only
-  const double chunk_sync = (v.KS > 1 ? 700.0 : 450.0) / std::min(conc, 2.0);
-  const double wave_time = wave_mfma / eff + p.chunks_per_split * chunk_sync;
-  const double wg_fixed = 3500.0 + 1200.0 * v.MT * v.NT / 2.0 + (v.KS > 1 ? 3000.0 * (v.KS - 1) : 0.0);
   const double rounds = std::ceil(per_cu / resident);
-  const double hidden = depth >= 2.0 ? 0.35 : 1.0;
-  // operand traffic from L2 into LDS, all workgroups together (bytes per cycle it can
-  // sustain, found by fitting the sweeps); part of it hides behind the MFMAs
+  const double pipe_waves = std::ceil(conc * nw / 4.0);               // waves sharing a matrix pipe
+  const double eff = pipe_waves >= 2.0 ? 1.0 : 0.78;
+  // staging instructions per thread and chunk: filter loads of AV words, input cells
   const double in_words = p.halo ? (double)npl * p.plane : (double)v.KR * p.plane;
-  const double wg_bytes = (double)p.chunks_per_split * ((double)v.BM() * v.KR * S + in_words) * 4.0;
-  const double t_mem = tiles * wg_bytes / 4000.0;
-  double t = simd_waves * wave_time + 0.6 * t_mem + rounds * wg_fixed * hidden + 9000.0;
-  if (p.nsplit > 1) t += 10000.0 + 150.0 * p.nsplit + (double)(2 * p.nsplit + 2) * p.out_elems * 4.0 / 1400.0;
+  const double stage_instr = (double)v.BM() * v.KR * S / v.NTHR() / v.AV +
+                             in_words / v.NTHR() / (v.BV == kModeCompact4 ? 4.0 : 1.0);
+  const double chunk_time = std::max(300.0, pipe_waves * chunk_mfma / eff) + 80.0 * stage_instr * pipe_waves;
+  const double wg_time = p.chunks_per_split * chunk_time + 1200.0 * v.MT * v.NT +
+                         1170.0 * (v.KS - 1) * v.MT * v.NT;
+  double t = 6000.0 + rounds * wg_time;
+  if (p.nsplit > 1) t += 3900.0 + 730.0 * p.nsplit + (double)(2 * p.nsplit + 2) * p.out_elems * 4.0 / 2000.0;
   return t;
 }
 
 static double variant_cost(const TileDesc& v, const Plan& pl) {
   double c = model_cost(v, pl);
   if (!v.S) c *= 3.0;                                   // a tile compiled for this kernel size beats the generic one
-  if (v.AV == 1) c *= 1.04;                             // four times the filter load instructions
-  if (v.BV == kModeSlots && v.R > 1 && v.S > 1 && v.STR == 1) c *= 1.12;   // an input row copy per kernel row
-  if (v.BV == kModeCompact4) c *= 0.85;                 // a quarter of the input load instructions
   return c;
 }
 

@@ -105,6 +105,22 @@ CASES = [
     ("k7s2_64x128_k2", 2, 3, 37, 41, 70, 7, 7, 2, 3, 1),            # 7x7 stride 2 with padding
     ("k7s2_64x256_k2", 1, 3, 64, 64, 64, 7, 7, 2, 3, 2),
     ("k7s2_64x128_k6_s3", 1, 2, 30, 29, 33, 7, 7, 2, 0, 1),
+    ("pw_32x32_k32_s4_v4b4", 2, 100, 14, 14, 70, 1, 1, 1, 0, 1),      # fine-grained tiles, reduction split over the waves
+    ("pw_32x32_k64_s4_v4", 3, 132, 7, 7, 40, 1, 1, 1, 0, 1),
+    ("pw_32x64_k32_s2_v4b4", 2, 68, 14, 14, 70, 1, 1, 1, 0, 2),
+    ("pw_64x32_k32_s2", 1, 37, 9, 9, 100, 1, 1, 1, 0, 1),
+    ("pw_64x64_k32_s2_v4b4", 2, 68, 14, 14, 130, 1, 1, 1, 0, 1),
+    ("pw_32x32_k64_s4_v4b4", 2, 132, 14, 14, 33, 1, 1, 1, 0, 1),
+    ("pw_32x32_k128_s8_v4b4", 2, 300, 14, 14, 40, 1, 1, 1, 0, 1),
+    ("pw_32x32_k64_s8_v4", 1, 132, 7, 7, 70, 1, 1, 1, 0, 1),
+    ("pw_64x32_k64_s4_v4b4", 2, 132, 14, 14, 70, 1, 1, 1, 0, 2),
+    ("k3_32x32_k24_s4_v4_h", 2, 20, 13, 13, 70, 3, 3, 1, 1, 1),
+    ("k3_32x64_k48_s4_h", 1, 37, 13, 13, 40, 3, 3, 1, 1, 1),
+    ("k3_64x32_k24_s4_v4_h", 2, 32, 9, 11, 100, 3, 3, 1, 1, 2),
+    ("k3_32x64_k24_s4_v4_h", 1, 24, 28, 28, 70, 3, 3, 1, 1, 1),
+    ("k5_32x32_k40_s4_v4_h", 2, 16, 12, 12, 33, 5, 5, 1, 2, 1),
+    ("k5_32x64_k40_s4_h", 1, 19, 27, 27, 40, 5, 5, 1, 2, 1),
+    ("k5_32x32_k20_s2_h", 2, 7, 14, 10, 20, 5, 5, 1, 2, 1),
     ("pws2_64x128_k16_v4", 2, 20, 14, 14, 70, 1, 1, 2, 0, 1),       # stride-2 pointwise
     ("pws2_32x128_k16", 1, 37, 28, 27, 40, 1, 1, 2, 1, 2),
     ("k3s2_64x64_k12_v4", 2, 12, 27, 27, 70, 3, 3, 2, 0, 1),        # 3x3 stride 2
