@@ -135,10 +135,50 @@ void maxpool_kernel(const float* __restrict__ in, float* __restrict__ out, int H
   }
 }
 
+// The same for a window and stride fixed at compile time, PPT planes per thread: the
+// KSZ*KSZ*PPT loads of a thread are independent and all in flight together, which is what
+// a kernel with one load round trip per thread needs to approach the memory bandwidth.
+template <int KSZ, int STRIDE, int PPT>
+__global__ __launch_bounds__(256)
+void maxpool_fixed_kernel(const float* __restrict__ in, float* __restrict__ out, int H, int W, int P,
+                          int Q, int planes) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= P * Q) return;
+  const int p = o / Q, q = o - p * Q;
+  const size_t base = (size_t)(p * STRIDE) * W + q * STRIDE;
+  for (int nc0 = blockIdx.y * PPT; nc0 < planes; nc0 += gridDim.y * PPT) {
+    float m[PPT];
+#pragma unroll
+    for (int u = 0; u < PPT; ++u) {
+      const int nc = nc0 + u < planes ? nc0 + u : planes - 1;   // tail: repeat the last plane
+      const float* src = in + (size_t)nc * H * W + base;
+      m[u] = src[0];
+#pragma unroll
+      for (int r = 0; r < KSZ; ++r)
+#pragma unroll
+        for (int s = 0; s < KSZ; ++s) {
+          float v = src[r * W + s];
+          m[u] = v > m[u] ? v : m[u];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < PPT; ++u)
+      if (nc0 + u < planes) out[(size_t)(nc0 + u) * P * Q + o] = m[u];
+  }
+}
+
 hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int W, int ksz,
                           int stride, int P, int Q, hipStream_t st) {
   const long long planes = (long long)N * C;
   const unsigned gx = (unsigned)(((long long)P * Q + 255) / 256);
+  if (ksz == 3 && stride == 2 && planes >= 1024) {
+    constexpr int kPpt = 4;
+    const long long groups = (planes + kPpt - 1) / kPpt;
+    const unsigned gy = (unsigned)(groups < 65535 ? groups : 65535);
+    hipLaunchKernelGGL((maxpool_fixed_kernel<3, 2, kPpt>), dim3(gx, gy), dim3(256), 0, st, in, out, H,
+                       W, P, Q, (int)planes);
+    return hipGetLastError();
+  }
   const unsigned gy = (unsigned)(planes < 65535 ? planes : 65535);
   hipLaunchKernelGGL(maxpool_kernel, dim3(gx, gy), dim3(256), 0, st, in, out, H, W, ksz, stride, P,
                      Q, (int)planes);

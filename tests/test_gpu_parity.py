@@ -281,8 +281,9 @@ def test_split_reduction_is_deterministic_on_a_reused_workspace():
 # ------------------------------------------------------------------ max pooling and the stack
 def test_maxpool_parity():
     dev = torch.device("cuda:0")
+    # the last two run the kernel that takes four planes per thread (a ragged group of planes at the end)
     for (N, C, H, W, k, s) in [(2, 96, 55, 55, 3, 2), (1, 256, 27, 27, 3, 2), (1, 3, 7, 9, 2, 1),
-                               (2, 2, 5, 5, 5, 1)]:
+                               (2, 2, 5, 5, 5, 1), (11, 97, 27, 27, 3, 2), (32, 96, 55, 55, 3, 2)]:
         x = workloads.make_random_problem(H * W, N, C, H, W, 1, 1, 1)[0]
         ref = oracle.maxpool_fwd(x, k, s)
         out = torch.empty(ref.shape, dtype=torch.float32, device=dev)
