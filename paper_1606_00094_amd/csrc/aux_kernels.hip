@@ -76,7 +76,19 @@ void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __re
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < out_quads;
        i += gridDim.x * blockDim.x) {
     float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    for (int z = 0; z < nsplit; ++z) {
+    int z = 0;
+    // four loads in flight at a time; the additions stay in split order
+    for (; z + 4 <= nsplit; z += 4) {
+      const float4 w0 = partial[(size_t)z * out_quads + i];
+      const float4 w1 = partial[(size_t)(z + 1) * out_quads + i];
+      const float4 w2 = partial[(size_t)(z + 2) * out_quads + i];
+      const float4 w3 = partial[(size_t)(z + 3) * out_quads + i];
+      v.x += w0.x; v.y += w0.y; v.z += w0.z; v.w += w0.w;
+      v.x += w1.x; v.y += w1.y; v.z += w1.z; v.w += w1.w;
+      v.x += w2.x; v.y += w2.y; v.z += w2.z; v.w += w2.w;
+      v.x += w3.x; v.y += w3.y; v.z += w3.z; v.w += w3.w;
+    }
+    for (; z < nsplit; ++z) {
       const float4 w = partial[(size_t)z * out_quads + i];
       v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
     }
@@ -102,7 +114,7 @@ hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* 
   if (quads) {
     const int n4 = out_elems / 4;
     int blocks = (n4 + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
+    if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(splitk_reduce4_kernel, dim3(blocks), dim3(256), 0, st,
                        reinterpret_cast<const float4*>(partial), bias, reinterpret_cast<float4*>(out),
                        nsplit, n4, K, PQ, relu);
