@@ -9,6 +9,7 @@ arrays into it.
 from .conv_oracle import (  # noqa: F401
     build,
     conv_fwd,
+    conv_fwd_f16,
     conv_out_dims,
     maxpool_fwd,
     num_threads,

@@ -29,6 +29,9 @@
  *
  * oracle_sgemm (further down) is the matrix product by its definition, pinned
  * against the float64 library product, the identity and the 1x1 convolution.
+ * oracle_conv_fwd_exact leaves the result in double for storage types narrower
+ * than fp32 (half precision: rounded once by the caller); pinned by a value whose
+ * rounding through fp32 would differ, closed forms and the fp32 function.
  *
  * Pins (tests/test_oracle_*.py): printed worked-example sizes, brute-force
  * im2col x matmul on tiny inputs, delta filter, linearity, exact-integer data,
@@ -93,6 +96,53 @@ int oracle_conv_fwd(const float *in, const float *filt, const float *bias,
                     if (relu && !(v > 0.0f))
                         v = 0.0f;
                     out[(((size_t)n * K + k) * P + p) * Q + q] = v;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* The same layer with the result left in double: the exact sum (to double
+ * rounding), bias added, ReLU applied, no rounding to a storage type.  Used for
+ * half-precision storage (the paper's Section VII outlook: fp16 storage for
+ * bandwidth-limited cases, arithmetic in fp32): the caller passes the fp16
+ * tensors widened to fp32 (exact) and rounds this result to fp16 once, so the
+ * expected value is the correctly rounded exact result.  Same loop order. */
+int oracle_conv_fwd_exact(const float *in, const float *filt, const float *bias,
+                          double *out, int N, int C, int H, int W, int K, int R,
+                          int S, int stride, int pad, int relu)
+{
+    int P, Q;
+    if (!in || !filt || !out || N <= 0 || C <= 0 || K <= 0)
+        return -1;
+    if (oracle_conv_out_dims(H, W, R, S, stride, pad, &P, &Q) != 0)
+        return -1;
+
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int k = 0; k < K; ++k) {
+            for (int p = 0; p < P; ++p) {
+                for (int q = 0; q < Q; ++q) {
+                    double acc = 0.0;
+                    for (int c = 0; c < C; ++c) {
+                        for (int r = 0; r < R; ++r) {
+                            for (int s = 0; s < S; ++s) {
+                                int y = p * stride - pad + r;
+                                int x = q * stride - pad + s;
+                                if (y < 0 || y >= H || x < 0 || x >= W)
+                                    continue; /* zero padding */
+                                size_t ii = (((size_t)n * C + c) * H + y) * W + x;
+                                size_t fi = (((size_t)k * C + c) * R + r) * S + s;
+                                acc += (double)in[ii] * (double)filt[fi];
+                            }
+                        }
+                    }
+                    if (bias)
+                        acc += (double)bias[k];
+                    if (relu && !(acc > 0.0))
+                        acc = 0.0;
+                    out[(((size_t)n * K + k) * P + p) * Q + q] = acc;
                 }
             }
         }

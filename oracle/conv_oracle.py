@@ -43,6 +43,9 @@ def _load():
         lib.oracle_conv_fwd.argtypes = ([_f32p, _f32p, _f32p, _f32p]
                                         + [ctypes.c_int] * 10)
         lib.oracle_conv_fwd.restype = ctypes.c_int
+        lib.oracle_conv_fwd_exact.argtypes = ([_f32p, _f32p, _f32p, ctypes.POINTER(ctypes.c_double)]
+                                              + [ctypes.c_int] * 10)
+        lib.oracle_conv_fwd_exact.restype = ctypes.c_int
         lib.oracle_maxpool_fwd.argtypes = [_f32p, _f32p] + [ctypes.c_int] * 6
         lib.oracle_maxpool_fwd.restype = ctypes.c_int
         lib.oracle_sgemm.argtypes = [_f32p] * 3 + [ctypes.c_int] * 3
@@ -92,6 +95,32 @@ def conv_fwd(inp, filt, bias=None, stride=1, pad=0, relu=False):
     if rc != 0:
         raise ValueError("oracle_conv_fwd rejected its arguments")
     return out
+
+
+def conv_fwd_f16(inp, filt, bias=None, stride=1, pad=0, relu=False):
+    """Half-precision storage: in[N,C,H,W] and filt[K,C,R,S] are fp16, bias fp32; the
+    exact result (double accumulation, bias, ReLU) is rounded to fp16 once."""
+    inp, filt = np.asarray(inp), np.asarray(filt)
+    if inp.dtype != np.float16 or filt.dtype != np.float16:
+        raise ValueError("expected fp16 input and filters")
+    inp, filt = _as_f32(inp), _as_f32(filt)      # widening is exact
+    if inp.ndim != 4 or filt.ndim != 4 or inp.shape[1] != filt.shape[1]:
+        raise ValueError("expected in[N,C,H,W] and filt[K,C,R,S] with equal C")
+    N, C, H, W = inp.shape
+    K, _, R, S = filt.shape
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    if bias is not None:
+        bias = _as_f32(bias)
+        if bias.shape != (K,):
+            raise ValueError("bias must have shape (K,)")
+    out = np.empty((N, K, P, Q), dtype=np.float64)
+    rc = _load().oracle_conv_fwd_exact(_ptr(inp), _ptr(filt),
+                                       _ptr(bias) if bias is not None else None,
+                                       out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                       N, C, H, W, K, R, S, stride, pad, 1 if relu else 0)
+    if rc != 0:
+        raise ValueError("oracle_conv_fwd_exact rejected its arguments")
+    return out.astype(np.float16)    # one rounding, to nearest even
 
 
 def maxpool_fwd(inp, ksz=3, stride=2):

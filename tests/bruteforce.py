@@ -72,3 +72,17 @@ def maxpool_separable(inp, ksz, stride):
     for p in range(P):
         out[:, :, p, :] = rowmax[:, :, p * stride:p * stride + ksz, :].max(axis=2)
     return out
+
+
+def conv_im2col_float64(inp, filt, bias=None, stride=1, pad=0, relu=False):
+    """out[N,K,P,Q] in float64 via explicit inmat x filtsmat (library product), no
+    rounding to a storage type."""
+    N = inp.shape[0]
+    K, _, R, S = filt.shape
+    a, P, Q = im2col(inp, R, S, stride, pad)
+    om = a @ filtsmat(filt)
+    if bias is not None:
+        om = om + np.asarray(bias, dtype=np.float64)[None, :]
+    if relu:
+        om = np.maximum(om, 0.0)
+    return np.ascontiguousarray(om.reshape(N, P, Q, K).transpose(0, 3, 1, 2))

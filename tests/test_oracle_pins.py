@@ -341,3 +341,60 @@ def test_sgemm_is_the_pointwise_convolution_of_one_image():
     b = rng.standard_normal((21, 30)).astype(np.float32)
     conv = oracle.conv_fwd(b.reshape(1, 21, 1, 30), a.reshape(9, 21, 1, 1))
     assert np.array_equal(conv.reshape(9, 30), oracle.sgemm(a, b))
+
+
+# ---- half-precision storage (Section VII: smaller storage types as the next step)
+
+def test_f16_result_is_rounded_once_from_the_exact_sum():
+    # exact sum 1 + 2^-11 + 2^-30 lies just above the midpoint of the fp16 neighbours 1 and
+    # 1 + 2^-10: one rounding gives the upper one; rounding to fp32 first would drop the
+    # 2^-30, land on the midpoint and round to even, i.e. to 1
+    x = np.array([1.0, 2.0 ** -11, 2.0 ** -15], dtype=np.float16).reshape(1, 3, 1, 1)
+    f = np.array([1.0, 1.0, 2.0 ** -15], dtype=np.float16).reshape(1, 3, 1, 1)
+    out = oracle.conv_fwd_f16(x, f)
+    assert out.dtype == np.float16 and out.shape == (1, 1, 1, 1)
+    assert float(out[0, 0, 0, 0]) == 1.0 + 2.0 ** -10
+    assert float(np.float16(oracle.conv_fwd(x, f)[0, 0, 0, 0])) == 1.0
+
+
+def test_f16_all_ones_closed_form_and_round_to_even():
+    # interior value = number of taps; 2049 taps is a tie between 2048 and 2050 -> 2048
+    for C, R, expect in [(3, 11, 363.0), (96, 5, 2400.0), (2049, 1, 2048.0), (2051, 1, 2052.0)]:
+        x = np.ones((1, C, R + 2, R + 2), dtype=np.float16)
+        f = np.ones((2, C, R, R), dtype=np.float16)
+        out = oracle.conv_fwd_f16(x, f)
+        assert out.shape == (1, 2, 3, 3) and np.all(out.astype(np.float64) == expect)
+
+
+def test_f16_matches_fp32_function_where_no_rounding_happens():
+    rng = np.random.default_rng(5)
+    x = rng.integers(-3, 4, size=(2, 5, 9, 8)).astype(np.float16)
+    f = rng.integers(-2, 3, size=(4, 5, 3, 3)).astype(np.float16)
+    b = rng.integers(-4, 5, size=4).astype(np.float32)
+    for relu in (False, True):
+        ref = oracle.conv_fwd(x.astype(np.float32), f.astype(np.float32), b, 2, 1, relu)
+        assert np.abs(ref).max() < 2048          # integers this small are exact in fp16
+        got = oracle.conv_fwd_f16(x, f, b, 2, 1, relu)
+        assert np.array_equal(got.astype(np.float32), ref)
+
+
+def test_f16_bias_joins_the_sum_before_the_rounding_and_relu_after():
+    x = np.ones((1, 1, 1, 1), dtype=np.float16)
+    f = np.ones((2, 1, 1, 1), dtype=np.float16)
+    # 1 + (2^-11 + 2^-31): above the midpoint only if the bias is added before rounding
+    b = np.array([np.float32(2.0 ** -11) * np.float32(1 + 2.0 ** -20), -3.0], dtype=np.float32)
+    out = oracle.conv_fwd_f16(x, f, b, 1, 0, False).astype(np.float64).ravel()
+    assert out[0] == 1.0 + 2.0 ** -10 and out[1] == -2.0
+    out = oracle.conv_fwd_f16(x, f, b, 1, 0, True).astype(np.float64).ravel()
+    assert out[0] == 1.0 + 2.0 ** -10 and out[1] == 0.0
+
+
+def test_f16_float_data_against_float64_im2col():
+    rng = np.random.default_rng(6)
+    x = rng.uniform(0, 1, size=(2, 7, 10, 9)).astype(np.float16)
+    f = (rng.standard_normal((5, 7, 3, 3)) * 0.05).astype(np.float16)
+    b = rng.uniform(-0.1, 0.1, size=5).astype(np.float32)
+    ref = bruteforce.conv_im2col_float64(x.astype(np.float64), f.astype(np.float64),
+                                         b.astype(np.float64), 1, 1, True)
+    got = oracle.conv_fwd_f16(x, f, b, 1, 1, True)
+    assert np.array_equal(got, ref.astype(np.float16))
