@@ -6,7 +6,8 @@ at batch 32, each call = variant selection + tiled MFMA kernel (+ split
 reduction) with fused bias + ReLU, inputs already resident in HBM.  `value` is
 the algorithmic GFLOP/s of that pass (2 flops per multiply-accumulate, the
 convention of the paper's SGEMM tables).  The same JSON line carries the
-per-layer table at batch 1 and 32 with both roofline fractions, the five-layer
+per-layer table at batch 1 and 32 with both roofline fractions (and the same
+layers with half-precision storage, as context), the five-layer
 stack at batch 1/5/20/32, the roofline of the dominant kernel measured with HIP
 events, and the CPU oracle timed on the host cores as a reported baseline.
 """
@@ -30,33 +31,38 @@ def log(*a):
 class LayerProblem:
     """Device tensors of one (layer, N) problem, `copies` rotating sets."""
 
-    def __init__(self, layer, N, copies=1):
+    def __init__(self, layer, N, copies=1, half=False):
         import torch
         import workloads
         from paper_1606_00094_amd import binding, roofline
-        self.layer, self.N = layer, N
+        self.layer, self.N, self.half = layer, N, half
         dev = torch.device("cuda:0")
         x, f, b = workloads.make_layer_inputs(layer, N)
         P, Q = workloads.out_hw(layer)
         self.dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
         self.flops = roofline.conv_flops(*self.dims)
         self.bytes = roofline.conv_bytes(*self.dims)
+        if half:   # in, filt, out stored as fp16; the bias stays fp32
+            self.bytes = (self.bytes - 4 * layer.K) // 2 + 4 * layer.K
         self.variant = binding.conv_selected_variant(*self.dims)
         need = binding.conv_fwd_workspace_bytes(*self.dims, self.variant)
         self.ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
         xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
+        store = torch.float16 if half else torch.float32
+        xd, fd = xd.to(store), fd.to(store)
         self.sets = []
         for c in range(copies):
             self.sets.append((xd if c == 0 else xd.clone(), fd if c == 0 else fd.clone(), bd,
-                              torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)))
+                              torch.empty((N, layer.K, P, Q), dtype=store, device=dev)))
         self.k = 0
 
     def launch(self):
         from paper_1606_00094_amd import binding
         x, f, b, o = self.sets[self.k]
         self.k = (self.k + 1) % len(self.sets)
-        binding.conv_fwd_ex(x, f, b, o, self.layer.stride, self.layer.pad, True,
-                            workspace=self.ws, variant=self.variant)
+        fn = binding.conv_fwd_f16_ex if self.half else binding.conv_fwd_ex
+        fn(x, f, b, o, self.layer.stride, self.layer.pad, True, workspace=self.ws,
+           variant=self.variant)
 
 
 def time_launches(fn, reps, warm=3):
@@ -275,6 +281,20 @@ def main():
     for row in table:
         log(json.dumps(row))
 
+    # ---- the same layers with half-precision storage (fp32 arithmetic): same variants,
+    # half the bytes; context beside the fp32 table, not part of `value`
+    table_f16 = []
+    if not args.no_layer_table:
+        for l in layers:
+            for N in (args.batch, 1):
+                ph = LayerProblem(l, N, half=True)
+                row = layer_row(ph, graph_time_us(ph.launch, launches=10 if N > 1 else 20) * 1e-3, "warm")
+                row["storage"] = "f16"
+                table_f16.append(row)
+                del ph
+    for row in table_f16:
+        log(json.dumps(row))
+
     # ---- roofline of the dominant kernel (largest share of the step)
     dom = max(probs, key=lambda p: per_layer_ms[p.layer.name])
     dom_ms = graph_time_us(dom.launch, launches=20) * 1e-3
@@ -322,7 +342,7 @@ def main():
                                if not args.layers else
                                "layers %s at batch %d, bias + ReLU fused" % (args.layers, args.batch),
                    "batch": args.batch, "gflop_per_step": round(total_flops / 1e9, 2)},
-        "roofline": roof, "cpu_baseline": cpu, "layers": table, "stack": stack, "sgemm": sgemm, "measured_peaks": measured,
+        "roofline": roof, "cpu_baseline": cpu, "layers": table, "layers_f16_storage": table_f16, "stack": stack, "sgemm": sgemm, "measured_peaks": measured,
     }), flush=True)
 
 

@@ -72,8 +72,29 @@ int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* ou
                 int relu, void* workspace, size_t workspace_bytes, void* hip_stream,
                 int variant_id);
 
+/* The same layer with half-precision storage (Section VII names smaller storage
+ * types, half floats, as the next step for bandwidth-limited cases; the arithmetic
+ * stays fp32).  in, filt and out are DEVICE pointers to dense IEEE binary16 tensors
+ * (same NCHW / KCRS layouts, 2-byte alignment is enough); bias stays fp32 (or NULL).
+ * Elements are widened exactly, products and sums are fp32 on the matrix cores, bias
+ * and ReLU are applied in fp32 and the result is rounded to binary16 once, to nearest
+ * even.  Variant ids, the workspace size (conv_fwd_workspace_bytes: partial sums are
+ * fp32) and all error codes are those of conv_fwd / conv_fwd_ex; a pointer that is not
+ * 2-byte aligned gives BCONV_EINVAL.  A variant with 4-element loads needs 8-byte
+ * aligned in / filt here; the table's choice degrades silently to its narrow twin,
+ * a forced one gives BCONV_EVARIANT. */
+int conv_fwd_f16(const void* in, const void* filt, const float* bias, void* out,
+                 int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                 int relu);
+int conv_fwd_f16_ex(const void* in, const void* filt, const float* bias, void* out,
+                    int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                    int relu, void* workspace, size_t workspace_bytes, void* hip_stream,
+                    int variant_id);
+
 /* Bytes of workspace conv_fwd_ex needs for this shape and variant (0 if none;
- * also 0 for arguments conv_fwd_ex would reject). */
+ * also 0 for arguments conv_fwd_ex would reject).  For variant_id = -1 the figure
+ * covers the table's choice for any pointer alignment (wide loads or their narrow
+ * twins). */
 size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
                                 int stride, int pad, int variant_id);
 

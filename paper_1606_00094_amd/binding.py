@@ -19,6 +19,8 @@ EXPORTS = {
     "conv_out_dims": ([_i] * 6 + [ctypes.POINTER(_i)] * 2, _i),
     "conv_fwd": ([_vp] * 4 + [_i] * 10, _i),
     "conv_fwd_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
+    "conv_fwd_f16": ([_vp] * 4 + [_i] * 10, _i),
+    "conv_fwd_f16_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
     "conv_fwd_workspace_bytes": ([_i] * 10, _sz),
     "sgemm": ([_vp] * 3 + [_i] * 3, _i),
     "sgemm_ex": ([_vp] * 3 + [_i] * 3 + [_vp, _sz, _vp, _i], _i),
@@ -70,13 +72,14 @@ def _check(status, where):
         raise BconvError(status, where)
 
 
-def _dev_ptr(t, name):
+def _dev_ptr(t, name, half=False):
     import torch
     if t is None:
         return None
-    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32
-            and t.is_contiguous()):
-        raise TypeError("%s must be a contiguous float32 tensor on the GPU" % name)
+    want = torch.float16 if half else torch.float32
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == want and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous %s tensor on the GPU"
+                        % (name, "float16" if half else "float32"))
     return t.data_ptr()
 
 
@@ -125,6 +128,32 @@ def conv_fwd(inp, filt, bias, out, stride, pad, relu):
     _check(lib().conv_fwd(_dev_ptr(inp, "in"), _dev_ptr(filt, "filt"), _dev_ptr(bias, "bias"),
                           _dev_ptr(out, "out"), N, C, H, W, K, R, S, stride, pad,
                           1 if relu else 0), "conv_fwd")
+    return out
+
+
+def conv_fwd_f16_ex(inp, filt, bias, out, stride, pad, relu, workspace=None, stream=None,
+                    variant=-1):
+    """conv_fwd_f16_ex of the C ABI: float16 in / filt / out, float32 bias."""
+    N, C, H, W, K, R, S = _dims(inp, filt)
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    if tuple(out.shape) != (N, K, P, Q):
+        raise ValueError("out must have shape %s" % ((N, K, P, Q),))
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib().conv_fwd_f16_ex(_dev_ptr(inp, "in", True), _dev_ptr(filt, "filt", True),
+                                 _dev_ptr(bias, "bias"), _dev_ptr(out, "out", True), N, C, H, W, K,
+                                 R, S, stride, pad, 1 if relu else 0, ws_ptr, ws_bytes,
+                                 _stream_handle(stream), int(variant)), "conv_fwd_f16_ex")
+    return out
+
+
+def conv_fwd_f16(inp, filt, bias, out, stride, pad, relu):
+    """conv_fwd_f16 of the C ABI (null stream, selection table, internal workspace)."""
+    N, C, H, W, K, R, S = _dims(inp, filt)
+    _check(lib().conv_fwd_f16(_dev_ptr(inp, "in", True), _dev_ptr(filt, "filt", True),
+                              _dev_ptr(bias, "bias"), _dev_ptr(out, "out", True), N, C, H, W, K,
+                              R, S, stride, pad, 1 if relu else 0), "conv_fwd_f16")
     return out
 
 

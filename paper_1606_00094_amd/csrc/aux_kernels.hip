@@ -9,9 +9,11 @@ namespace bconv {
 
 // One thread per output point, loops over (c, r, s): the definition of the
 // paper's Section II executed literally, fp32 accumulation, 64-bit indexing.
+// T is the storage type of input, filters and output (float or _Float16).
+template <typename T>
 __global__ __launch_bounds__(256)
-void direct_conv_kernel(const float* __restrict__ in, const float* __restrict__ filt,
-                        const float* __restrict__ bias, float* __restrict__ out, Shape s,
+void direct_conv_kernel(const T* __restrict__ in, const T* __restrict__ filt,
+                        const float* __restrict__ bias, T* __restrict__ out, Shape s,
                         int relu, long long total) {
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (long long)gridDim.x * blockDim.x) {
@@ -24,38 +26,44 @@ void direct_conv_kernel(const float* __restrict__ in, const float* __restrict__ 
     const int ih0 = p * s.stride - s.pad, iw0 = q * s.stride - s.pad;
     float acc = 0.0f;
     for (int c = 0; c < s.C; ++c) {
-      const float* ip = in + ((long long)n * s.C + c) * s.H * s.W;
-      const float* fp = filt + ((long long)k * s.C + c) * s.R * s.S;
+      const T* ip = in + ((long long)n * s.C + c) * s.H * s.W;
+      const T* fp = filt + ((long long)k * s.C + c) * s.R * s.S;
       for (int r = 0; r < s.R; ++r) {
         int ih = ih0 + r;
         if (ih < 0 || ih >= s.H) continue;
         for (int ss = 0; ss < s.S; ++ss) {
           int iw = iw0 + ss;
           if (iw < 0 || iw >= s.W) continue;
-          acc = fmaf(ip[(long long)ih * s.W + iw], fp[r * s.S + ss], acc);
+          acc = fmaf((float)ip[(long long)ih * s.W + iw], (float)fp[r * s.S + ss], acc);
         }
       }
     }
     if (bias) acc += bias[k];
     if (relu) acc = acc > 0.0f ? acc : 0.0f;
-    out[idx] = acc;
+    out[idx] = (T)acc;
   }
 }
 
 hipError_t launch_direct_conv(const float* in, const float* filt, const float* bias, float* out,
-                              const Shape& s, int relu, hipStream_t st) {
+                              const Shape& s, int relu, bool f16, hipStream_t st) {
   long long total = (long long)s.N * s.K * s.P * s.Q;
   long long blocks = (total + 255) / 256;
   if (blocks > 65536 * 16) blocks = 65536 * 16;
-  hipLaunchKernelGGL(direct_conv_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, filt, bias,
-                     out, s, relu, total);
+  if (f16)
+    hipLaunchKernelGGL(direct_conv_kernel<_Float16>, dim3((unsigned)blocks), dim3(256), 0, st,
+                       reinterpret_cast<const _Float16*>(in), reinterpret_cast<const _Float16*>(filt),
+                       bias, reinterpret_cast<_Float16*>(out), s, relu, total);
+  else
+    hipLaunchKernelGGL(direct_conv_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, in, filt,
+                       bias, out, s, relu, total);
   return hipGetLastError();
 }
 
 // out[i] = act(bias[k(i)] + sum_z partial[z][i]), summed in split order.
+template <typename T>
 __global__ __launch_bounds__(256)
 void splitk_reduce_kernel(const float* __restrict__ partial, const float* __restrict__ bias,
-                          float* __restrict__ out, int nsplit, int out_elems, int K, int PQ,
+                          T* __restrict__ out, int nsplit, int out_elems, int K, int PQ,
                           int relu) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < out_elems;
        i += gridDim.x * blockDim.x) {
@@ -63,15 +71,26 @@ void splitk_reduce_kernel(const float* __restrict__ partial, const float* __rest
     for (int z = 0; z < nsplit; ++z) v += partial[(size_t)z * out_elems + i];
     if (bias) v += bias[(i / PQ) % K];
     if (relu) v = v > 0.0f ? v : 0.0f;
-    out[i] = v;
+    out[i] = (T)v;
   }
 }
 
+// Four results as stored: fp32 (16 bytes) or half precision (8 bytes).
+struct alignas(8) Half4 { _Float16 v[4]; };
+__device__ __forceinline__ void store_quad(float4* dst, const float4& v) { *dst = v; }
+__device__ __forceinline__ void store_quad(Half4* dst, const float4& v) {
+  Half4 h;
+  h.v[0] = (_Float16)v.x; h.v[1] = (_Float16)v.y; h.v[2] = (_Float16)v.z; h.v[3] = (_Float16)v.w;
+  *dst = h;
+}
+
 // The same sum four consecutive elements at a time with 16-byte accesses (out_elems % 4 == 0,
-// 16-byte aligned out and partial); the additions per element are in the same order.
+// 16-byte aligned partial, out aligned to four elements); the additions per element are in the
+// same order.  Q4 is float4 or Half4.
+template <typename Q4>
 __global__ __launch_bounds__(256)
 void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __restrict__ bias,
-                           float4* __restrict__ out, int nsplit, int out_quads, int K, int PQ,
+                           Q4* __restrict__ out, int nsplit, int out_quads, int K, int PQ,
                            int relu) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < out_quads;
        i += gridDim.x * blockDim.x) {
@@ -103,27 +122,36 @@ void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __re
       v.x = v.x > 0.0f ? v.x : 0.0f; v.y = v.y > 0.0f ? v.y : 0.0f;
       v.z = v.z > 0.0f ? v.z : 0.0f; v.w = v.w > 0.0f ? v.w : 0.0f;
     }
-    out[i] = v;
+    store_quad(out + i, v);
   }
 }
 
 hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* out, int nsplit,
-                                int out_elems, int K, int PQ, int relu, hipStream_t st) {
+                                int out_elems, int K, int PQ, int relu, bool f16, hipStream_t st) {
+  const uintptr_t out_mask = f16 ? 7 : 15;
   const bool quads = (out_elems % 4 == 0) && ((reinterpret_cast<uintptr_t>(partial) & 15) == 0) &&
-                     ((reinterpret_cast<uintptr_t>(out) & 15) == 0);
+                     ((reinterpret_cast<uintptr_t>(out) & out_mask) == 0);
   if (quads) {
     const int n4 = out_elems / 4;
     int blocks = (n4 + 255) / 256;
     if (blocks > 16384) blocks = 16384;
-    hipLaunchKernelGGL(splitk_reduce4_kernel, dim3(blocks), dim3(256), 0, st,
-                       reinterpret_cast<const float4*>(partial), bias, reinterpret_cast<float4*>(out),
-                       nsplit, n4, K, PQ, relu);
+    const float4* p4 = reinterpret_cast<const float4*>(partial);
+    if (f16)
+      hipLaunchKernelGGL(splitk_reduce4_kernel<Half4>, dim3(blocks), dim3(256), 0, st, p4, bias,
+                         reinterpret_cast<Half4*>(out), nsplit, n4, K, PQ, relu);
+    else
+      hipLaunchKernelGGL(splitk_reduce4_kernel<float4>, dim3(blocks), dim3(256), 0, st, p4, bias,
+                         reinterpret_cast<float4*>(out), nsplit, n4, K, PQ, relu);
     return hipGetLastError();
   }
   int blocks = (out_elems + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, partial, bias, out,
-                     nsplit, out_elems, K, PQ, relu);
+  if (f16)
+    hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, st, partial, bias,
+                       reinterpret_cast<_Float16*>(out), nsplit, out_elems, K, PQ, relu);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, st, partial, bias, out,
+                       nsplit, out_elems, K, PQ, relu);
   return hipGetLastError();
 }
 

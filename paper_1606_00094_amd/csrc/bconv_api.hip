@@ -20,6 +20,12 @@ static const TileLaunchFn kLaunch[] = {
 #include "variants.def"
 #undef X
 };
+// the same tiles for tensors stored in half precision
+static const TileLaunchFn kLaunchF16[] = {
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) launch_f16_##name,
+#include "variants.def"
+#undef X
+};
 static const TileDesc* const kTiles = kTileDescs;
 
 // Reduction splits offered for every tile variant.
@@ -220,15 +226,18 @@ static int internal_workspace(size_t need, void** out) {
 }
 
 // ------------------------------------------------------------------ run
+// f16: in, filt and out hold _Float16 elements (passed through float pointers); the
+// tiles' 4-element loads then need 8-byte instead of 16-byte alignment.
 static int run_conv(const float* in, const float* filt, const float* bias, float* out,
                     const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
-                    hipStream_t st, int variant_id) {
-  const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & 15u) == 0;
-  const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
+                    hipStream_t st, int variant_id, bool f16 = false) {
+  const uintptr_t vec_mask = f16 ? 7u : 15u;
+  const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & vec_mask) == 0;
+  const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & vec_mask) == 0;
   if (variant_id < 0) variant_id = select_variant(s, aligned16, in_aligned16);
   if (variant_id == 0) {
-    return launch_direct_conv(in, filt, bias, out, s, relu, st) == hipSuccess ? BCONV_OK
-                                                                              : BCONV_ELAUNCH;
+    return launch_direct_conv(in, filt, bias, out, s, relu, f16, st) == hipSuccess ? BCONV_OK
+                                                                                   : BCONV_ELAUNCH;
   }
   int t, nsplit;
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
@@ -250,10 +259,11 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
   pl.p.out = out;
   pl.p.partial = pl.ws_bytes ? static_cast<float*>(ws) : nullptr;
   pl.p.relu = relu;
-  if (kLaunch[t](pl.p, dim3(pl.gx, pl.gy, pl.gz), pl.lds_bytes, st) != hipSuccess) return BCONV_ELAUNCH;
+  if ((f16 ? kLaunchF16 : kLaunch)[t](pl.p, dim3(pl.gx, pl.gy, pl.gz), pl.lds_bytes, st) != hipSuccess)
+    return BCONV_ELAUNCH;
   if (nsplit > 1) {
     if (launch_splitk_reduce(pl.p.partial, bias, out, nsplit, pl.p.out_elems, s.K, s.P * s.Q, relu,
-                             st) != hipSuccess)
+                             f16, st) != hipSuccess)
       return BCONV_ELAUNCH;
   }
   return BCONV_OK;
@@ -391,13 +401,55 @@ int conv_fwd(const float* in, const float* filt, const float* bias, float* out, 
   return run_conv(in, filt, bias, out, s, relu, nullptr, 0, true, nullptr, -1);
 }
 
+// Half-precision storage: the same layer with in, filt and out as IEEE binary16.
+int conv_fwd_f16_ex(const void* in, const void* filt, const float* bias, void* out, int N, int C,
+                    int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                    void* workspace, size_t workspace_bytes, void* hip_stream, int variant_id) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (relu != 0 && relu != 1) return BCONV_EINVAL;
+  if (!in || !filt || !out) return BCONV_ENULL;
+  if (((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(filt) |
+        reinterpret_cast<uintptr_t>(out)) & 1u) != 0)
+    return BCONV_EINVAL;
+  if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
+  return run_conv(static_cast<const float*>(in), static_cast<const float*>(filt), bias,
+                  static_cast<float*>(out), s, relu, workspace, workspace_bytes, false,
+                  static_cast<hipStream_t>(hip_stream), variant_id, true);
+}
+
+int conv_fwd_f16(const void* in, const void* filt, const float* bias, void* out, int N, int C,
+                 int H, int W, int K, int R, int S, int stride, int pad, int relu) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (relu != 0 && relu != 1) return BCONV_EINVAL;
+  if (!in || !filt || !out) return BCONV_ENULL;
+  if (((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(filt) |
+        reinterpret_cast<uintptr_t>(out)) & 1u) != 0)
+    return BCONV_EINVAL;
+  return run_conv(static_cast<const float*>(in), static_cast<const float*>(filt), bias,
+                  static_cast<float*>(out), s, relu, nullptr, 0, true, nullptr, -1, true);
+}
+
 size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
                                 int pad, int variant_id) {
   Shape s;
   if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
-  if (variant_id < 0) variant_id = select_variant(s);
   int t, nsplit;
   Plan pl;
+  if (variant_id < 0) {
+    // the choice depends on whether in / filt allow the wide loads, which this call
+    // cannot know: enough for whichever of the four cases the pointers turn out to be
+    size_t need = 0;
+    for (int mask = 0; mask < 4; ++mask) {
+      const int id = select_variant(s, (mask & 1) != 0, (mask & 2) != 0);
+      if (decode_variant(id, &t, &nsplit) && plan_tconv(s, kTiles[t], nsplit, &pl) && pl.ws_bytes > need)
+        need = pl.ws_bytes;
+    }
+    return need;
+  }
   if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return 0;
   return pl.ws_bytes;
 }

@@ -9,16 +9,21 @@ namespace bconv {
 typedef hipError_t (*TileLaunchFn)(const TconvParams& p, dim3 grid, size_t lds_bytes,
                                    hipStream_t st);
 
+// launch_<tile>: fp32 tensors; launch_f16_<tile>: half-precision tensors behind the same
+// argument block (its float pointers then address _Float16 elements; bias and partial
+// sums stay fp32).
 #define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) \
-  hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st);
+  hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st); \
+  hipError_t launch_f16_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st);
 #include "variants.def"
 #undef X
 
 // Auxiliary kernels (aux_kernels.hip).
+// f16: in, filt and out address _Float16 elements (bias and partial sums are fp32 always).
 hipError_t launch_direct_conv(const float* in, const float* filt, const float* bias, float* out,
-                              const Shape& s, int relu, hipStream_t st);
+                              const Shape& s, int relu, bool f16, hipStream_t st);
 hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* out, int nsplit,
-                                int out_elems, int K, int PQ, int relu, hipStream_t st);
+                                int out_elems, int K, int PQ, int relu, bool f16, hipStream_t st);
 hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int W, int ksz,
                           int stride, int P, int Q, hipStream_t st);
 

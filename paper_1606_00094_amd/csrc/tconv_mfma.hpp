@@ -1,4 +1,5 @@
-// Tiled MFMA forward convolution for gfx950 (CDNA4), fp32 in / fp32 accumulate.
+// Tiled MFMA forward convolution for gfx950 (CDNA4), fp32 arithmetic; tensors stored as
+// fp32 or, with T = _Float16, as half floats widened on their way into LDS.
 //
 // One workgroup computes BM filters x BN consecutive output pixels.  The main
 // loop has the shape of the paper's SGEMM template (Section V: barrier,
@@ -73,7 +74,15 @@ constexpr int cdiv_c(int a, int b) { return (a + b - 1) / b; }
 // KS > 1 splits the reduction inside the workgroup: KS groups of WM*WN waves share
 // the staged tiles, group g consuming row pairs [g*NPAIR, (g+1)*NPAIR) of every
 // chunk, and their accumulators are summed through LDS before the epilogue.
-template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV, int PD, int WPE>
+//
+// T is the storage type of input, filters and output (float, or _Float16: the paper's
+// Section VII outlook of half-precision storage with the arithmetic left in fp32).  Half
+// elements are loaded with 2- and 8-byte accesses in place of 4 and 16, kept as raw bits
+// in the staging registers and widened when they are stored to LDS; LDS, the MFMAs and
+// the partial sums of a split reduction are fp32 either way; the result is rounded to
+// T (to nearest even) once, after bias and ReLU.
+template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV, int PD, int WPE,
+          typename T = float>
 __global__ __launch_bounds__(WM * WN * KS * 64, WPE)
 void tconv_mfma_kernel(const TconvParams p) {
   constexpr int NW = WM * WN;              // waves per reduction group
@@ -118,6 +127,11 @@ void tconv_mfma_kernel(const TconvParams p) {
   constexpr bool B_SCALAR = HALO || (R_ == 1 && S_ == 1 && STR_ == 1);
   typedef typename VecOf<VW>::type avec_t;
   typedef typename VecOf<SW>::type svec_t;
+  static_assert(sizeof(T) == 4 || sizeof(T) == 2, "fp32 or fp16 storage");
+  constexpr int ESZ = sizeof(T);                       // bytes per stored element
+  constexpr bool F16 = ESZ == 2;
+  constexpr int AVR = F16 ? (AV + 1) / 2 : AV;         // 32-bit registers per filter load item
+  constexpr int BVR = F16 ? (BVW + 1) / 2 : BVW;       // and per input load item
 
   const int R = R_ > 0 ? R_ : p.R;
   const int S = S_ > 0 ? S_ : p.S;
@@ -168,10 +182,10 @@ void tconv_mfma_kernel(const TconvParams p) {
     // does not depend on the kernel row, so it is folded into the offset here
     const bool never = HALO ? (c_ih0[i] == kNeverValid)
                             : (B_SCALAR && (unsigned)c_ih0[i] >= (unsigned)p.H);
-    c_goff[i] = never ? (int)0x80000000u : (c.goff + p.gbias) * 4;
+    c_goff[i] = never ? (int)0x80000000u : (c.goff + p.gbias) * ESZ;
     if constexpr (FLAT) {
       // this thread's first plane folded into both offsets (the marker stays out of range)
-      c_goff[i] += kl0 * p.HW * 4;
+      c_goff[i] += kl0 * p.HW * ESZ;
       c_lds[i] += kl0 * c_pl[i];
     }
   }
@@ -203,8 +217,9 @@ void tconv_mfma_kernel(const TconvParams p) {
   // PD register sets: the words of chunks i+2 .. i+PD are in flight while those of
   // chunk i+1 are being stored to LDS and chunk i is consumed
   static_assert(PD == 2 || PD == 4, "prefetch depth");
-  float ra[PD][NA * AV];
-  float rb[PD][NB * BVW];
+  // (half elements stay packed, two to a register, until they are stored to LDS)
+  float ra[PD][NA * AVR];
+  float rb[PD][NB * BVR];
 
   // Global loads go through raw buffer descriptors: a load whose offset is out of
   // range returns 0, so zero padding, ragged tails and masked lanes need no select
@@ -218,10 +233,12 @@ void tconv_mfma_kernel(const TconvParams p) {
   // handling of requests that hit a line still in flight (neighbouring kernel rows of
   // one channel, filter rows that straddle lines) only stalls the other loads.
   constexpr int kLoadPolicy = 17;
+  T* const in_base = reinterpret_cast<T*>(const_cast<float*>(p.in)) - p.gbias;
+  T* const filt_base = reinterpret_cast<T*>(const_cast<float*>(p.filt));
   const __amdgpu_buffer_rsrc_t rsrc_in = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<float*>(p.in) - p.gbias, 0, (p.N * p.CHW + p.gbias) * 4, 0x00020000);
+      in_base, 0, (p.N * p.CHW + p.gbias) * ESZ, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_filt = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<float*>(p.filt), 0, p.K * p.CRS * 4, 0x00020000);
+      filt_base, 0, p.K * p.CRS * ESZ, 0x00020000);
 
   // per-lane byte offsets of the filter load items (out-of-range marker where the
   // item lies outside the tile, the filter count or the chunk's row width)
@@ -233,11 +250,11 @@ void tconv_mfma_kernel(const TconvParams p) {
       const int m = e / AGRP;
       const int j = (e - m * AGRP) * AV;
       const bool ok = (((q + 1) * NTHR <= BM * AGRP) || (m < BM)) && (S_ > 0 || j < KRS) && (m0 + m < p.K);
-      a_voff[q] = ok ? (unsigned)(((m0 + m) * p.CRS + j) * 4) : kOob;
+      a_voff[q] = ok ? (unsigned)(((m0 + m) * p.CRS + j) * ESZ) : kOob;
     }
   }
-  const unsigned filt_bytes = (unsigned)(p.K * p.CRS * 4);
-  const unsigned in_bytes = (unsigned)((p.N * p.CHW + p.gbias) * 4);
+  const unsigned filt_bytes = (unsigned)(p.K * p.CRS * ESZ);
+  const unsigned in_bytes = (unsigned)((p.N * p.CHW + p.gbias) * ESZ);
   // the last chunk of the reduction may be narrower than KR rows: its filter words
   // past the end of the row are zeroed in LDS after they are stored
   const bool has_tail = p.nchunks * KR * S > p.CRS;
@@ -279,13 +296,20 @@ void tconv_mfma_kernel(const TconvParams p) {
         voff = a_voff[q];
         // (the range check covers per-lane plus scalar offset, so a lane of the last
         // filter row that would run past the tensor reads 0)
-        rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.filt), 0, chok ? filt_bytes : 0u,
-                                                   0x00020000);
+        rsrc_a = __builtin_amdgcn_make_buffer_rsrc(filt_base, 0, chok ? filt_bytes : 0u, 0x00020000);
       } else {
-        voff = ok ? (unsigned)(((m0 + m) * p.CRS + j) * 4) : kOob;
+        voff = ok ? (unsigned)(((m0 + m) * p.CRS + j) * ESZ) : kOob;
         rsrc_a = rsrc_filt;
       }
-      if constexpr (AV == 4) {
+      if constexpr (F16 && AV == 4) {
+        floatx2 v = __builtin_bit_cast(
+            floatx2, __builtin_amdgcn_raw_buffer_load_b64(rsrc_a, voff, col0 * ESZ, kLoadPolicy));
+        ra[SET][q * 2] = v[0];
+        ra[SET][q * 2 + 1] = v[1];
+      } else if constexpr (F16) {
+        ra[SET][q] = __builtin_bit_cast(
+            float, (unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_a, voff, col0 * ESZ, kLoadPolicy));
+      } else if constexpr (AV == 4) {
         floatx4 v = __builtin_bit_cast(
             floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, voff, col0 * 4, kLoadPolicy));
 #pragma unroll
@@ -315,13 +339,21 @@ void tconv_mfma_kernel(const TconvParams p) {
         // channel in the last chunk; those cells are zeroed in LDS after the store)
         const bool sok = HALO ? ok : (chok && (kk0 + kl < p.CRrows));
         voff = (unsigned)c_goff[i];
-        rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.in) - p.gbias, 0, sok ? in_bytes : 0u,
-                                                   0x00020000);
+        rsrc_b = __builtin_amdgcn_make_buffer_rsrc(in_base, 0, sok ? in_bytes : 0u, 0x00020000);
       } else {
         voff = ok ? (unsigned)c_goff[i] : kOob;
         rsrc_b = rsrc_in;
       }
-      if constexpr (BVW == 4) {
+      if constexpr (F16 && BVW == 4) {
+        floatx2 v = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(
+                                                    rsrc_b, voff, (c * p.HW + r * p.W) * ESZ, kLoadPolicy));
+        rb[SET][(q - NA) * 2] = v[0];
+        rb[SET][(q - NA) * 2 + 1] = v[1];
+      } else if constexpr (F16) {
+        rb[SET][q - NA] = __builtin_bit_cast(
+            float, (unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
+                       rsrc_b, voff, (c * p.HW + r * p.W) * ESZ, kLoadPolicy));
+      } else if constexpr (BVW == 4) {
         floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
                                                     rsrc_b, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
 #pragma unroll
@@ -330,6 +362,17 @@ void tconv_mfma_kernel(const TconvParams p) {
         rb[SET][q - NA] = __builtin_bit_cast(
             float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_b, voff, (c * p.HW + r * p.W) * 4, kLoadPolicy));
       }
+    }
+  };
+
+  // element u of the load item whose first register is regs[base]: the fp32 word itself,
+  // or half u of the packed pairs widened to fp32 (exact)
+  auto element = [&](const auto& regs, int base, int u) -> float {
+    if constexpr (F16) {
+      const unsigned bits = __builtin_bit_cast(unsigned, regs[base + (u >> 1)]) >> ((u & 1) * 16);
+      return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
+    } else {
+      return regs[base + u];
     }
   };
 
@@ -348,10 +391,10 @@ void tconv_mfma_kernel(const TconvParams p) {
       for (int u = 0; u < AV; u += SW) {
         svec_t v;
         if constexpr (SW == 1) {
-          v = ra[SET][q * AV + u];
+          v = element(ra[SET], q * AVR, u);
         } else {
 #pragma unroll
-          for (int w = 0; w < SW; ++w) v[w] = ra[SET][q * AV + u + w];
+          for (int w = 0; w < SW; ++w) v[w] = element(ra[SET], q * AVR, u + w);
         }
         *reinterpret_cast<svec_t*>(dst + u) = v;
       }
@@ -361,10 +404,10 @@ void tconv_mfma_kernel(const TconvParams p) {
       if constexpr (BVW == 4) {
         floatx4 v;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = rb[SET][(q - NA) * 4 + u];
+        for (int u = 0; u < 4; ++u) v[u] = element(rb[SET], (q - NA) * BVR, u);
         *reinterpret_cast<floatx4*>(B + kl * c_pl[i] + c_lds[i]) = v;
       } else {
-        B[kl * c_pl[i] + c_lds[i]] = rb[SET][q - NA];
+        B[kl * c_pl[i] + c_lds[i]] = element(rb[SET], q - NA, 0);
       }
     }
   };
@@ -592,34 +635,46 @@ void tconv_mfma_kernel(const TconvParams p) {
   // would need a device-scope release/acquire per workgroup, which on this part
   // means writing back and invalidating a whole L2 slice each time)
   const bool split = p.nsplit > 1;
-  float* const dst = split ? p.partial + (size_t)z * (size_t)p.out_elems : p.out;
+  // bias through a buffer descriptor that is empty when there is none to add (no bias,
+  // or partial sums): out-of-range loads return 0, so nothing is selected afterwards
+  const __amdgpu_buffer_rsrc_t rsrc_bias = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(p.bias), 0, (!split && p.bias) ? p.K * 4 : 0, 0x00020000);
   float bvals[MT][16];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
-      const bool ok = !split && p.bias && (k < p.K);
-      const float v = (p.bias ? p.bias : p.filt)[ok ? k : 0];
-      bvals[mt][i] = ok ? v : 0.0f;
+      bvals[mt][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_bias, k * 4, 0, 0));
     }
+  // dst: fp32 partial sums of this split, or the output tensor in its storage type
+  auto emit = [&](auto* dst) {
+    typedef std::remove_pointer_t<decltype(dst)> out_t;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
-      if (k < p.K) {
-        const float bv = bvals[mt][i];
+      for (int i = 0; i < 16; ++i) {
+        const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
+        if (k < p.K) {
+          const float bv = bvals[mt][i];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          if (colvalid[nt]) {
-            float v = acc[mt][nt][i] + bv;
-            if (!split && p.relu) v = v > 0.0f ? v : 0.0f;
-            dst[outoff[nt] + k * p.PQ] = v;
+          for (int nt = 0; nt < NT; ++nt) {
+            if (colvalid[nt]) {
+              float v = acc[mt][nt][i] + bv;
+              if (!split && p.relu) v = v > 0.0f ? v : 0.0f;
+              dst[outoff[nt] + k * p.PQ] = (out_t)v;
+            }
           }
         }
       }
     }
+  };
+  float* const part = p.partial + (split ? (size_t)z * (size_t)p.out_elems : (size_t)0);
+  if constexpr (F16) {
+    if (split) emit(part);
+    else emit(reinterpret_cast<T*>(p.out));
+  } else {
+    emit(split ? part : p.out);
   }
 }
 

@@ -63,6 +63,35 @@ def test_conv_fwd_rejects_bad_arguments_without_a_gpu():
     assert binding.strerror(-99) == "unknown status"
 
 
+def test_conv_fwd_f16_rejects_bad_arguments_without_a_gpu():
+    lib = binding.lib()
+    fake = ctypes.c_void_p(4096)   # never dereferenced: every call below fails validation
+    odd = ctypes.c_void_p(4097)
+    ok_dims = (1, 3, 8, 8, 4, 3, 3, 1, 1)
+    assert lib.conv_fwd_f16(None, fake, fake, fake, *ok_dims, 1) == -2
+    assert lib.conv_fwd_f16(fake, fake, fake, None, *ok_dims, 0) == -2
+    assert lib.conv_fwd_f16(fake, fake, fake, fake, 1, 0, 8, 8, 4, 3, 3, 1, 1, 0) == -1
+    assert lib.conv_fwd_f16(fake, fake, fake, fake, *ok_dims, 3) == -1
+    assert lib.conv_fwd_f16(fake, fake, fake, fake, 1, 3, 2, 2, 4, 5, 5, 1, 0, 0) == -3
+    # half elements need 2-byte aligned tensors
+    assert lib.conv_fwd_f16(odd, fake, fake, fake, *ok_dims, 0) == -1
+    assert lib.conv_fwd_f16(fake, odd, fake, fake, *ok_dims, 0) == -1
+    assert lib.conv_fwd_f16_ex(fake, fake, fake, odd, *ok_dims, 0, None, 0, None, -1) == -1
+    nv = binding.conv_num_variants()
+    assert lib.conv_fwd_f16_ex(fake, fake, fake, fake, *ok_dims, 0, None, 0, None, nv) == -6
+
+
+def test_default_workspace_size_covers_every_pointer_alignment():
+    """With variant -1 the choice depends on whether the pointers allow the wide loads;
+    the size query cannot know and must cover the narrow-load choices too."""
+    names = binding.variant_ids_by_name()
+    for layer in workloads.ALL_LAYERS:
+        dims = (1, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        chosen = binding.conv_selected_variant(*dims)
+        assert binding.conv_fwd_workspace_bytes(*dims, -1) >= binding.conv_fwd_workspace_bytes(*dims, chosen)
+    assert names["direct"] == 0
+
+
 def test_variant_catalogue():
     nv = binding.conv_num_variants()
     assert nv > 10

@@ -29,12 +29,18 @@ def assert_close(got, ref, what=""):
                              % (what, int(bad.sum()), bad.size, i, got[i], ref[i]))
 
 
-def gpu_conv(x, f, b, stride, pad, relu, variant=-1, use_simple_entry=False, guard=64):
+def gpu_conv(x, f, b, stride, pad, relu, variant=-1, use_simple_entry=False, guard=64, shift=0):
     """Runs the library on host arrays; returns out as numpy.  `out` sits between
-    two guard bands that must come back untouched."""
+    two guard bands that must come back untouched.  shift > 0 places in and filt that
+    many elements into their allocations (pointers aligned to 4 bytes only)."""
     dev = torch.device("cuda:0")
-    xd = torch.from_numpy(np.ascontiguousarray(x)).to(dev)
-    fd = torch.from_numpy(np.ascontiguousarray(f)).to(dev)
+
+    def put(a):
+        flat = torch.zeros(a.size + shift, dtype=torch.float32, device=dev)
+        flat[shift:] = torch.from_numpy(np.ascontiguousarray(a)).to(dev).reshape(-1)
+        return flat[shift:].view(*a.shape)
+
+    xd, fd = put(x), put(f)
     bd = torch.from_numpy(np.ascontiguousarray(b)).to(dev) if b is not None else None
     N, C, H, W = x.shape
     K, _, R, S = f.shape
@@ -398,6 +404,22 @@ def test_unlisted_shapes_heuristic_choice(layer):
     xi, fi, bi = workloads.make_integer_problem(11, 2, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S)
     refi = oracle.conv_fwd(xi, fi, bi, stride=layer.stride, pad=layer.pad, relu=False)
     assert np.array_equal(gpu_conv(xi, fi, bi, layer.stride, layer.pad, False), refi)
+
+
+def test_pointers_with_four_byte_alignment_only():
+    """in and filt one element into their allocations: the table's wide-load choice must
+    degrade to a narrow-load tile (the default workspace size covers it), a forced
+    wide-load variant must be refused."""
+    for layer in (workloads.PW_A, workloads.CONV3, workloads.RED5):
+        x, f, b, s, p = _layer_case(layer, 1)
+        ref = oracle.conv_fwd(x, f, b, stride=s, pad=p, relu=True)
+        assert_close(gpu_conv(x, f, b, s, p, True, shift=1), ref, layer.name + " shifted")
+        assert_close(gpu_conv(x, f, b, s, p, True, shift=2), ref, layer.name + " shifted by 2")
+    x, f, b, s, p = _layer_case(workloads.PW_A, 1)
+    wide = binding.variant_ids_by_name()["pw_64x64_k16_v4b4/s1"]
+    with pytest.raises(binding.BconvError) as e:
+        gpu_conv(x, f, b, s, p, True, variant=wide, shift=1)
+    assert e.value.status == -6
 
 
 @pytest.mark.parametrize("guard", [64, 61])

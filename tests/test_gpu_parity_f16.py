@@ -1,0 +1,178 @@
+"""Parity of the half-precision-storage entry points against the CPU oracle.
+
+The oracle rounds the exact result to fp16 once.  The library widens the fp16
+elements exactly, multiplies exactly (an fp16 x fp16 product fits fp32) and sums in
+fp32 on the matrix cores, then rounds to fp16 once.  The fp32 sum differs from the
+exact one by far less than half an fp16 spacing, so the two roundings land on the same
+fp16 value or on neighbours: |gpu - oracle| <= one fp16 spacing = 2^-10 * |oracle| at
+most, with the fp32 path's absolute floor of 1e-5 where the terms cancel.
+Integer-valued problems must match bit for bit: both sides round the same exact
+integer.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from paper_1606_00094_amd import binding
+from tests.test_gpu_parity import FAMILY_SHAPES, _family_of, _tile_families
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 2.0 ** -10, 1e-5
+
+
+def assert_close_f16(got, ref, what=""):
+    assert got.dtype == np.float16 and ref.dtype == np.float16
+    g, r = got.astype(np.float64), ref.astype(np.float64)
+    err = np.abs(g - r)
+    lim = np.maximum(ATOL, RTOL * np.abs(r))
+    bad = err > lim
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - lim), err.shape)
+        raise AssertionError("%s: %d of %d elements out of tolerance; worst at %s: got %r ref %r"
+                             % (what, int(bad.sum()), bad.size, i, got[i], ref[i]))
+
+
+def gpu_conv_f16(x, f, b, stride, pad, relu, variant=-1, use_simple_entry=False, guard=64,
+                 shift=0):
+    """Runs the fp16 entry point on host arrays; `out` sits between guard bands that must
+    come back untouched.  shift > 0 places in and filt `shift` elements into their
+    allocations (2-byte aligned pointers only)."""
+    dev = torch.device("cuda:0")
+
+    def put(a):
+        flat = torch.zeros(a.size + shift, dtype=torch.float16, device=dev)
+        flat[shift:] = torch.from_numpy(np.ascontiguousarray(a)).to(dev).reshape(-1)
+        return flat[shift:].view(*a.shape)
+
+    xd, fd = put(x), put(f)
+    bd = torch.from_numpy(np.ascontiguousarray(b)).to(dev) if b is not None else None
+    N, C, H, W = x.shape
+    K, _, R, S = f.shape
+    P, Q = binding.conv_out_dims(H, W, R, S, stride, pad)
+    n_out = N * K * P * Q
+    canary = 1234.5
+    buf = torch.full((n_out + 2 * guard,), canary, dtype=torch.float16, device=dev)
+    out = buf[guard:guard + n_out].view(N, K, P, Q)
+    if use_simple_entry:
+        torch.cuda.synchronize()
+        binding.conv_fwd_f16(xd, fd, bd, out, stride, pad, relu)
+    else:
+        ws = None
+        need = binding.conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant)
+        if need:
+            ws = torch.zeros((need + 3) // 4, dtype=torch.float32, device=dev)
+        binding.conv_fwd_f16_ex(xd, fd, bd, out, stride, pad, relu, workspace=ws, variant=variant)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert (host[:guard] == np.float16(canary)).all() and \
+        (host[guard + n_out:] == np.float16(canary)).all(), "store outside the output tensor"
+    return host[guard:guard + n_out].reshape(N, K, P, Q).copy()
+
+
+def _layer_case(layer, N):
+    """The benchmark layer's fp32 tensors rounded to fp16 (that rounding is the data's,
+    not the method's); the bias stays fp32."""
+    x, f, b = workloads.make_layer_inputs(layer, N)
+    return x.astype(np.float16), f.astype(np.float16), b, layer.stride, layer.pad
+
+
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS, ids=lambda l: l.name)
+def test_f16_benchmark_layers_batch1(layer):
+    x, f, b, s, p = _layer_case(layer, 1)
+    for relu in (False, True):
+        ref = oracle.conv_fwd_f16(x, f, b, stride=s, pad=p, relu=relu)
+        got = gpu_conv_f16(x, f, b, s, p, relu)
+        assert_close_f16(got, ref, "%s relu=%d" % (layer.name, relu))
+
+
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS[1:], ids=lambda l: l.name)
+def test_f16_benchmark_layers_batch32_sampled_images(layer):
+    N = 32
+    x, f, b, s, p = _layer_case(layer, N)
+    for relu in (False, True):
+        got = gpu_conv_f16(x, f, b, s, p, relu)
+        for n in (0, 13, 31):
+            ref = oracle.conv_fwd_f16(x[n:n + 1], f, b, stride=s, pad=p, relu=relu)
+            assert_close_f16(got[n:n + 1], ref, "%s N=32 image %d relu=%d" % (layer.name, n, relu))
+        assert np.isfinite(got).all()
+
+
+def test_f16_simple_entry_direct_kernel_and_missing_bias():
+    for layer in (workloads.TOY, workloads.PW_B):
+        x, f, b, s, p = _layer_case(layer, 1)
+        ref = oracle.conv_fwd_f16(x, f, b, stride=s, pad=p, relu=True)
+        assert_close_f16(gpu_conv_f16(x, f, b, s, p, True, use_simple_entry=True), ref, layer.name)
+        assert_close_f16(gpu_conv_f16(x, f, b, s, p, True, variant=0), ref, layer.name + " direct")
+        ref = oracle.conv_fwd_f16(x, f, None, stride=s, pad=p, relu=False)
+        assert_close_f16(gpu_conv_f16(x, f, None, s, p, False), ref, layer.name + " no bias")
+
+
+@pytest.mark.parametrize("tile", sorted(_tile_families()))
+def test_f16_every_tile_variant_exact_on_integers(tile):
+    """Each compiled tile in its fp16 instantiation, unsplit and with every applicable
+    reduction split, on shapes with ragged tails: bitwise equal to the oracle."""
+    fam = _family_of(tile)
+    ran = 0
+    for shp in FAMILY_SHAPES[fam]:
+        if fam == (0, 0, 0):
+            N, C, H, W, K, pad, R, S, stride = shp
+        else:
+            N, C, H, W, K, pad = shp
+            R, S, stride = fam
+        x, f, b = workloads.make_integer_problem(len(tile) + sum(shp), N, C, H, W, K, R, S)
+        x, f = x.astype(np.float16), f.astype(np.float16)
+        ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=False)
+        for v in _tile_families()[tile]:
+            if not binding.conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+                continue
+            got = gpu_conv_f16(x, f, b, stride, pad, False, variant=v)
+            assert np.array_equal(got, ref), "%s on %s" % (binding.conv_variant_name(v), (shp,))
+            ran += 1
+    assert ran > 0
+
+
+def test_f16_pointers_with_two_byte_alignment_only():
+    """in and filt one element into their allocations: the table's 4-element-load choice
+    must degrade to its narrow twin, a forced wide variant must be refused."""
+    for layer in (workloads.PW_A, workloads.CONV3, workloads.RED5):
+        x, f, b, s, p = _layer_case(layer, 1)
+        ref = oracle.conv_fwd_f16(x, f, b, stride=s, pad=p, relu=True)
+        assert_close_f16(gpu_conv_f16(x, f, b, s, p, True, shift=1), ref, layer.name + " shifted")
+    layer = workloads.PW_A
+    x, f, b, s, p = _layer_case(layer, 1)
+    wide = binding.variant_ids_by_name()["pw_64x64_k16_v4b4/s1"]
+    with pytest.raises(binding.BconvError) as e:
+        gpu_conv_f16(x, f, b, s, p, True, variant=wide, shift=1)
+    assert e.value.status == -6
+
+
+def test_f16_split_reduction_both_store_widths():
+    # out_elems % 4 == 0 and != 0; the second through an output pointer 2 bytes off 8
+    for (N, C, H, W, K, R, pad, tile) in [(1, 64, 8, 8, 40, 3, 1, "k3_64x64_k12_h/s4"),
+                                          (1, 64, 7, 7, 33, 3, 1, "k3_64x64_k12_h/s4"),
+                                          (1, 96, 6, 6, 40, 1, 0, "pw_64x64_k16/s3")]:
+        x, f, b = workloads.make_random_problem(N * C + H, N, C, H, W, K, R, R)
+        x, f = x.astype(np.float16), f.astype(np.float16)
+        v = binding.variant_ids_by_name()[tile]
+        ref = oracle.conv_fwd_f16(x, f, b, stride=1, pad=pad, relu=True)
+        for guard in (64, 63):
+            got = gpu_conv_f16(x, f, b, 1, pad, True, variant=v, guard=guard)
+            assert_close_f16(got, ref, "%s guard %d" % (tile, guard))
+
+
+def test_f16_rejects_odd_pointers_and_float32_tensors():
+    dev = torch.device("cuda:0")
+    x = torch.zeros((1, 4, 5, 5), dtype=torch.float16, device=dev)
+    f = torch.zeros((3, 4, 3, 3), dtype=torch.float16, device=dev)
+    out = torch.zeros((1, 3, 3, 3), dtype=torch.float16, device=dev)
+    with pytest.raises(TypeError):
+        binding.conv_fwd_f16(x.float(), f, None, out, 1, 0, False)
+    rc = binding.lib().conv_fwd_f16(ctypes.c_void_p(x.data_ptr() + 1), f.data_ptr(), None,
+                                    out.data_ptr(), 1, 4, 5, 5, 3, 3, 3, 1, 0, 0)
+    assert rc == -1
+    torch.cuda.synchronize()
