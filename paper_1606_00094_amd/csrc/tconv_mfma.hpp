@@ -209,6 +209,27 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
 
+  const bool split = p.nsplit > 1;
+  // bias through a buffer descriptor that is empty when there is none to add (no bias,
+  // or partial sums): out-of-range loads return 0, so nothing is selected afterwards.
+  // A tile with one accumulator row per wave fetches its 16 values here, ahead of the
+  // main loop, so that a workgroup that runs alone (small batches) does not end on an
+  // exposed memory round trip; larger tiles keep the registers free and load at the end.
+  constexpr bool BIAS_EARLY = (MT == 1);
+  const __amdgpu_buffer_rsrc_t rsrc_bias = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(p.bias), 0, (!split && p.bias) ? p.K * 4 : 0, 0x00020000);
+  float bvals[MT][16];
+  auto load_bias = [&]() {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
+        bvals[mt][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_bias, k * 4, 0, 0));
+      }
+  };
+  if constexpr (BIAS_EARLY) load_bias();
+
   const int z = bt.z;
   const int ch_begin = z * p.chunks_per_split;
   int ch_end = ch_begin + p.chunks_per_split;
@@ -634,19 +655,7 @@ void tconv_mfma_kernel(const TconvParams p) {
   // partial tiles are summed by a second kernel: exchanging them inside this one
   // would need a device-scope release/acquire per workgroup, which on this part
   // means writing back and invalidating a whole L2 slice each time)
-  const bool split = p.nsplit > 1;
-  // bias through a buffer descriptor that is empty when there is none to add (no bias,
-  // or partial sums): out-of-range loads return 0, so nothing is selected afterwards
-  const __amdgpu_buffer_rsrc_t rsrc_bias = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<float*>(p.bias), 0, (!split && p.bias) ? p.K * 4 : 0, 0x00020000);
-  float bvals[MT][16];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
-      bvals[mt][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_bias, k * 4, 0, 0));
-    }
+  if constexpr (!BIAS_EARLY) load_bias();
   // dst: fp32 partial sums of this split, or the output tensor in its storage type
   auto emit = [&](auto* dst) {
     typedef std::remove_pointer_t<decltype(dst)> out_t;
