@@ -378,14 +378,28 @@ int conv_out_dims(int H, int W, int R, int S, int stride, int pad, int* P, int* 
   return BCONV_OK;
 }
 
+// Argument checks shared by the four convolution entry points (elem_bytes: 4 for
+// fp32 tensors, 2 for half precision, whose pointers must be 2-byte aligned).
+static int check_conv_args(const void* in, const void* filt, const void* out, int N, int C, int H,
+                           int W, int K, int R, int S, int stride, int pad, int relu,
+                           int elem_bytes, Shape* s) {
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, s);
+  if (rc != BCONV_OK) return rc;
+  if (relu != 0 && relu != 1) return BCONV_EINVAL;
+  if (!in || !filt || !out) return BCONV_ENULL;
+  if (elem_bytes == 2 &&
+      ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(filt) |
+        reinterpret_cast<uintptr_t>(out)) & 1u) != 0)
+    return BCONV_EINVAL;
+  return BCONV_OK;
+}
+
 int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* out, int N, int C,
                 int H, int W, int K, int R, int S, int stride, int pad, int relu, void* workspace,
                 size_t workspace_bytes, void* hip_stream, int variant_id) {
   Shape s;
-  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 4, &s);
   if (rc != BCONV_OK) return rc;
-  if (relu != 0 && relu != 1) return BCONV_EINVAL;
-  if (!in || !filt || !out) return BCONV_ENULL;
   if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
   return run_conv(in, filt, bias, out, s, relu, workspace, workspace_bytes, false,
                   static_cast<hipStream_t>(hip_stream), variant_id);
@@ -394,10 +408,8 @@ int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* ou
 int conv_fwd(const float* in, const float* filt, const float* bias, float* out, int N, int C,
              int H, int W, int K, int R, int S, int stride, int pad, int relu) {
   Shape s;
-  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 4, &s);
   if (rc != BCONV_OK) return rc;
-  if (relu != 0 && relu != 1) return BCONV_EINVAL;
-  if (!in || !filt || !out) return BCONV_ENULL;
   return run_conv(in, filt, bias, out, s, relu, nullptr, 0, true, nullptr, -1);
 }
 
@@ -406,13 +418,8 @@ int conv_fwd_f16_ex(const void* in, const void* filt, const float* bias, void* o
                     int H, int W, int K, int R, int S, int stride, int pad, int relu,
                     void* workspace, size_t workspace_bytes, void* hip_stream, int variant_id) {
   Shape s;
-  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 2, &s);
   if (rc != BCONV_OK) return rc;
-  if (relu != 0 && relu != 1) return BCONV_EINVAL;
-  if (!in || !filt || !out) return BCONV_ENULL;
-  if (((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(filt) |
-        reinterpret_cast<uintptr_t>(out)) & 1u) != 0)
-    return BCONV_EINVAL;
   if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
   return run_conv(static_cast<const float*>(in), static_cast<const float*>(filt), bias,
                   static_cast<float*>(out), s, relu, workspace, workspace_bytes, false,
@@ -422,13 +429,8 @@ int conv_fwd_f16_ex(const void* in, const void* filt, const float* bias, void* o
 int conv_fwd_f16(const void* in, const void* filt, const float* bias, void* out, int N, int C,
                  int H, int W, int K, int R, int S, int stride, int pad, int relu) {
   Shape s;
-  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 2, &s);
   if (rc != BCONV_OK) return rc;
-  if (relu != 0 && relu != 1) return BCONV_EINVAL;
-  if (!in || !filt || !out) return BCONV_ENULL;
-  if (((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(filt) |
-        reinterpret_cast<uintptr_t>(out)) & 1u) != 0)
-    return BCONV_EINVAL;
   return run_conv(static_cast<const float*>(in), static_cast<const float*>(filt), bias,
                   static_cast<float*>(out), s, relu, nullptr, 0, true, nullptr, -1, true);
 }
