@@ -65,8 +65,10 @@ __global__ __launch_bounds__(256)
 void splitk_reduce_kernel(const float* __restrict__ partial, const float* __restrict__ bias,
                           T* __restrict__ out, int nsplit, int out_elems, int K, int PQ,
                           int relu) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < out_elems;
-       i += gridDim.x * blockDim.x) {
+  // (64-bit counter: i + stride may pass 2^31 when out_elems is close to it)
+  for (long long i64 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i64 < out_elems;
+       i64 += (long long)gridDim.x * blockDim.x) {
+    const int i = (int)i64;
     float v = 0.0f;
     for (int z = 0; z < nsplit; ++z) v += partial[(size_t)z * out_elems + i];
     if (bias) v += bias[(i / PQ) % K];
@@ -92,8 +94,9 @@ __global__ __launch_bounds__(256)
 void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __restrict__ bias,
                            Q4* __restrict__ out, int nsplit, int out_quads, int K, int PQ,
                            int relu) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < out_quads;
-       i += gridDim.x * blockDim.x) {
+  for (long long i64 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i64 < out_quads;
+       i64 += (long long)gridDim.x * blockDim.x) {
+    const int i = (int)i64;
     float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     int z = 0;
     // four loads in flight at a time; the additions stay in split order
@@ -163,7 +166,7 @@ void maxpool_kernel(const float* __restrict__ in, float* __restrict__ out, int H
   const int o = blockIdx.x * blockDim.x + threadIdx.x;
   if (o >= P * Q) return;
   const int p = o / Q, q = o - p * Q;
-  for (int nc = blockIdx.y; nc < planes; nc += gridDim.y) {
+  for (long long nc = blockIdx.y; nc < planes; nc += gridDim.y) {
     const float* src = in + (size_t)nc * H * W + (size_t)(p * stride) * W + q * stride;
     float m = src[0];
     for (int r = 0; r < ksz; ++r)
@@ -186,11 +189,11 @@ void maxpool_fixed_kernel(const float* __restrict__ in, float* __restrict__ out,
   if (o >= P * Q) return;
   const int p = o / Q, q = o - p * Q;
   const size_t base = (size_t)(p * STRIDE) * W + q * STRIDE;
-  for (int nc0 = blockIdx.y * PPT; nc0 < planes; nc0 += gridDim.y * PPT) {
+  for (long long nc0 = (long long)blockIdx.y * PPT; nc0 < planes; nc0 += (long long)gridDim.y * PPT) {
     float m[PPT];
 #pragma unroll
     for (int u = 0; u < PPT; ++u) {
-      const int nc = nc0 + u < planes ? nc0 + u : planes - 1;   // tail: repeat the last plane
+      const long long nc = nc0 + u < planes ? nc0 + u : planes - 1;   // tail: repeat the last plane
       const float* src = in + (size_t)nc * H * W + base;
       m[u] = src[0];
 #pragma unroll
