@@ -134,7 +134,8 @@ def run_sgemm(n):
 
 
 def run_stack(N, reps):
-    """Five-layer stack with 3x3/s2 max pooling after the first two layers."""
+    """Five-layer stack with 3x3/s2 max pooling after the first two layers (those two
+    through the convolution + pooling call)."""
     import torch
     import workloads
     from paper_1606_00094_amd import binding, roofline
@@ -147,29 +148,25 @@ def run_stack(N, reps):
         dims = (n, c, h, w, layer.K, layer.R, layer.S, layer.stride, layer.pad)
         P, Q = binding.conv_out_dims(h, w, layer.R, layer.S, layer.stride, layer.pad)
         v = binding.conv_selected_variant(*dims)
-        need = binding.conv_fwd_workspace_bytes(*dims, v)
+        pooled = li in workloads.STACK_POOL_AFTER
+        need = (binding.conv_pool_fwd_workspace_bytes if pooled else binding.conv_fwd_workspace_bytes)(*dims, v)
         ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
-        out = torch.empty((n, layer.K, P, Q), dtype=torch.float32, device=dev)
-        plan.append(("conv", len(bufs) - 1, len(bufs), torch.from_numpy(f).to(dev),
-                     torch.from_numpy(b).to(dev), layer, ws, v))
+        shape = (n, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1) if pooled else (n, layer.K, P, Q)
+        out = torch.empty(shape, dtype=torch.float32, device=dev)
+        plan.append((len(bufs) - 1, len(bufs), torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev),
+                     layer, ws, v, pooled))
         bufs.append(out)
         flops += roofline.conv_flops(*dims)
         cur_shape = out.shape
-        if li in workloads.STACK_POOL_AFTER:
-            pooled = torch.empty((n, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1),
-                                 dtype=torch.float32, device=dev)
-            plan.append(("pool", len(bufs) - 1, len(bufs)))
-            bufs.append(pooled)
-            cur_shape = pooled.shape
 
     def step():
-        for op in plan:
-            if op[0] == "conv":
-                _, i, o, f, b, layer, ws, v = op
+        for i, o, f, b, layer, ws, v, pooled in plan:
+            if pooled:
+                binding.conv_pool_fwd_ex(bufs[i], f, b, bufs[o], layer.stride, layer.pad, True, 3, 2, ws,
+                                         variant=v)
+            else:
                 binding.conv_fwd_ex(bufs[i], f, b, bufs[o], layer.stride, layer.pad, True,
                                     workspace=ws, variant=v)
-            else:
-                binding.maxpool_fwd(bufs[op[1]], bufs[op[2]], 3, 2)
 
     ms = graph_time_us(step, launches=reps) * 1e-3
     return {"N": N, "ms": round(ms, 4), "gflops": round(flops / (ms * 1e-3) / 1e9, 1),

@@ -137,6 +137,26 @@ long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int
 double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                               int variant_id);
 
+/* Convolution + bias + optional ReLU followed by max pooling (window pool_ksz, step
+ * pool_stride, no padding, floor extents) in one call: the next operation of the
+ * chain in the networks the paper draws its layers from (Section I-A lists pooling
+ * among the deployment primitives).  out is the POOLED tensor N*K*PP*PQ with
+ * PP = floor((P-pool_ksz)/pool_stride)+1; the unpooled result is never written to
+ * `out`.  When the variant splits the reduction the pooling is folded into the
+ * reduction kernel (two kernels in all instead of three); otherwise the convolution
+ * writes to the workspace and a pooling kernel follows.  Values are those of
+ * conv_fwd_ex followed by maxpool_fwd, bit for bit.
+ *   workspace: at least conv_pool_fwd_workspace_bytes(...) bytes, 256-byte aligned,
+ *     always needed.  variant_id as for conv_fwd_ex.
+ * Errors as conv_fwd_ex, plus BCONV_EINVAL for a non-positive window or step and
+ * BCONV_ESHAPE when the window is larger than the convolution's output. */
+int conv_pool_fwd_ex(const float* in, const float* filt, const float* bias, float* out,
+                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                     int relu, int pool_ksz, int pool_stride, void* workspace,
+                     size_t workspace_bytes, void* hip_stream, int variant_id);
+size_t conv_pool_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
+                                     int stride, int pad, int variant_id);
+
 /* Measurement aid: launches `workgroups` workgroups of 256 threads that each issue
  * iters * 16 fp32 32x32x2 MFMAs per wave from registers only (iters * 16 * 4096 flops per
  * wave, four waves per workgroup) and write one float per thread to `out`

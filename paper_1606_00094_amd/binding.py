@@ -22,6 +22,8 @@ EXPORTS = {
     "conv_fwd_f16": ([_vp] * 4 + [_i] * 10, _i),
     "conv_fwd_f16_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
     "conv_fwd_workspace_bytes": ([_i] * 10, _sz),
+    "conv_pool_fwd_ex": ([_vp] * 4 + [_i] * 12 + [_vp, _sz, _vp, _i], _i),
+    "conv_pool_fwd_workspace_bytes": ([_i] * 10, _sz),
     "sgemm": ([_vp] * 3 + [_i] * 3, _i),
     "sgemm_ex": ([_vp] * 3 + [_i] * 3 + [_vp, _sz, _vp, _i], _i),
     "sgemm_workspace_bytes": ([_i] * 4, _sz),
@@ -155,6 +157,29 @@ def conv_fwd_f16(inp, filt, bias, out, stride, pad, relu):
                               _dev_ptr(bias, "bias"), _dev_ptr(out, "out", True), N, C, H, W, K,
                               R, S, stride, pad, 1 if relu else 0), "conv_fwd_f16")
     return out
+
+
+def conv_pool_fwd_ex(inp, filt, bias, out, stride, pad, relu, pool_ksz, pool_stride, workspace,
+                     stream=None, variant=-1):
+    """conv_pool_fwd_ex of the C ABI: convolution + bias + ReLU + max pooling; `out` is the
+    pooled tensor."""
+    N, C, H, W, K, R, S = _dims(inp, filt)
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    if 0 < pool_ksz <= min(P, Q) and pool_stride > 0 and tuple(out.shape) != (
+            N, K, (P - pool_ksz) // pool_stride + 1, (Q - pool_ksz) // pool_stride + 1):
+        raise ValueError("out must be the pooled tensor")
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib().conv_pool_fwd_ex(_dev_ptr(inp, "in"), _dev_ptr(filt, "filt"), _dev_ptr(bias, "bias"),
+                                  _dev_ptr(out, "out"), N, C, H, W, K, R, S, stride, pad,
+                                  1 if relu else 0, pool_ksz, pool_stride, ws_ptr, ws_bytes,
+                                  _stream_handle(stream), int(variant)), "conv_pool_fwd_ex")
+    return out
+
+
+def conv_pool_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant=-1):
+    return int(lib().conv_pool_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, int(variant)))
 
 
 def conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant=-1):

@@ -158,6 +158,106 @@ hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* 
   return hipGetLastError();
 }
 
+// Split reduction with the pooling folded in: one thread per pooled output point takes the
+// max over its ksz x ksz window of act(bias + sum_z partial[z][.]), each element summed in
+// split order exactly as splitk_reduce_kernel does, so the result equals reducing first and
+// pooling afterwards bit for bit.  An element shared by neighbouring windows is summed once
+// per window (2.25 times on average for 3x3 / 2); the layers that split are the small ones.
+__global__ __launch_bounds__(256)
+void splitk_reduce_pool_kernel(const float* __restrict__ partial, const float* __restrict__ bias,
+                               float* __restrict__ out, int nsplit, int out_elems, int K, int P,
+                               int Q, int PP, int PQ2, int ksz, int pstride, int relu,
+                               long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int q2 = (int)(idx % PQ2);
+    long long t = idx / PQ2;
+    const int p2 = (int)(t % PP);
+    const long long nk = t / PP;               // image * K + filter
+    const float b = bias ? bias[(int)(nk % K)] : 0.0f;
+    const long long plane = nk * P * Q;
+    float m = 0.0f;
+    for (int r = 0; r < ksz; ++r)
+      for (int c = 0; c < ksz; ++c) {
+        const long long e = plane + (long long)(p2 * pstride + r) * Q + (q2 * pstride + c);
+        float v = 0.0f;
+        for (int z = 0; z < nsplit; ++z) v += partial[(size_t)z * out_elems + e];
+        v += b;
+        if (relu) v = v > 0.0f ? v : 0.0f;
+        m = (r == 0 && c == 0) ? v : (v > m ? v : m);
+      }
+    out[idx] = m;
+  }
+}
+
+// The same for a window and step fixed at compile time: the KSZ*KSZ elements of a window
+// are summed side by side, four splits at a time, so that up to 4*KSZ*KSZ loads are in
+// flight per thread instead of one (the generic kernel above pays a memory round trip
+// per load).  Per element the additions are still in split order.
+template <int KSZ, int PSTRIDE>
+__global__ __launch_bounds__(256)
+void splitk_reduce_pool_fixed_kernel(const float* __restrict__ partial,
+                                     const float* __restrict__ bias, float* __restrict__ out,
+                                     int nsplit, int out_elems, int K, int P, int Q, int PP, int PQ2,
+                                     int relu, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int q2 = (int)(idx % PQ2);
+    long long t = idx / PQ2;
+    const int p2 = (int)(t % PP);
+    const long long nk = t / PP;
+    const float b = bias ? bias[(int)(nk % K)] : 0.0f;
+    const float* src = partial + nk * P * Q + (long long)(p2 * PSTRIDE) * Q + q2 * PSTRIDE;
+    float v[KSZ * KSZ];
+#pragma unroll
+    for (int e = 0; e < KSZ * KSZ; ++e) v[e] = 0.0f;
+    int z = 0;
+    for (; z + 4 <= nsplit; z += 4) {
+      float w[4][KSZ * KSZ];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < KSZ * KSZ; ++e)
+          w[u][e] = src[(size_t)(z + u) * out_elems + (e / KSZ) * Q + (e % KSZ)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < KSZ * KSZ; ++e) v[e] += w[u][e];
+    }
+    for (; z < nsplit; ++z) {
+      float w[KSZ * KSZ];
+#pragma unroll
+      for (int e = 0; e < KSZ * KSZ; ++e) w[e] = src[(size_t)z * out_elems + (e / KSZ) * Q + (e % KSZ)];
+#pragma unroll
+      for (int e = 0; e < KSZ * KSZ; ++e) v[e] += w[e];
+    }
+    float m = 0.0f;
+#pragma unroll
+    for (int e = 0; e < KSZ * KSZ; ++e) {
+      float x = v[e] + b;
+      if (relu) x = x > 0.0f ? x : 0.0f;
+      m = e == 0 ? x : (x > m ? x : m);
+    }
+    out[idx] = m;
+  }
+}
+
+hipError_t launch_splitk_reduce_pool(const float* partial, const float* bias, float* out, int nsplit,
+                                     int out_elems, int N, int K, int P, int Q, int ksz, int pstride,
+                                     int relu, hipStream_t st) {
+  const int PP = (P - ksz) / pstride + 1, PQ2 = (Q - ksz) / pstride + 1;
+  const long long total = (long long)N * K * PP * PQ2;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  if (ksz == 3 && pstride == 2)
+    hipLaunchKernelGGL((splitk_reduce_pool_fixed_kernel<3, 2>), dim3((unsigned)blocks), dim3(256), 0, st,
+                       partial, bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, relu, total);
+  else
+    hipLaunchKernelGGL(splitk_reduce_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, partial,
+                       bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, ksz, pstride, relu, total);
+  return hipGetLastError();
+}
+
 // One (image, channel) plane per blockIdx.y (strided when there are more planes than the
 // grid allows), 256 output points of the plane per block: 32-bit index math, one division.
 __global__ __launch_bounds__(256)

@@ -269,6 +269,57 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
   return BCONV_OK;
 }
 
+// Convolution + bias + ReLU followed by max pooling (window ksz, step pstride, no padding)
+// in one call, fp32.  Workspace need of a variant: the partial sums when it splits the
+// reduction (the pooling is then folded into the reduction kernel), else the unpooled
+// convolution output (pooled by a second kernel).
+static size_t conv_pool_need(const Shape& s, int variant_id) {
+  const size_t conv_bytes = (size_t)s.N * s.K * s.P * s.Q * sizeof(float);
+  int t, nsplit;
+  Plan pl;
+  if (variant_id == 0) return conv_bytes;
+  if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return 0;
+  return nsplit > 1 ? pl.ws_bytes : conv_bytes;
+}
+
+static int run_conv_pool(const float* in, const float* filt, const float* bias, float* out,
+                         const Shape& s, int relu, int ksz, int pstride, void* ws, size_t ws_bytes,
+                         hipStream_t st, int variant_id) {
+  const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & 15u) == 0;
+  const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
+  if (variant_id < 0) variant_id = select_variant(s, aligned16, in_aligned16);
+  const size_t need = conv_pool_need(s, variant_id);
+  if (need == 0) return BCONV_EVARIANT;
+  if (!ws || ws_bytes < need) return BCONV_EWORKSPACE;
+  int t = 0, nsplit = 1;
+  if (variant_id > 0 && !decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
+  float* const scratch = static_cast<float*>(ws);
+  if (variant_id == 0 || nsplit == 1) {
+    // unpooled output into the workspace (a variant without split needs none of its own)
+    int rc = run_conv(in, filt, bias, scratch, s, relu, nullptr, 0, false, st, variant_id);
+    if (rc != BCONV_OK) return rc;
+    return launch_maxpool(scratch, out, s.N, s.K, s.P, s.Q, ksz, pstride, (s.P - ksz) / pstride + 1,
+                          (s.Q - ksz) / pstride + 1, st) == hipSuccess
+               ? BCONV_OK
+               : BCONV_ELAUNCH;
+  }
+  Plan pl;
+  if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
+  if (kTiles[t].AV == 4 && !aligned16) return BCONV_EVARIANT;
+  if (kTiles[t].BV == kModeCompact4 && !in_aligned16) return BCONV_EVARIANT;
+  pl.p.in = in;
+  pl.p.filt = filt;
+  pl.p.bias = bias;
+  pl.p.out = nullptr;          // a split launch writes partial sums only
+  pl.p.partial = scratch;
+  pl.p.relu = relu;
+  if (kLaunch[t](pl.p, dim3(pl.gx, pl.gy, pl.gz), pl.lds_bytes, st) != hipSuccess) return BCONV_ELAUNCH;
+  return launch_splitk_reduce_pool(scratch, bias, out, nsplit, pl.p.out_elems, s.N, s.K, s.P, s.Q, ksz,
+                                   pstride, relu, st) == hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
 // ------------------------------------------------------------------ audit
 static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
   const TconvParams& p = pl.p;
@@ -433,6 +484,34 @@ int conv_fwd_f16(const void* in, const void* filt, const float* bias, void* out,
   if (rc != BCONV_OK) return rc;
   return run_conv(static_cast<const float*>(in), static_cast<const float*>(filt), bias,
                   static_cast<float*>(out), s, relu, nullptr, 0, true, nullptr, -1, true);
+}
+
+// Convolution + bias + ReLU + max pooling; see include/bconv.h.
+int conv_pool_fwd_ex(const float* in, const float* filt, const float* bias, float* out, int N,
+                     int C, int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                     int pool_ksz, int pool_stride, void* workspace, size_t workspace_bytes,
+                     void* hip_stream, int variant_id) {
+  Shape s;
+  int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 4, &s);
+  if (rc != BCONV_OK) return rc;
+  if (pool_ksz <= 0 || pool_stride <= 0) return BCONV_EINVAL;
+  if (s.P < pool_ksz || s.Q < pool_ksz) return BCONV_ESHAPE;
+  if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
+  return run_conv_pool(in, filt, bias, out, s, relu, pool_ksz, pool_stride, workspace,
+                       workspace_bytes, static_cast<hipStream_t>(hip_stream), variant_id);
+}
+
+size_t conv_pool_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                     int pad, int variant_id) {
+  Shape s;
+  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+  if (variant_id >= 0) return variant_id < kNumVariants ? conv_pool_need(s, variant_id) : 0;
+  size_t need = 0;
+  for (int mask = 0; mask < 4; ++mask) {     // whichever loads the pointers turn out to allow
+    const size_t n = conv_pool_need(s, select_variant(s, (mask & 1) != 0, (mask & 2) != 0));
+    if (n > need) need = n;
+  }
+  return need;
 }
 
 size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,

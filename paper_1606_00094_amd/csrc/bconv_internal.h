@@ -24,6 +24,9 @@ hipError_t launch_direct_conv(const float* in, const float* filt, const float* b
                               const Shape& s, int relu, bool f16, hipStream_t st);
 hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* out, int nsplit,
                                 int out_elems, int K, int PQ, int relu, bool f16, hipStream_t st);
+hipError_t launch_splitk_reduce_pool(const float* partial, const float* bias, float* out, int nsplit,
+                                     int out_elems, int N, int K, int P, int Q, int ksz, int pstride,
+                                     int relu, hipStream_t st);
 hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int W, int ksz,
                           int stride, int P, int Q, hipStream_t st);
 

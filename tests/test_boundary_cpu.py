@@ -92,6 +92,27 @@ def test_default_workspace_size_covers_every_pointer_alignment():
     assert names["direct"] == 0
 
 
+def test_conv_pool_rejects_bad_arguments_and_sizes_its_workspace_without_a_gpu():
+    lib = binding.lib()
+    fake = ctypes.c_void_p(4096)
+    ok = (1, 3, 8, 8, 4, 3, 3, 1, 1)
+    assert lib.conv_pool_fwd_ex(None, fake, fake, fake, *ok, 1, 3, 2, fake, 1 << 20, None, -1) == -2
+    assert lib.conv_pool_fwd_ex(fake, fake, fake, fake, *ok, 1, 0, 2, fake, 1 << 20, None, -1) == -1
+    assert lib.conv_pool_fwd_ex(fake, fake, fake, fake, *ok, 1, 3, -1, fake, 1 << 20, None, -1) == -1
+    assert lib.conv_pool_fwd_ex(fake, fake, fake, fake, *ok, 1, 9, 1, fake, 1 << 20, None, -1) == -3
+    assert lib.conv_pool_fwd_ex(fake, fake, fake, fake, *ok, 1, 3, 2, fake, 1 << 20, None,
+                                binding.conv_num_variants()) == -6
+    assert lib.conv_pool_fwd_ex(fake, fake, fake, fake, *ok, 1, 3, 2, None, 0, None, 0) == -4
+    names = binding.variant_ids_by_name()
+    dims = (1, 256, 13, 13, 384, 3, 3, 1, 1)
+    conv_bytes = 384 * 169 * 4
+    assert binding.conv_pool_fwd_workspace_bytes(*dims, names["direct"]) == conv_bytes
+    assert binding.conv_pool_fwd_workspace_bytes(*dims, names["k3_64x64_k12/s1"]) == conv_bytes
+    assert binding.conv_pool_fwd_workspace_bytes(*dims, names["k3_64x64_k12/s4"]) == 4 * conv_bytes
+    assert binding.conv_pool_fwd_workspace_bytes(*dims, -1) >= conv_bytes
+    assert binding.conv_pool_fwd_workspace_bytes(1, 256, 13, 13, 384, 3, 3, 1, 1, binding.conv_num_variants()) == 0
+
+
 def test_variant_catalogue():
     nv = binding.conv_num_variants()
     assert nv > 10

@@ -298,6 +298,76 @@ def test_maxpool_parity():
         assert np.array_equal(out.cpu().numpy(), ref)
 
 
+def gpu_conv_pool(x, f, b, stride, pad, relu, ksz, pstride, variant=-1):
+    dev = torch.device("cuda:0")
+    xd, fd = torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev)
+    bd = torch.from_numpy(b).to(dev) if b is not None else None
+    N, C, H, W = x.shape
+    K, _, R, S = f.shape
+    P, Q = binding.conv_out_dims(H, W, R, S, stride, pad)
+    need = binding.conv_pool_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant)
+    assert need > 0
+    ws = torch.full(((need + 3) // 4,), float("nan"), dtype=torch.float32, device=dev)
+    out = torch.full((N, K, (P - ksz) // pstride + 1, (Q - ksz) // pstride + 1), -7.0,
+                     dtype=torch.float32, device=dev)
+    binding.conv_pool_fwd_ex(xd, fd, bd, out, stride, pad, relu, ksz, pstride, ws, variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("N", [1, 5, 32])
+@pytest.mark.parametrize("layer", [workloads.CONV1, workloads.CONV2], ids=lambda l: l.name)
+def test_conv_pool_on_the_stack_layers(layer, N):
+    """The table's variant (split at small batches: pooling folded into the reduction;
+    unsplit at batch 32: pooling kernel after the convolution).  Against the oracle's
+    convolution followed by its pooling, and bit for bit against the library's own
+    two calls."""
+    x, f, b, s, p = _layer_case(layer, N)
+    got = gpu_conv_pool(x, f, b, s, p, True, 3, 2)
+    two = gpu_conv(x, f, b, s, p, True)
+    dev = torch.device("cuda:0")
+    pooled = torch.empty(got.shape, dtype=torch.float32, device=dev)
+    binding.maxpool_fwd(torch.from_numpy(two).to(dev), pooled, 3, 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(got, pooled.cpu().numpy())
+    for n in sorted({0, N // 2, N - 1}):
+        ref = oracle.maxpool_fwd(oracle.conv_fwd(x[n:n + 1], f, b, stride=s, pad=p, relu=True), 3, 2)
+        assert_close(got[n:n + 1], ref, "%s N=%d image %d" % (layer.name, N, n))
+
+
+def test_conv_pool_forced_variants_windows_and_no_relu():
+    ids = binding.variant_ids_by_name()
+    x, f, b = workloads.make_integer_problem(31, 2, 24, 13, 11, 40, 3, 3)
+    for relu in (False, True):
+        conv = oracle.conv_fwd(x, f, b, stride=1, pad=1, relu=relu)
+        for (ksz, pstride) in [(3, 2), (2, 1), (2, 2), (13, 1)]:
+            if conv.shape[3] < ksz:
+                continue
+            ref = oracle.maxpool_fwd(conv, ksz, pstride)
+            for name in ("direct", "k3_64x64_k12_h/s1", "k3_64x64_k12_h/s3", "k3_32x128_k12/s2", "gen_64x64_k2/s2"):
+                assert binding.conv_variant_applicable(2, 24, 13, 11, 40, 3, 3, 1, 1, ids[name]), name
+                got = gpu_conv_pool(x, f, b, 1, 1, relu, ksz, pstride, variant=ids[name])
+                assert np.array_equal(got, ref), (name, ksz, pstride, relu)
+    # missing bias
+    ref = oracle.maxpool_fwd(oracle.conv_fwd(x, f, None, stride=1, pad=1, relu=True), 3, 2)
+    assert np.array_equal(gpu_conv_pool(x, f, None, 1, 1, True, 3, 2, variant=ids["k3_64x64_k12_h/s3"]), ref)
+
+
+def test_conv_pool_errors():
+    dev = torch.device("cuda:0")
+    x = torch.zeros((1, 4, 6, 6), dtype=torch.float32, device=dev)
+    f = torch.zeros((3, 4, 3, 3), dtype=torch.float32, device=dev)
+    ws = torch.zeros(1024, dtype=torch.float32, device=dev)
+    out = torch.zeros((1, 3, 1, 1), dtype=torch.float32, device=dev)
+    for args, status in [((1, 0, True, 0, 2, ws), -1), ((1, 0, True, 3, 0, ws), -1),
+                         ((1, 0, True, 5, 1, ws), -3), ((1, 0, True, 3, 2, None), -4),
+                         ((1, 0, True, 3, 2, ws[:4]), -4)]:
+        with pytest.raises(binding.BconvError) as e:
+            binding.conv_pool_fwd_ex(x, f, None, out, *args)
+        assert e.value.status == status, args
+    torch.cuda.synchronize()
+
+
 def gpu_stack(img, params):
     """conv1 -> pool -> conv2 -> pool -> conv3 -> conv4 -> conv5, all fused bias+ReLU,
     one stream, no host synchronisation between layers.  Returns every layer's
