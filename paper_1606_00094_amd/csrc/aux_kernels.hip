@@ -99,7 +99,16 @@ void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __re
     const int i = (int)i64;
     float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     int z = 0;
-    // four loads in flight at a time; the additions stay in split order
+    // eight, then four loads in flight at a time; the additions stay in split order
+    for (; z + 8 <= nsplit; z += 8) {
+      float4 w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) w[u] = partial[(size_t)(z + u) * out_quads + i];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        v.x += w[u].x; v.y += w[u].y; v.z += w[u].z; v.w += w[u].w;
+      }
+    }
     for (; z + 4 <= nsplit; z += 4) {
       const float4 w0 = partial[(size_t)z * out_quads + i];
       const float4 w1 = partial[(size_t)(z + 1) * out_quads + i];
