@@ -7,8 +7,8 @@
  * i.e. for every output point the window of the input starting at
  * (p*stride, q*stride) (in zero-padded coordinates) over all input channels is
  * multiplied element-wise with filter k and summed, with no filter flip; images
- * of a batch are independent; act is the identity or ReLU max(0,x), fused
- * (Section II: the activation "is often fused into the convolution").  The
+ * of a batch are independent; act is the identity or ReLU max(0,x), applied
+ * in the same kernel (Section II notes that the activation is commonly fused).  The
  * per-output-channel bias, which the paper leaves out of its discussion, is
  * added before the activation.  Output extent (Section II size rule, floor
  * reading):  P = floor((H + 2*pad - R)/stride) + 1, same for Q with W, S.
@@ -52,7 +52,7 @@ int conv_out_dims(int H, int W, int R, int S, int stride, int pad, int* P, int* 
 
 /* Forward convolution + bias + optional ReLU on the null stream, variant chosen
  * by the selection table (the role of the paper's per-operation variant and
- * blocking choice, Section V "blocking strategy" and Section VI variants).
+ * blocking choice: Section V on choosing the blocking, Section VI on the variants).
  * If the chosen variant splits the reduction, partial sums go to a workspace
  * the library allocates once per device and keeps until the process ends. */
 int conv_fwd(const float* in, const float* filt, const float* bias, float* out,

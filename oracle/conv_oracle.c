@@ -6,12 +6,12 @@
  * benchmark's cpu_baseline leg may call it; the product library never does and
  * shares no code, header, table or helper with it.
  *
- * What is computed (paper Section II, "Deep Neural Networks" / convolution
- * definition): for every output point the window of the input that starts at
+ * What is computed (paper Section II, the definition of the convolution
+ * layer): for every output point the window of the input that starts at
  * (oy*stride, ox*stride) and spans all input channels is multiplied element by
  * element with the filter slice of that output channel and summed -- no filter
- * flip (cross-correlation).  The input is padded with zeros (Section II: input
- * "often padded ... usually zeros"), images of a batch are independent
+ * flip (cross-correlation).  The input is padded with zeros (Section II, on
+ * padding of the input), images of a batch are independent
  * (Section II, batch dimension B), the activation max(0,x) may be fused
  * (Section II, ReLU).  The per-output-channel bias, which the paper leaves out
  * of its discussion, is added before the activation.

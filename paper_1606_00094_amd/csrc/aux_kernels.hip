@@ -1,6 +1,7 @@
 // Small kernels around the tiled MFMA convolution: the plain direct convolution
 // (always-applicable fallback, variant 0), the split-K reduction with the fused
-// bias + ReLU epilogue, and max pooling.
+// bias + ReLU epilogue (optionally with max pooling folded in), max pooling, and a
+// register-only MFMA loop used as a measurement aid.
 #include <cstdint>
 
 #include "bconv_internal.h"
