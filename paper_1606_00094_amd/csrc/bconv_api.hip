@@ -112,8 +112,12 @@ static double model_cost(const TileDesc& v, const Plan& pl) {
   const double eff = pipe_waves >= 2.0 ? 1.0 : 0.78;
   // staging instructions per thread and chunk: filter loads of AV words, input cells
   const double in_words = p.halo ? (double)npl * p.plane : (double)v.KR * p.plane;
+  // (input loads that keep per-load address selects -- slot staging of a padded layer --
+  // count one and a half times)
+  const bool scalar_in = p.halo || v.BV == kModeSlotsNoPad || (v.R == 1 && v.S == 1 && v.STR == 1);
   const double stage_instr = (double)v.BM() * v.KR * S / v.NTHR() / v.AV +
-                             in_words / v.NTHR() / (v.BV == kModeCompact4 ? 4.0 : 1.0);
+                             in_words / v.NTHR() / (v.BV == kModeCompact4 ? 4.0 : 1.0) *
+                                 (scalar_in ? 1.0 : 1.5);
   const double chunk_time = std::max(300.0, pipe_waves * chunk_mfma / eff) + 80.0 * stage_instr * pipe_waves;
   const double wg_time = p.chunks_per_split * chunk_time + 1200.0 * v.MT * v.NT +
                          1170.0 * (v.KS - 1) * v.MT * v.NT;

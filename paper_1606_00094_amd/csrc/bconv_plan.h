@@ -39,6 +39,7 @@ constexpr int kSmaxGeneric = 16;   // widest kernel the run-time generic tiles t
 constexpr int kModeSlots = 1;      // one copy of an input row per kernel row and output row (or compact cells)
 constexpr int kModeCompact4 = 4;   // compact cells of four pixels, 16-byte loads (flattened pointwise)
 constexpr int kModeHalo = 2;       // whole padded rows per channel, staged once
+constexpr int kModeSlotsNoPad = 3; // kModeSlots for layers without padding (every staged row is inside the image)
 constexpr int kLdsTrashWords = 16; // LDS words (in front of the filter buffers, behind each input buffer) that absorb masked stores
 
 struct Plan {
@@ -75,6 +76,8 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   // 16-byte input loads: only for flattened pointwise layers whose images are a
   // multiple of four pixels long, so that no group of four pixels straddles images
   if (v.BV == kModeCompact4 && !(flat && s.W % 4 == 0)) return false;
+  // the no-padding form of slot staging: nothing to mask per kernel row (and no pointwise cells)
+  if (v.BV == kModeSlotsNoPad && (s.pad != 0 || (s.S == 1 && s.stride == 1))) return false;
   // halo staging needs kernel sizes fixed at compile time, a kernel wider than one
   // column or a stride, and half-chunks / reduction groups made of whole channels
   if (v.BV == kModeHalo &&

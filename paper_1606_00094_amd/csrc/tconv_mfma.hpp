@@ -96,10 +96,11 @@ void tconv_mfma_kernel(const TconvParams p) {
   static_assert(AV == 1 || (AV == 4 && S_ > 0 && KRSP % 4 == 0), "vector filter loads need KR*S % 4 == 0");
   constexpr int AGRP = KRSP / AV;                      // load groups per filter row
   constexpr int NA = (BM * AGRP + NTHR - 1) / NTHR;    // filter load items per thread
-  // BV is the input staging mode: kModeSlots, kModeCompact4 or kModeHalo
+  // BV is the input staging mode: kModeSlots, kModeSlotsNoPad, kModeCompact4 or kModeHalo
   constexpr bool HALO = (BV == kModeHalo);
   constexpr int BVW = (BV == kModeCompact4) ? 4 : 1;   // words per input load
-  static_assert(BV == kModeSlots || BV == kModeCompact4 || BV == kModeHalo, "unknown staging mode");
+  static_assert(BV == kModeSlots || BV == kModeSlotsNoPad || BV == kModeCompact4 || BV == kModeHalo,
+                "unknown staging mode");
   static_assert(BV != kModeCompact4 || (S_ == 1 && STR_ == 1), "16-byte input loads are for pointwise tiles");
   static_assert(!HALO || (R_ > 0 && S_ > 0 && STR_ > 0 && (KR / 2) % (R_ > 0 ? R_ : 1) == 0 &&
                           (KR / 2 / KS) % (R_ > 0 ? R_ : 1) == 0),
@@ -124,7 +125,9 @@ void tconv_mfma_kernel(const TconvParams p) {
   // instruction then writes a register that a load also writes, so the compiler needs
   // no wait on loads in flight before it issues the next ones.
   constexpr bool A_SCALAR = NA <= 12;                  // one offset register per filter item
-  constexpr bool B_SCALAR = HALO || (R_ == 1 && S_ == 1 && STR_ == 1);
+  // (slot staging qualifies when the layer has no padding: a cell that loads at all loads for
+  // every kernel row, so its validity does not change from chunk to chunk)
+  constexpr bool B_SCALAR = HALO || (R_ == 1 && S_ == 1 && STR_ == 1) || BV == kModeSlotsNoPad;
   typedef typename VecOf<VW>::type avec_t;
   typedef typename VecOf<SW>::type svec_t;
   static_assert(sizeof(T) == 4 || sizeof(T) == 2, "fp32 or fp16 storage");

@@ -168,6 +168,12 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
             if (e * p.bv >= ncell) continue;
             BCell cell = b_cell(p, t, e, Sk, STR);
             bool ok = rowok && ((unsigned)(cell.ih0 + r) < (unsigned)p.H);
+            if (v.BV == kModeSlotsNoPad) {
+              // scalar addressing: a cell that ever loads, loads for every kernel row; the
+              // row must then be inside the image (the kernel has no per-row mask)
+              ok = rowok && cell.ih0 != kNeverValid;
+              if (ok && !((unsigned)(cell.ih0 + r) < (unsigned)p.H)) oob.hit("unmasked row", cell.ih0 + r, p.H);
+            }
             for (int u = 0; u < p.bv; ++u) {
               long long gi = ok ? (long long)cell.goff + koff + u : 0;
               if (p.bv == 4 && u == 0 && ok && (gi % 4) != 0) oob.hit("in alignment", gi, 4);

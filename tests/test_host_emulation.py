@@ -121,6 +121,16 @@ CASES = [
     ("k5_32x32_k40_s4_v4_h", 2, 16, 12, 12, 33, 5, 5, 1, 2, 1),
     ("k5_32x64_k40_s4_h", 1, 19, 27, 27, 40, 5, 5, 1, 2, 1),
     ("k5_32x32_k20_s2_h", 2, 7, 14, 10, 20, 5, 5, 1, 2, 1),
+    ("k11s4_96x128_k2_np", 2, 3, 51, 47, 70, 11, 11, 4, 0, 1),         # slot staging without padding: scalar addressing
+    ("k11s4_32x128_k4_s2_np", 1, 5, 35, 39, 40, 11, 11, 4, 0, 3),
+    ("k11s4_96x128_k2_np_w3", 3, 2, 27, 31, 97, 11, 11, 4, 0, 1),
+    ("k7s2_64x128_k2_np", 1, 3, 41, 37, 70, 7, 7, 2, 0, 1),
+    ("gen_64x64_k2_np", 2, 5, 12, 17, 40, 2, 5, 3, 0, 2),
+    ("gen_32x128_k2_np", 1, 4, 9, 30, 33, 1, 4, 1, 0, 1),
+    ("pws2_64x128_k16_v4_np", 2, 20, 14, 14, 70, 1, 1, 2, 0, 1),    # the same with scalar addressing
+    ("pws2_32x128_k16_np", 1, 37, 28, 27, 40, 1, 1, 2, 0, 2),
+    ("k3s2_64x64_k12_v4_np", 2, 20, 15, 13, 70, 3, 3, 2, 0, 1),
+    ("k3s2_32x128_k12_np", 1, 7, 27, 27, 33, 3, 3, 2, 0, 1),
     ("pws2_64x128_k16_v4", 2, 20, 14, 14, 70, 1, 1, 2, 0, 1),       # stride-2 pointwise
     ("pws2_32x128_k16", 1, 37, 28, 27, 40, 1, 1, 2, 1, 2),
     ("k3s2_64x64_k12_v4", 2, 12, 27, 27, 70, 3, 3, 2, 0, 1),        # 3x3 stride 2
@@ -164,6 +174,11 @@ def test_tile_that_does_not_apply_is_refused(emu):
     x, f, b = workloads.make_integer_problem(1, 1, 2, 8, 8, 4, 5, 5)
     rc, _ = _run(emu, tile, 1, x, f, b, 1, 2, False)
     assert rc == 1
+    # a no-padding tile must refuse a padded layer
+    tile = _tiles(emu)["k11s4_32x128_k2_np"]
+    x, f, b = workloads.make_integer_problem(2, 1, 3, 40, 40, 8, 11, 11)
+    assert _run(emu, tile, 1, x, f, b, 4, 2, False)[0] == 1
+    assert _run(emu, tile, 1, x, f, b, 4, 0, False)[0] == 0
 
 
 @pytest.mark.parametrize("grid", [(183, 8, 1), (85, 6, 1), (3, 6, 8), (1, 1, 1), (5, 3, 4), (757, 1, 1), (7, 11, 3)])
