@@ -468,13 +468,13 @@ void tconv_mfma_kernel(const TconvParams p) {
     }
   };
 
-  // Pointwise tiles with one accumulator tile per wave raise the wave's priority while it
-  // issues a step's MFMA: with several short-chunk waves per SIMD the matrix pipe then goes
-  // to the wave that has its operands rather than to one that is about to stall on staging
-  // (1.5-4 % on the 1x1 layers and the small matrix products; tiles with one or two waves
-  // per SIMD -- the 3x3 and first-layer tiles, the 128x128 pointwise tile -- only pay for
-  // the two extra instructions and lose 1-2 %).
-  constexpr bool MFMA_PRIO = (R_ == 1 && S_ == 1 && MT * NT == 1);
+  // Waves with one accumulator tile raise their priority while they issue a step's MFMA:
+  // with several short-step waves per SIMD the matrix pipe then goes to the wave that has
+  // its operands rather than to one that is about to stall on staging (1.5-4 % on the 1x1
+  // layers and small matrix products, 0-3 % on the other single-tile waves).  Tiles whose
+  // waves hold several accumulator tiles run one or two waves per SIMD, have nobody to take
+  // priority from, and lost 1-2 % to the two extra instructions.
+  constexpr bool MFMA_PRIO = (MT * NT == 1);
   auto mfma_tile = [&](const float (&a)[MT], const float (&b)[NT]) {
     if constexpr (MFMA_PRIO) __builtin_amdgcn_s_setprio(2);
 #pragma unroll
