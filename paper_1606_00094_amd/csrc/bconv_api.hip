@@ -339,7 +339,7 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
   if (v.KS > 1 && (size_t)BM * BN * 4 > pl.lds_bytes) ++bad;
   if ((long long)ncell > (long long)v.EPT * NTHR * p.bv) ++bad;
   for (unsigned bx = 0; bx < pl.gx; ++bx) {
-    PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
+    PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q, p.fdQ);
     if (t.cnt < 1 || t.cnt > BN) ++bad;
     if (p.halo) {
       HaloTile ht = halo_tile(p, t);

@@ -29,6 +29,32 @@
 
 namespace bconv {
 
+// Division of a non-negative 31-bit number by a divisor fixed per launch, as a multiply
+// and a shift (the round-up method for unsigned division by an invariant integer): the
+// host derives (mul, shift) once, the kernel's prologue then spends three instructions
+// per quotient instead of the ~30 of a run-time integer division.
+struct FastDiv {
+  unsigned mul, shift;
+};
+
+inline FastDiv make_fastdiv(unsigned d) {
+  if (d == 0) d = 1;
+  unsigned s = 0;
+  while ((1u << s) < d) ++s;                                    // ceil(log2 d)
+  const unsigned long long m = ((1ull << 32) * ((1ull << s) - d)) / d + 1;   // < 2^32 for d < 2^31
+  return FastDiv{(unsigned)m, s};
+}
+
+// floor(n / d) for 0 <= n < 2^31 and the d that f was made for.
+BCONV_HD int fd_div(int n, FastDiv f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const unsigned hi = __umulhi((unsigned)n, f.mul);
+#else
+  const unsigned hi = (unsigned)(((unsigned long long)(unsigned)n * f.mul) >> 32);
+#endif
+  return (int)((hi + (unsigned)n) >> f.shift);
+}
+
 // Kernel argument block of the tiled MFMA kernel (plain data).
 struct TconvParams {
   const float* in;
@@ -48,6 +74,7 @@ struct TconvParams {
   int ast;                             // LDS stride between filter rows (odd)
   int nchunks, chunks_per_split, nsplit;
   int out_elems;                       // N*K*P*Q
+  FastDiv fdQ, fdP, fdRowst, fdHp;     // divisions by Q, P, rowst and hp (hp: halo mode)
 };
 
 // Which tile a workgroup computes, from its position in dispatch order (x fastest, then
@@ -79,15 +106,15 @@ struct PixTile {
   int rho1, qlast;    // output row / column of the last valid pixel
 };
 
-BCONV_HD PixTile pix_tile(int tile_idx, int BN, int NPQ, int Q) {
+BCONV_HD PixTile pix_tile(int tile_idx, int BN, int NPQ, int Q, FastDiv fdQ) {
   PixTile t;
   t.g0 = tile_idx * BN;
   int rem = NPQ - t.g0;
   t.cnt = rem < BN ? rem : BN;
-  t.rho0 = t.g0 / Q;
+  t.rho0 = fd_div(t.g0, fdQ);
   t.q00 = t.g0 - t.rho0 * Q;
   int gl = t.g0 + t.cnt - 1;
-  t.rho1 = gl / Q;
+  t.rho1 = fd_div(gl, fdQ);
   t.qlast = gl - t.rho1 * Q;
   return t;
 }
@@ -123,9 +150,9 @@ BCONV_HD BCell b_cell(const TconvParams& p, const PixTile& t, int e, int S, int 
     int col = e * p.bv;
     bool ok = col < t.cnt;
     int g = t.g0 + (ok ? col : 0);
-    int rho = g / p.Q;
+    int rho = fd_div(g, p.fdQ);
     int q = g - rho * p.Q;
-    int img = rho / p.P;
+    int img = fd_div(rho, p.fdP);
     int pp = rho - img * p.P;
     int iw = q - p.pad;
     ok = ok && (iw >= 0) && (iw < p.W);
@@ -135,11 +162,11 @@ BCONV_HD BCell b_cell(const TconvParams& p, const PixTile& t, int e, int S, int 
     c.ih0 = ok ? ih0 : kNeverValid;
     return c;
   }
-  int slot = e / p.rowst;
+  int slot = fd_div(e, p.fdRowst);
   int xrel = e - slot * p.rowst;
   int rho = t.rho0 + slot;
   bool ok = (slot < p.nrows) && (rho <= t.rho1);
-  int img = rho / p.P;
+  int img = fd_div(rho, p.fdP);
   int pp = rho - img * p.P;
   int qlo = (slot == 0) ? t.q00 : 0;
   int qhi = (rho == t.rho1) ? t.qlast : p.Q - 1;
@@ -167,11 +194,11 @@ BCONV_HD BLane b_lane(const TconvParams& p, const PixTile& t, int col) {
   l.valid = col < t.cnt;
   int cc = l.valid ? col : t.cnt - 1;   // ragged tail: alias the last valid pixel
   int g = t.g0 + cc;
-  int rho = g / p.Q;
+  int rho = fd_div(g, p.fdQ);
   int q = g - rho * p.Q;
   int slot = rho - t.rho0;
   int qlo = (slot == 0) ? t.q00 : 0;
-  int img = rho / p.P;
+  int img = fd_div(rho, p.fdP);
   int pp = rho - img * p.P;
   l.ldsbase = p.compact ? cc : slot * p.rowst + (q - qlo);
   l.outoff = img * p.K * p.PQ + pp * p.Q + q;
@@ -193,8 +220,8 @@ struct HaloTile {
 
 BCONV_HD HaloTile halo_tile(const TconvParams& p, const PixTile& t) {
   HaloTile h;
-  int img0 = t.rho0 / p.P, p0 = t.rho0 - img0 * p.P;
-  int img1 = t.rho1 / p.P, p1 = t.rho1 - img1 * p.P;
+  int img0 = fd_div(t.rho0, p.fdP), p0 = t.rho0 - img0 * p.P;
+  int img1 = fd_div(t.rho1, p.fdP), p1 = t.rho1 - img1 * p.P;
   h.u_first = img0 * p.hp + p0 * p.stride;
   h.vr = img1 * p.hp + p1 * p.stride + p.R - h.u_first;
   return h;
@@ -205,11 +232,11 @@ BCONV_HD HaloTile halo_tile(const TconvParams& p, const PixTile& t) {
 // that loads, kNeverValid one that holds padding (or lies outside the halo).
 BCONV_HD BCell h_cell(const TconvParams& p, const HaloTile& ht, int e, int STR) {
   BCell c;
-  int v = e / p.rowst;
+  int v = fd_div(e, p.fdRowst);
   int xp = e - v * p.rowst;
   bool ok = (v < ht.vr) && (xp < p.wt);
   int u = ht.u_first + v;
-  int img = u / p.hp;
+  int img = fd_div(u, p.fdHp);
   int ih = u - img * p.hp - p.pad;
   int iw = xp - p.pad;
   ok = ok && (img < p.N) && (ih >= 0) && (ih < p.H) && (iw >= 0) && (iw < p.W);
@@ -224,9 +251,9 @@ BCONV_HD BLane h_lane(const TconvParams& p, const PixTile& t, const HaloTile& ht
   l.valid = col < t.cnt;
   int cc = l.valid ? col : t.cnt - 1;
   int g = t.g0 + cc;
-  int rho = g / p.Q;
+  int rho = fd_div(g, p.fdQ);
   int q = g - rho * p.Q;
-  int img = rho / p.P;
+  int img = fd_div(rho, p.fdP);
   int pp = rho - img * p.P;
   l.ldsbase = (img * p.hp + pp * p.stride - ht.u_first) * p.rowst + q;
   l.outoff = img * p.K * p.PQ + pp * p.Q + q;

@@ -95,6 +95,8 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   p.CRS = s.C * s.R * s.S;
   p.CRrows = s.C * s.R;
   p.out_elems = s.N * s.K * p.PQ;
+  p.fdQ = make_fastdiv((unsigned)p.Q);
+  p.fdP = make_fastdiv((unsigned)p.P);
   const int BN = v.BN(), BM = v.BM();
   long long total_rows = (long long)s.N * s.P;
   p.gbias = s.pad * s.W + s.pad;
@@ -107,11 +109,12 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
     p.wt = s.W + 2 * s.pad;
     p.phst = (p.wt + s.stride - 1) / s.stride;
     p.rowst = s.stride * p.phst;
+    p.fdHp = make_fastdiv((unsigned)p.hp);
     p.nrows = 0;
     p.vr = 0;
     const int ntiles = (p.NPQ + BN - 1) / BN;
     for (int ti = 0; ti < ntiles; ++ti) {
-      HaloTile ht = halo_tile(p, pix_tile(ti, BN, p.NPQ, p.Q));
+      HaloTile ht = halo_tile(p, pix_tile(ti, BN, p.NPQ, p.Q, p.fdQ));
       if (ht.vr > p.vr) p.vr = ht.vr;
     }
     p.nrows = p.vr;
@@ -126,6 +129,8 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
     p.rowst = s.stride * p.phst;
   }
   p.plane = p.nrows * p.rowst;
+  p.fdRowst = make_fastdiv((unsigned)p.rowst);
+  if (!p.halo) p.fdHp = make_fastdiv(1);
   if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR() * p.bv) return false;
   p.ast = a_row_stride(v.KR * s.S, a_read_width(v.KR, v.S, v.KS));
   size_t lds = (size_t)(2 * BM * p.ast + 2 * (planes * p.plane + kLdsTrashWords) + kLdsTrashWords) * sizeof(float);

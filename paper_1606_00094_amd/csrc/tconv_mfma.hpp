@@ -163,7 +163,7 @@ void tconv_mfma_kernel(const TconvParams p) {
 
   const BlockTile bt = xcd_tile(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), gridDim.x,
                                 gridDim.y, gridDim.z);
-  const PixTile t = pix_tile(bt.x, BN, p.NPQ, p.Q);
+  const PixTile t = pix_tile(bt.x, BN, p.NPQ, p.Q, p.fdQ);
   const HaloTile ht = HALO ? halo_tile(p, t) : HaloTile{0, 0};
   const int m0 = bt.y * BM;
 

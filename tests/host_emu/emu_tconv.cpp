@@ -62,7 +62,7 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
   for (unsigned lin = 0; lin < pl.gx * pl.gy * pl.gz; ++lin) {
     const BlockTile bt = xcd_tile(lin, pl.gx, pl.gy, pl.gz);
     const unsigned bx = (unsigned)bt.x, by = (unsigned)bt.y, bz = (unsigned)bt.z;
-    const PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q);
+    const PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q, p.fdQ);
     const HaloTile ht = p.halo ? halo_tile(p, t) : HaloTile{0, 0};
     if (p.halo && ht.vr > p.vr) oob.hit("halo rows", ht.vr, p.vr);
     const int m0 = (int)by * BM;
@@ -257,6 +257,14 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
     out[i] = val;
   }
   return oob.count ? 2 + oob.count : 0;
+}
+
+// fd_div(n, make_fastdiv(d)) for each pair; returns the index of the first quotient that
+// differs from n / d, or -1.
+extern "C" long long emu_fastdiv_check(const int* n, const int* d, long long count) {
+  for (long long i = 0; i < count; ++i)
+    if (fd_div(n[i], make_fastdiv((unsigned)d[i])) != n[i] / d[i]) return i;
+  return -1;
 }
 
 extern "C" void emu_xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz, int* x, int* y, int* z) {

@@ -181,6 +181,30 @@ def test_tile_that_does_not_apply_is_refused(emu):
     assert _run(emu, tile, 1, x, f, b, 4, 0, False)[0] == 0
 
 
+def test_fast_division_matches_integer_division(emu):
+    """The multiply-and-shift quotient the kernel's index math uses, against n // d: all
+    small pairs, divisors around powers of two, the largest dividends, random pairs."""
+    rng = np.random.default_rng(77)
+    top = 2 ** 31 - 1
+    ds = list(range(1, 300)) + [2 ** k + o for k in range(8, 31) for o in (-1, 0, 1)] + [top, top - 1, 3025, 729, 169]
+    ns, dd = [], []
+    for d in ds:
+        d = min(d, top)
+        cand = [0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, top, top - 1, top // 2] + \
+            [int(x) for x in rng.integers(0, top, size=40)] + [(top // d) * d - 1, (top // d) * d]
+        for n in cand:
+            if 0 <= n <= top:
+                ns.append(n); dd.append(d)
+    n_small, d_small = np.meshgrid(np.arange(0, 2000), np.arange(1, 400))
+    ns = np.concatenate([np.array(ns, dtype=np.int32), n_small.ravel().astype(np.int32)])
+    dd = np.concatenate([np.array(dd, dtype=np.int32), d_small.ravel().astype(np.int32)])
+    emu.emu_fastdiv_check.restype = ctypes.c_longlong
+    emu.emu_fastdiv_check.argtypes = [ctypes.POINTER(ctypes.c_int)] * 2 + [ctypes.c_longlong]
+    ptr = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int))
+    bad = emu.emu_fastdiv_check(ptr(ns), ptr(dd), len(ns))
+    assert bad == -1, (int(ns[bad]), int(dd[bad]))
+
+
 @pytest.mark.parametrize("grid", [(183, 8, 1), (85, 6, 1), (3, 6, 8), (1, 1, 1), (5, 3, 4), (757, 1, 1), (7, 11, 3)])
 def test_block_to_tile_map_is_a_bijection_that_groups_tiles_by_die(emu, grid):
     """Every tile of the grid is computed exactly once, and the workgroups of one die
