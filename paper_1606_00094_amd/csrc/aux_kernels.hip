@@ -60,19 +60,27 @@ hipError_t launch_direct_conv(const float* in, const float* filt, const float* b
   return hipGetLastError();
 }
 
+// Filter index of output element e of an N x K x PQ tensor: (e / PQ) % K, the two divisions
+// as multiplies and shifts with constants made by the host (a run-time integer division is
+// ~30 instructions, and these kernels are a handful of loads long).
+__device__ __forceinline__ int filter_of(int e, int K, FastDiv fdPQ, FastDiv fdK) {
+  const int plane = fd_div(e, fdPQ);
+  return plane - fd_div(plane, fdK) * K;
+}
+
 // out[i] = act(bias[k(i)] + sum_z partial[z][i]), summed in split order.
 template <typename T>
 __global__ __launch_bounds__(256)
 void splitk_reduce_kernel(const float* __restrict__ partial, const float* __restrict__ bias,
                           T* __restrict__ out, int nsplit, int out_elems, int K, int PQ,
-                          int relu) {
+                          int relu, FastDiv fdPQ, FastDiv fdK) {
   // (64-bit counter: i + stride may pass 2^31 when out_elems is close to it)
   for (long long i64 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i64 < out_elems;
        i64 += (long long)gridDim.x * blockDim.x) {
     const int i = (int)i64;
     float v = 0.0f;
     for (int z = 0; z < nsplit; ++z) v += partial[(size_t)z * out_elems + i];
-    if (bias) v += bias[(i / PQ) % K];
+    if (bias) v += bias[filter_of(i, K, fdPQ, fdK)];
     if (relu) v = v > 0.0f ? v : 0.0f;
     out[i] = (T)v;
   }
@@ -94,7 +102,7 @@ template <typename Q4>
 __global__ __launch_bounds__(256)
 void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __restrict__ bias,
                            Q4* __restrict__ out, int nsplit, int out_quads, int K, int PQ,
-                           int relu) {
+                           int relu, FastDiv fdPQ, FastDiv fdK) {
   for (long long i64 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i64 < out_quads;
        i64 += (long long)gridDim.x * blockDim.x) {
     const int i = (int)i64;
@@ -126,10 +134,10 @@ void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __re
     }
     if (bias) {
       const int e = i * 4;
-      v.x += bias[(e / PQ) % K];
-      v.y += bias[((e + 1) / PQ) % K];
-      v.z += bias[((e + 2) / PQ) % K];
-      v.w += bias[((e + 3) / PQ) % K];
+      v.x += bias[filter_of(e, K, fdPQ, fdK)];
+      v.y += bias[filter_of(e + 1, K, fdPQ, fdK)];
+      v.z += bias[filter_of(e + 2, K, fdPQ, fdK)];
+      v.w += bias[filter_of(e + 3, K, fdPQ, fdK)];
     }
     if (relu) {
       v.x = v.x > 0.0f ? v.x : 0.0f; v.y = v.y > 0.0f ? v.y : 0.0f;
@@ -141,6 +149,7 @@ void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __re
 
 hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* out, int nsplit,
                                 int out_elems, int K, int PQ, int relu, bool f16, hipStream_t st) {
+  const FastDiv fdPQ = make_fastdiv((unsigned)PQ), fdK = make_fastdiv((unsigned)K);
   const uintptr_t out_mask = f16 ? 7 : 15;
   const bool quads = (out_elems % 4 == 0) && ((reinterpret_cast<uintptr_t>(partial) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(out) & out_mask) == 0);
@@ -151,20 +160,20 @@ hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* 
     const float4* p4 = reinterpret_cast<const float4*>(partial);
     if (f16)
       hipLaunchKernelGGL(splitk_reduce4_kernel<Half4>, dim3(blocks), dim3(256), 0, st, p4, bias,
-                         reinterpret_cast<Half4*>(out), nsplit, n4, K, PQ, relu);
+                         reinterpret_cast<Half4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK);
     else
       hipLaunchKernelGGL(splitk_reduce4_kernel<float4>, dim3(blocks), dim3(256), 0, st, p4, bias,
-                         reinterpret_cast<float4*>(out), nsplit, n4, K, PQ, relu);
+                         reinterpret_cast<float4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK);
     return hipGetLastError();
   }
   int blocks = (out_elems + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   if (f16)
     hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, st, partial, bias,
-                       reinterpret_cast<_Float16*>(out), nsplit, out_elems, K, PQ, relu);
+                       reinterpret_cast<_Float16*>(out), nsplit, out_elems, K, PQ, relu, fdPQ, fdK);
   else
     hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, st, partial, bias, out,
-                       nsplit, out_elems, K, PQ, relu);
+                       nsplit, out_elems, K, PQ, relu, fdPQ, fdK);
   return hipGetLastError();
 }
 
@@ -177,15 +186,14 @@ __global__ __launch_bounds__(256)
 void splitk_reduce_pool_kernel(const float* __restrict__ partial, const float* __restrict__ bias,
                                float* __restrict__ out, int nsplit, int out_elems, int K, int P,
                                int Q, int PP, int PQ2, int ksz, int pstride, int relu,
-                               long long total) {
+                               long long total, FastDiv fdPQ2, FastDiv fdPP, FastDiv fdK) {
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (long long)gridDim.x * blockDim.x) {
-    const int q2 = (int)(idx % PQ2);
-    long long t = idx / PQ2;
-    const int p2 = (int)(t % PP);
-    const long long nk = t / PP;               // image * K + filter
-    const float b = bias ? bias[(int)(nk % K)] : 0.0f;
-    const long long plane = nk * P * Q;
+    // total <= out_elems < 2^31: the index splits with 32-bit multiply-and-shift divisions
+    const int t = fd_div((int)idx, fdPQ2), q2 = (int)idx - t * PQ2;
+    const int nk = fd_div(t, fdPP), p2 = t - nk * PP;   // nk = image * K + filter
+    const float b = bias ? bias[nk - fd_div(nk, fdK) * K] : 0.0f;
+    const long long plane = (long long)nk * P * Q;
     float m = 0.0f;
     for (int r = 0; r < ksz; ++r)
       for (int c = 0; c < ksz; ++c) {
@@ -209,15 +217,14 @@ __global__ __launch_bounds__(256)
 void splitk_reduce_pool_fixed_kernel(const float* __restrict__ partial,
                                      const float* __restrict__ bias, float* __restrict__ out,
                                      int nsplit, int out_elems, int K, int P, int Q, int PP, int PQ2,
-                                     int relu, long long total) {
+                                     int relu, long long total, FastDiv fdPQ2, FastDiv fdPP,
+                                     FastDiv fdK) {
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (long long)gridDim.x * blockDim.x) {
-    const int q2 = (int)(idx % PQ2);
-    long long t = idx / PQ2;
-    const int p2 = (int)(t % PP);
-    const long long nk = t / PP;
-    const float b = bias ? bias[(int)(nk % K)] : 0.0f;
-    const float* src = partial + nk * P * Q + (long long)(p2 * PSTRIDE) * Q + q2 * PSTRIDE;
+    const int t = fd_div((int)idx, fdPQ2), q2 = (int)idx - t * PQ2;
+    const int nk = fd_div(t, fdPP), p2 = t - nk * PP;
+    const float b = bias ? bias[nk - fd_div(nk, fdK) * K] : 0.0f;
+    const float* src = partial + (long long)nk * P * Q + (long long)(p2 * PSTRIDE) * Q + q2 * PSTRIDE;
     float v[KSZ * KSZ];
 #pragma unroll
     for (int e = 0; e < KSZ * KSZ; ++e) v[e] = 0.0f;
@@ -259,12 +266,16 @@ hipError_t launch_splitk_reduce_pool(const float* partial, const float* bias, fl
   const long long total = (long long)N * K * PP * PQ2;
   long long blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
+  const FastDiv fdPQ2 = make_fastdiv((unsigned)PQ2), fdPP = make_fastdiv((unsigned)PP),
+                fdK = make_fastdiv((unsigned)K);
   if (ksz == 3 && pstride == 2)
     hipLaunchKernelGGL((splitk_reduce_pool_fixed_kernel<3, 2>), dim3((unsigned)blocks), dim3(256), 0, st,
-                       partial, bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, relu, total);
+                       partial, bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, relu, total, fdPQ2, fdPP,
+                       fdK);
   else
     hipLaunchKernelGGL(splitk_reduce_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, partial,
-                       bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, ksz, pstride, relu, total);
+                       bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, ksz, pstride, relu, total, fdPQ2,
+                       fdPP, fdK);
   return hipGetLastError();
 }
 
