@@ -147,8 +147,8 @@ def run_stack(N, reps):
         n, c, h, w = cur_shape
         dims = (n, c, h, w, layer.K, layer.R, layer.S, layer.stride, layer.pad)
         P, Q = binding.conv_out_dims(h, w, layer.R, layer.S, layer.stride, layer.pad)
-        v = binding.conv_selected_variant(*dims)
         pooled = li in workloads.STACK_POOL_AFTER
+        v = binding.conv_pool_selected_variant(*dims, 3, 2) if pooled else binding.conv_selected_variant(*dims)
         need = (binding.conv_pool_fwd_workspace_bytes if pooled else binding.conv_fwd_workspace_bytes)(*dims, v)
         ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
         shape = (n, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1) if pooled else (n, layer.K, P, Q)

@@ -145,9 +145,12 @@ double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, i
  * `out`.  When the variant splits the reduction the pooling is folded into the
  * reduction kernel (two kernels in all instead of three); otherwise the convolution
  * writes to the workspace and a pooling kernel follows.  Values are those of
- * conv_fwd_ex followed by maxpool_fwd, bit for bit.
+ * conv_fwd_ex with the same variant followed by maxpool_fwd, bit for bit (with
+ * variant_id = -1 the two entry points may pick different variants, whose sums differ
+ * in rounding order).
  *   workspace: at least conv_pool_fwd_workspace_bytes(...) bytes, 256-byte aligned,
- *     always needed.  variant_id as for conv_fwd_ex.
+ *     always needed (with variant_id = -1 the query covers any window and alignment).
+ *     variant_id as for conv_fwd_ex; -1 = conv_pool_selected_variant's choice.
  * Errors as conv_fwd_ex, plus BCONV_EINVAL for a non-positive window or step and
  * BCONV_ESHAPE when the window is larger than the convolution's output. */
 int conv_pool_fwd_ex(const float* in, const float* filt, const float* bias, float* out,
@@ -156,6 +159,12 @@ int conv_pool_fwd_ex(const float* in, const float* filt, const float* bias, floa
                      size_t workspace_bytes, void* hip_stream, int variant_id);
 size_t conv_pool_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
                                      int stride, int pad, int variant_id);
+/* The variant conv_pool_fwd_ex runs with variant_id = -1 and suitably aligned pointers:
+ * its own measured choice where one is listed for this shape and a 3x3 / step-2 window
+ * (per-operation variant choice, Section VI), else conv_selected_variant's.  Negative
+ * status on an invalid shape or window. */
+int conv_pool_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride,
+                               int pad, int pool_ksz, int pool_stride);
 
 /* Measurement aid: launches `workgroups` workgroups of 256 threads that each issue
  * iters * 16 fp32 32x32x2 MFMAs per wave from registers only (iters * 16 * 4096 flops per

@@ -24,6 +24,7 @@ EXPORTS = {
     "conv_fwd_workspace_bytes": ([_i] * 10, _sz),
     "conv_pool_fwd_ex": ([_vp] * 4 + [_i] * 12 + [_vp, _sz, _vp, _i], _i),
     "conv_pool_fwd_workspace_bytes": ([_i] * 10, _sz),
+    "conv_pool_selected_variant": ([_i] * 11, _i),
     "sgemm": ([_vp] * 3 + [_i] * 3, _i),
     "sgemm_ex": ([_vp] * 3 + [_i] * 3 + [_vp, _sz, _vp, _i], _i),
     "sgemm_workspace_bytes": ([_i] * 4, _sz),
@@ -243,6 +244,14 @@ def conv_selected_variant(N, C, H, W, K, R, S, stride, pad):
     v = int(lib().conv_selected_variant(N, C, H, W, K, R, S, stride, pad))
     if v < 0:
         raise BconvError(v, "conv_selected_variant")
+    return v
+
+
+def conv_pool_selected_variant(N, C, H, W, K, R, S, stride, pad, pool_ksz, pool_stride):
+    v = int(lib().conv_pool_selected_variant(N, C, H, W, K, R, S, stride, pad, int(pool_ksz),
+                                             int(pool_stride)))
+    if v < 0:
+        raise BconvError(v, "conv_pool_selected_variant")
     return v
 
 

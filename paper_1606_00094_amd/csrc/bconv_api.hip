@@ -68,6 +68,11 @@ struct TableRow {
 static const TableRow kTable[] = {
 #include "selection_table.inc"
     {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
+// Choices for convolution + 3x3 / step-2 max pooling in one call, where the best one differs
+// from the convolution's own (a split variant carries the pooling in its reduction kernel).
+static const TableRow kPoolTable[] = {
+#include "pool_selection_table.inc"
+    {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
 
 static int find_variant(const char* tile, int nsplit) {
   for (int t = 0; t < kNumTiles; ++t)
@@ -166,8 +171,9 @@ static int select_variant(const Shape& s, bool filt_aligned16 = true, bool in_al
   return id;
 }
 
-static int select_variant_uncached(const Shape& s, bool filt_aligned16, bool in_aligned16) {
-  for (const TableRow* r = kTable; r->tile; ++r) {
+// The table's variant for this exact shape if the pointers allow its loads, else -1.
+static int table_lookup(const TableRow* table, const Shape& s, bool filt_aligned16, bool in_aligned16) {
+  for (const TableRow* r = table; r->tile; ++r) {
     if (r->N == s.N && r->C == s.C && r->H == s.H && r->W == s.W && r->K == s.K && r->R == s.R &&
         r->S == s.S && r->stride == s.stride && r->pad == s.pad) {
       int id = find_variant(r->tile, r->nsplit);
@@ -179,6 +185,23 @@ static int select_variant_uncached(const Shape& s, bool filt_aligned16, bool in_
         return id;
     }
   }
+  return -1;
+}
+
+// Convolution + pooling in one call: the pooled table covers windows of 3 with step 2
+// (the pooling of the benchmark stack); everything else takes the convolution's choice.
+static int select_pool_variant(const Shape& s, int ksz, int pstride, bool filt_aligned16,
+                               bool in_aligned16) {
+  if (ksz == 3 && pstride == 2) {
+    const int id = table_lookup(kPoolTable, s, filt_aligned16, in_aligned16);
+    if (id > 0) return id;
+  }
+  return select_variant(s, filt_aligned16, in_aligned16);
+}
+
+static int select_variant_uncached(const Shape& s, bool filt_aligned16, bool in_aligned16) {
+  const int listed = table_lookup(kTable, s, filt_aligned16, in_aligned16);
+  if (listed > 0) return listed;
   int best = 0;
   double best_cost = 0.0;
   for (int t = 0; t < kNumTiles; ++t) {
@@ -291,7 +314,7 @@ static int run_conv_pool(const float* in, const float* filt, const float* bias, 
                          hipStream_t st, int variant_id) {
   const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & 15u) == 0;
   const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
-  if (variant_id < 0) variant_id = select_variant(s, aligned16, in_aligned16);
+  if (variant_id < 0) variant_id = select_pool_variant(s, ksz, pstride, aligned16, in_aligned16);
   const size_t need = conv_pool_need(s, variant_id);
   if (need == 0) return BCONV_EVARIANT;
   if (!ws || ws_bytes < need) return BCONV_EWORKSPACE;
@@ -512,10 +535,23 @@ size_t conv_pool_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, i
   if (variant_id >= 0) return variant_id < kNumVariants ? conv_pool_need(s, variant_id) : 0;
   size_t need = 0;
   for (int mask = 0; mask < 4; ++mask) {     // whichever loads the pointers turn out to allow
+    // (the pooling window is not known here: enough for the pooled table's choice too)
     const size_t n = conv_pool_need(s, select_variant(s, (mask & 1) != 0, (mask & 2) != 0));
+    const size_t m = conv_pool_need(s, select_pool_variant(s, 3, 2, (mask & 1) != 0, (mask & 2) != 0));
     if (n > need) need = n;
+    if (m > need) need = m;
   }
   return need;
+}
+
+int conv_pool_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               int pool_ksz, int pool_stride) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (pool_ksz <= 0 || pool_stride <= 0) return BCONV_EINVAL;
+  if (s.P < pool_ksz || s.Q < pool_ksz) return BCONV_ESHAPE;
+  return select_pool_variant(s, pool_ksz, pool_stride, true, true);
 }
 
 size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,

@@ -60,6 +60,77 @@ def sweep_layer(layer, N, check=True, max_split=32):
     return rows
 
 
+def sweep_layer_pooled(layer, N, max_split=32, ksz=3, pstride=2):
+    """The same sweep through the convolution + pooling call: a variant that splits the
+    reduction carries the pooling in its reduction kernel, one without pays a pooling
+    kernel, so the ranking differs from the convolution's own."""
+    dev = torch.device("cuda:0")
+    x, f, b = workloads.make_layer_inputs(layer, N)
+    xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
+    dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+    P, Q = workloads.out_hw(layer)
+    conv = torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)
+    binding.conv_fwd_ex(xd, fd, bd, conv, layer.stride, layer.pad, True, variant=0)
+    ref = torch.empty((N, layer.K, (P - ksz) // pstride + 1, (Q - ksz) // pstride + 1),
+                      dtype=torch.float32, device=dev)
+    binding.maxpool_fwd(conv, ref, ksz, pstride)
+    out = torch.empty_like(ref)
+    rows = []
+    for v in range(1, binding.conv_num_variants()):
+        if not binding.conv_variant_applicable(*dims, v):
+            continue
+        if _split_of(binding.conv_variant_name(v)) > max_split:
+            continue
+        need = binding.conv_pool_fwd_workspace_bytes(*dims, v)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+
+        def run():
+            binding.conv_pool_fwd_ex(xd, fd, bd, out, layer.stride, layer.pad, True, ksz, pstride, ws,
+                                     variant=v)
+        us = graph_time_us(run, best=True)
+        err = (out - ref).abs()
+        ok = bool((err <= torch.clamp(ref.abs() * 1e-4, min=1e-5) * 2).all())
+        rows.append({"variant": binding.conv_variant_name(v), "us": round(us, 2), "ok": ok})
+        del ws
+    rows.sort(key=lambda r: r["us"])
+    return rows
+
+
+def main_pooled(args, batches, names):
+    """--pool: rows for pool_selection_table.inc, for the layers a 3x3 / step-2 pooling
+    follows; a row is written only where the pooled best beats the convolution's own
+    choice run through the same call by more than 2 %."""
+    layers = [l for l in workloads.POOLED_LAYERS if not names or l.name in names]
+    results, table = [], []
+    for layer in layers:
+        for N in batches:
+            rows = sweep_layer_pooled(layer, N, max_split=args.max_split or (32 if N <= 2 else 12 if N <= 8 else 6))
+            good = [r for r in rows if r["ok"]]
+            dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+            own = binding.conv_variant_name(binding.conv_selected_variant(*dims))
+            own_us = next((r["us"] for r in rows if r["variant"] == own), None)
+            best = good[0] if good else None
+            results.append({"layer": layer.name, "N": N, "best": best, "all": rows,
+                            "conv_choice": own, "conv_choice_us": own_us})
+            print("%-18s N=%-3d pooled best %-26s %8.2f us; convolution's choice %s %s"
+                  % (layer.name, N, best["variant"] if best else "-", best["us"] if best else 0, own,
+                     "%.2f us" % own_us if own_us else "-"), flush=True)
+            if best and own_us and best["variant"] != own and best["us"] < 0.98 * own_us:
+                tile, split = best["variant"].split("/s")
+                table.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, "%s", %s},  // %s N=%d: %.1f us (convolution\'s choice %s: %.1f)'
+                             % (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride,
+                                layer.pad, tile, split, layer.name, N, best["us"], own, own_us))
+    with open(args.out, "w") as fh:
+        json.dump(results, fh, indent=1)
+    with open(args.table, "w") as fh:
+        fh.write("// Variant choices for convolution + 3x3 / step-2 max pooling in one call, written by the\n"
+                 "// offline tuning sweep (paper_1606_00094_amd/tune.py --pool).  Only shapes whose best\n"
+                 "// pooled variant differs from the convolution's own choice are listed.\n"
+                 "// Row: {N, C, H, W, K, R, S, stride, pad, \"tile\", nsplit},\n")
+        fh.write("\n".join(table) + ("\n" if table else ""))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="tune.json")
@@ -69,10 +140,14 @@ def main():
     ap.add_argument("--extra", action="store_true",
                     help="also sweep the shapes kept out of the table (heuristic quality check)")
     ap.add_argument("--sgemm", action="store_true", help="also sweep the square matrix products")
+    ap.add_argument("--pool", action="store_true",
+                    help="sweep the convolution + pooling call instead (rows for pool_selection_table.inc)")
     ap.add_argument("--max-split", type=int, default=0, help="largest reduction split to try (0: by batch)")
     args = ap.parse_args()
     batches = [int(t) for t in args.batches.split(",")]
     names = [t for t in args.layers.split(",") if t]
+    if args.pool:
+        return main_pooled(args, batches, names)
     # the square matrix products (batch 1 only) are swept when named, or with --sgemm
     pool = workloads.ALL_LAYERS + (workloads.SGEMM_LAYERS if args.sgemm or names else []) + \
         (workloads.EXTRA_LAYERS if args.extra or names else [])

@@ -174,3 +174,32 @@ def test_every_selection_table_row_resolves_to_its_variant():
         dims = tuple(int(v) for v in row[:9])
         want = "%s/s%s" % (row[9], row[10])
         assert binding.conv_variant_name(binding.conv_selected_variant(*dims)) == want, (dims, want)
+
+
+def test_pooled_selection_table_rows_and_fallback():
+    """Each row of the convolution + pooling table comes back as written for a 3x3 / step-2
+    window and is applicable; any other window, and any shape the table does not list, takes
+    the convolution's own choice; the variant -1 workspace query covers both choices."""
+    path = os.path.join(ROOT, "paper_1606_00094_amd", "csrc", "pool_selection_table.inc")
+    rows = re.findall(r'\{(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), "(\w+)", (\d+)\}',
+                      open(path).read())
+    assert rows
+    for row in rows:
+        dims = tuple(int(v) for v in row[:9])
+        want = "%s/s%s" % (row[9], row[10])
+        v = binding.conv_pool_selected_variant(*dims, 3, 2)
+        assert binding.conv_variant_name(v) == want, (dims, want)
+        assert binding.conv_variant_applicable(*dims, v)
+        own = binding.conv_selected_variant(*dims)
+        assert own != v                                   # listed only where it differs
+        assert binding.conv_pool_selected_variant(*dims, 2, 2) == own
+        need = binding.conv_pool_fwd_workspace_bytes(*dims, -1)
+        assert need >= binding.conv_pool_fwd_workspace_bytes(*dims, v)
+        assert need >= binding.conv_pool_fwd_workspace_bytes(*dims, own)
+    dims = (3, 24, 13, 11, 40, 3, 3, 1, 1)                # not a table shape
+    assert binding.conv_pool_selected_variant(*dims, 3, 2) == binding.conv_selected_variant(*dims)
+    lib = binding.lib()
+    assert lib.conv_pool_selected_variant(*dims, 0, 2) == -1
+    assert lib.conv_pool_selected_variant(*dims, 3, 0) == -1
+    assert lib.conv_pool_selected_variant(*dims, 14, 1) == -3
+    assert lib.conv_pool_selected_variant(1, 0, 13, 11, 40, 3, 3, 1, 1, 3, 2) < 0

@@ -324,7 +324,10 @@ def test_conv_pool_on_the_stack_layers(layer, N):
     two calls."""
     x, f, b, s, p = _layer_case(layer, N)
     got = gpu_conv_pool(x, f, b, s, p, True, 3, 2)
-    two = gpu_conv(x, f, b, s, p, True)
+    # the same variant through the two calls (the pooled call's own choice may differ from the
+    # convolution's, and another variant sums in another order)
+    v = binding.conv_pool_selected_variant(N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, s, p, 3, 2)
+    two = gpu_conv(x, f, b, s, p, True, variant=v)
     dev = torch.device("cuda:0")
     pooled = torch.empty(got.shape, dtype=torch.float32, device=dev)
     binding.maxpool_fwd(torch.from_numpy(two).to(dev), pooled, 3, 2)
@@ -333,6 +336,19 @@ def test_conv_pool_on_the_stack_layers(layer, N):
     for n in sorted({0, N // 2, N - 1}):
         ref = oracle.maxpool_fwd(oracle.conv_fwd(x[n:n + 1], f, b, stride=s, pad=p, relu=True), 3, 2)
         assert_close(got[n:n + 1], ref, "%s N=%d image %d" % (layer.name, N, n))
+
+
+def test_conv_pool_rows_of_the_pooled_table():
+    """Shapes whose convolution + pooling choice differs from the convolution's own (variant
+    -1 takes the pooled table's row): against the oracle's convolution followed by its pooling."""
+    for layer, N in ((workloads.CONV1, 2), (workloads.CONV2, 4), (workloads.CONV5, 1)):
+        dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        assert binding.conv_pool_selected_variant(*dims, 3, 2) != binding.conv_selected_variant(*dims)
+        x, f, b, s, p = _layer_case(layer, N)
+        got = gpu_conv_pool(x, f, b, s, p, True, 3, 2)
+        for n in sorted({0, N - 1}):
+            ref = oracle.maxpool_fwd(oracle.conv_fwd(x[n:n + 1], f, b, stride=s, pad=p, relu=True), 3, 2)
+            assert_close(got[n:n + 1], ref, "%s N=%d image %d" % (layer.name, N, n))
 
 
 def test_conv_pool_forced_variants_windows_and_no_relu():

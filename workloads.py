@@ -36,6 +36,9 @@ CONFIG_MIDDLE = [CONV2, CONV3, CONV4, CONV5]
 CONFIG_POINTWISE = [PW_A, PW_B, PW_C, RED3, RED5]
 STACK = [CONV1, CONV2, CONV3, CONV4, CONV5]   # 3x3/s2 max-pool after conv1 and conv2
 STACK_POOL_AFTER = (0, 1)
+# Layers that a 3x3 / step-2 max pooling follows in the network the stack is cut from
+# (swept through the convolution + pooling call by the tuner).
+POOLED_LAYERS = [CONV1, CONV2, CONV5]
 ALL_LAYERS = CONFIG_TOY + CONFIG_FIRST + CONFIG_MIDDLE + CONFIG_POINTWISE
 
 # Square single-precision matrix products at the sizes of the paper's two SGEMM
