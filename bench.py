@@ -309,6 +309,28 @@ def main():
     for row in sgemm:
         log(json.dumps({"sgemm": row}))
 
+    # ---- one isolated call, host clock: from the call until the host sees it complete
+    # (library host code + launch + kernel(s) + completion signal), median of 30
+    single = []
+    if not args.no_layer_table:
+        for l, N in ((workloads.TOY, 1), (workloads.CONV3, 1), (workloads.CONV2, args.batch)):
+            ps = LayerProblem(l, N)
+            for _ in range(3):
+                ps.launch()
+            times = []
+            for _ in range(30):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ps.launch()
+                torch.cuda.synchronize()
+                times.append(time.perf_counter() - t0)
+            times.sort()
+            single.append({"layer": l.name, "N": N, "wall_us": round(times[len(times) // 2] * 1e6, 1),
+                           "min_us": round(times[0] * 1e6, 1)})
+            del ps
+    for row in single:
+        log(json.dumps({"single_launch": row}))
+
     # what the machine at hand sustains, beside the published peaks: a register-only MFMA
     # loop through the library, and a large device-to-device copy
     measured = None
@@ -339,7 +361,8 @@ def main():
                                if not args.layers else
                                "layers %s at batch %d, bias + ReLU fused" % (args.layers, args.batch),
                    "batch": args.batch, "gflop_per_step": round(total_flops / 1e9, 2)},
-        "roofline": roof, "cpu_baseline": cpu, "layers": table, "layers_f16_storage": table_f16, "stack": stack, "sgemm": sgemm, "measured_peaks": measured,
+        "roofline": roof, "cpu_baseline": cpu, "layers": table, "layers_f16_storage": table_f16, "stack": stack, "sgemm": sgemm, "single_launch": single,
+        "measured_peaks": measured,
     }), flush=True)
 
 
