@@ -411,6 +411,65 @@ def gpu_stack(img, params):
     return [(a.cpu().numpy(), o.cpu().numpy()) for a, o in acts]
 
 
+def test_stack_captured_in_a_graph_replays_like_eager_launches():
+    """The benchmark times replayed HIP graphs of library calls.  The five-layer chain at
+    batch 2 (split variants, so reduction kernels and the fused reduction + pooling are in it)
+    is captured once and replayed on three different images written into the same input
+    buffer, with eager work and synchronisations in between; every replay must equal the
+    eager launches on that image bit for bit."""
+    N = 2
+    dev = torch.device("cuda:0")
+    img, params = workloads.make_stack_inputs(N)
+    x = torch.from_numpy(img).to(dev)
+    plan, cur = [], x
+    for li, (layer, (f, b)) in enumerate(zip(workloads.STACK, params)):
+        n, c, h, w = cur.shape
+        dims = (n, c, h, w, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        P, Q = binding.conv_out_dims(h, w, layer.R, layer.S, layer.stride, layer.pad)
+        pooled = li in workloads.STACK_POOL_AFTER
+        need = (binding.conv_pool_fwd_workspace_bytes if pooled else binding.conv_fwd_workspace_bytes)(*dims, -1)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        shape = (n, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1) if pooled else (n, layer.K, P, Q)
+        out = torch.empty(shape, dtype=torch.float32, device=dev)
+        plan.append((cur, torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev), out, layer, ws, pooled))
+        cur = out
+    last = cur
+
+    def chain():
+        for i, f, b, o, layer, ws, pooled in plan:
+            if pooled:
+                binding.conv_pool_fwd_ex(i, f, b, o, layer.stride, layer.pad, True, 3, 2, ws)
+            else:
+                binding.conv_fwd_ex(i, f, b, o, layer.stride, layer.pad, True, workspace=ws)
+
+    chain()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        chain()
+    for rep in range(3):
+        new_img = workloads.make_random_problem(900 + rep, N, 3, 227, 227, 1, 1, 1)[0]
+        x.copy_(torch.from_numpy(np.abs(new_img)).to(dev))
+        chain()
+        torch.cuda.synchronize()
+        eager = last.clone()
+        last.fill_(-3.0)                        # eager work between the replays
+        for _, _, _, o, _, ws, _ in plan:
+            ws.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(last, eager), "replay %d differs from the eager launches" % rep
+        assert float(eager.abs().max()) > 0.0
+    del g
+
+
 @pytest.mark.parametrize("N", [1, 5])
 def test_five_layer_stack(N):
     img, params = workloads.make_stack_inputs(N)
