@@ -411,6 +411,58 @@ def gpu_stack(img, params):
     return [(a.cpu().numpy(), o.cpu().numpy()) for a, o in acts]
 
 
+def test_concurrent_host_threads_and_streams():
+    """Two host threads, each with its own stream, workspace and tensors, call the library at
+    the same time (ctypes releases the interpreter lock): shapes from the table and shapes
+    the heuristic has to plan (the selection cache is shared).  Every result must equal the
+    one the same call gives when run alone."""
+    import threading
+    dev = torch.device("cuda:0")
+    shapes = [(1, 256, 13, 13, 384, 3, 3, 1, 1), (2, 40, 17, 19, 24, 3, 3, 1, 1), (1, 480, 14, 14, 192, 1, 1, 1, 0),
+              (3, 24, 21, 9, 50, 5, 5, 1, 2), (2, 7, 30, 30, 33, 7, 7, 2, 3), (1, 100, 9, 9, 70, 1, 1, 2, 0)]
+    jobs = []
+    for i, (N, C, H, W, K, R, S, stride, pad) in enumerate(shapes):
+        x, f, b = workloads.make_random_problem(4000 + i, N, C, H, W, K, R, S)
+        xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
+        P, Q = binding.conv_out_dims(H, W, R, S, stride, pad)
+        need = binding.conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, -1)
+        jobs.append((xd, fd, bd, stride, pad, (N, K, P, Q), need))
+    alone = []
+    for xd, fd, bd, stride, pad, oshape, need in jobs:
+        out = torch.empty(oshape, dtype=torch.float32, device=dev)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+        binding.conv_fwd_ex(xd, fd, bd, out, stride, pad, True, workspace=ws)
+        torch.cuda.synchronize()
+        alone.append(out.clone())
+    errors = []
+
+    def worker(order):
+        try:
+            stream = torch.cuda.Stream()
+            outs = [torch.empty(j[5], dtype=torch.float32, device=dev) for j in jobs]
+            wss = [torch.zeros(max(1, (j[6] + 3) // 4), dtype=torch.float32, device=dev) for j in jobs]
+            stream.wait_stream(torch.cuda.default_stream())
+            for rep in range(10):
+                for i in order:
+                    xd, fd, bd, stride, pad, _, _ = jobs[i]
+                    binding.conv_fwd_ex(xd, fd, bd, outs[i], stride, pad, True, workspace=wss[i], stream=stream)
+            stream.synchronize()
+            for i in order:
+                if not torch.equal(outs[i], alone[i]):
+                    errors.append("shape %d differs" % i)
+        except Exception as e:      # reported by the main thread
+            errors.append(repr(e))
+
+    torch.cuda.synchronize()
+    threads = [threading.Thread(target=worker, args=(o,)) for o in ([0, 1, 2, 3, 4, 5], [5, 3, 1, 4, 2, 0])]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+
+
 def test_stack_captured_in_a_graph_replays_like_eager_launches():
     """The benchmark times replayed HIP graphs of library calls.  The five-layer chain at
     batch 2 (split variants, so reduction kernels and the fused reduction + pooling are in it)
