@@ -24,6 +24,13 @@
  *     null stream).
  *   - Return value: BCONV_OK (0) or a negative bconv_status; on error nothing
  *     has been launched.  No C++ exception crosses the boundary.
+ *   - Tensor sizes: up to 2^40 elements each.  One launch of a tiled kernel addresses
+ *     at most 2 GiB of input and 2^31 output elements; a larger batch is computed
+ *     as consecutive launches over runs of whole images (the images of a batch are
+ *     independent, Section II), all inside the one call and on its stream.  The
+ *     variant queries below then describe the launch over a full run, and a forced
+ *     variant must be able to run every run.  A single image beyond those limits
+ *     goes to the direct kernel (64-bit indexing).
  *   - One scalar stride and one scalar pad apply to both axes (Section II:
  *     kernel size and stride taken as scalars); R and S are independent.
  *     No groups, no dilation.

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <type_traits>
 #include <unordered_map>
 
 #include "../../include/bconv.h"
@@ -57,6 +58,44 @@ static int make_shape(int N, int C, int H, int W, int K, int R, int S, int strid
     return BCONV_ESHAPE;
   *s = Shape{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q};
   return BCONV_OK;
+}
+
+// ------------------------------------------------------------------ batch runs
+// One launch of a tiled kernel addresses its input through 32-bit byte offsets and its
+// output through 31-bit element offsets.  The images of a batch are independent
+// (Section II), so a larger batch is computed as consecutive launches over runs of whole
+// images, every run but the last of the size returned here (near-equal runs); s.N when
+// one launch takes the whole batch.  When not even one image fits, the whole batch is
+// one run again: no tile applies to it and the direct kernel (64-bit indexing) takes it.
+static int images_per_launch(const Shape& s) {
+  const long long i31 = (1LL << 31) - 1;
+  const long long in_img = (long long)s.C * s.H * s.W, out_img = (long long)s.K * s.P * s.Q;
+  long long n = (i31 / 4 - ((long long)s.pad * s.W + s.pad)) / in_img;
+  if (i31 / out_img < n) n = i31 / out_img;
+  if (n >= s.N || n < 1) return s.N;
+  const long long launches = (s.N + n - 1) / n;
+  return (int)((s.N + launches - 1) / launches);
+}
+
+static Shape batch_of(const Shape& s, int n) {
+  Shape c = s;
+  c.N = n;
+  return c;
+}
+
+// The (at most two) distinct run shapes of a batch: every full run, and the shorter last one.
+static int run_shapes(const Shape& s, Shape out[2]) {
+  const int per = images_per_launch(s);
+  out[0] = batch_of(s, per);
+  if (s.N % per == 0) return 1;
+  out[1] = batch_of(s, s.N % per);
+  return 2;
+}
+
+template <typename P>
+static P* byte_offset(P* ptr, size_t bytes) {
+  typedef std::conditional_t<std::is_const<P>::value, const char, char> byte_t;
+  return reinterpret_cast<P*>(reinterpret_cast<byte_t*>(ptr) + bytes);
 }
 
 // ------------------------------------------------------------------ selection
@@ -255,14 +294,19 @@ static int internal_workspace(size_t need, void** out) {
 // ------------------------------------------------------------------ run
 // f16: in, filt and out hold _Float16 elements (passed through float pointers); the
 // tiles' 4-element loads then need 8-byte instead of 16-byte alignment.
-static int run_conv(const float* in, const float* filt, const float* bias, float* out,
-                    const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
-                    hipStream_t st, int variant_id, bool f16 = false) {
+// One launch (plus its reduction kernel) over a batch that a single launch can address.
+// dry: resolve the variant and check everything a launch would, store the workspace need
+// in *need_out, and return before allocating or launching anything.
+static int run_conv_launch(const float* in, const float* filt, const float* bias, float* out,
+                           const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
+                           hipStream_t st, int variant_id, bool f16, bool dry, size_t* need_out) {
   const uintptr_t vec_mask = f16 ? 7u : 15u;
   const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & vec_mask) == 0;
   const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & vec_mask) == 0;
   if (variant_id < 0) variant_id = select_variant(s, aligned16, in_aligned16);
+  if (need_out) *need_out = 0;
   if (variant_id == 0) {
+    if (dry) return BCONV_OK;
     return launch_direct_conv(in, filt, bias, out, s, relu, f16, st) == hipSuccess ? BCONV_OK
                                                                                    : BCONV_ELAUNCH;
   }
@@ -272,14 +316,18 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
   if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
   if (kTiles[t].AV == 4 && !aligned16) return BCONV_EVARIANT;
   if (kTiles[t].BV == kModeCompact4 && !in_aligned16) return BCONV_EVARIANT;
+  if (need_out) *need_out = pl.ws_bytes;
   if (pl.ws_bytes) {
     if (own_ws) {
-      int rc = internal_workspace(pl.ws_bytes, &ws);
-      if (rc != BCONV_OK) return rc;
+      if (!dry) {
+        int rc = internal_workspace(pl.ws_bytes, &ws);
+        if (rc != BCONV_OK) return rc;
+      }
     } else if (!ws || ws_bytes < pl.ws_bytes) {
       return BCONV_EWORKSPACE;
     }
   }
+  if (dry) return BCONV_OK;
   pl.p.in = in;
   pl.p.filt = filt;
   pl.p.bias = bias;
@@ -292,6 +340,38 @@ static int run_conv(const float* in, const float* filt, const float* bias, float
     if (launch_splitk_reduce(pl.p.partial, bias, out, nsplit, pl.p.out_elems, s.K, s.P * s.Q, relu,
                              f16, st) != hipSuccess)
       return BCONV_ELAUNCH;
+  }
+  return BCONV_OK;
+}
+
+// The whole batch: one launch, or consecutive launches over runs of images when the
+// tensors are beyond what one launch addresses.  All runs are checked before the first
+// is launched, so that an error leaves nothing enqueued.
+static int run_conv(const float* in, const float* filt, const float* bias, float* out,
+                    const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
+                    hipStream_t st, int variant_id, bool f16 = false) {
+  const int per = images_per_launch(s);
+  if (per >= s.N)
+    return run_conv_launch(in, filt, bias, out, s, relu, ws, ws_bytes, own_ws, st, variant_id, f16,
+                           false, nullptr);
+  const size_t esz = f16 ? 2 : 4;
+  const size_t in_img = (size_t)s.C * s.H * s.W * esz, out_img = (size_t)s.K * s.P * s.Q * esz;
+  size_t need = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int n0 = 0; n0 < s.N; n0 += per) {
+      const Shape run = batch_of(s, s.N - n0 < per ? s.N - n0 : per);
+      size_t n = 0;
+      int rc = run_conv_launch(byte_offset(in, n0 * in_img), filt, bias, byte_offset(out, n0 * out_img),
+                               run, relu, ws, ws_bytes, own_ws, st, variant_id, f16, pass == 0, &n);
+      if (rc != BCONV_OK) return rc;
+      if (n > need) need = n;
+    }
+    if (pass == 0 && own_ws && need) {        // one allocation that serves every run
+      int rc = internal_workspace(need, &ws);
+      if (rc != BCONV_OK) return rc;
+      ws_bytes = need;
+      own_ws = false;
+    }
   }
   return BCONV_OK;
 }
@@ -309,9 +389,9 @@ static size_t conv_pool_need(const Shape& s, int variant_id) {
   return nsplit > 1 ? pl.ws_bytes : conv_bytes;
 }
 
-static int run_conv_pool(const float* in, const float* filt, const float* bias, float* out,
-                         const Shape& s, int relu, int ksz, int pstride, void* ws, size_t ws_bytes,
-                         hipStream_t st, int variant_id) {
+static int run_conv_pool_launch(const float* in, const float* filt, const float* bias, float* out,
+                                const Shape& s, int relu, int ksz, int pstride, void* ws,
+                                size_t ws_bytes, hipStream_t st, int variant_id, bool dry) {
   const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & 15u) == 0;
   const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
   if (variant_id < 0) variant_id = select_pool_variant(s, ksz, pstride, aligned16, in_aligned16);
@@ -323,8 +403,9 @@ static int run_conv_pool(const float* in, const float* filt, const float* bias, 
   float* const scratch = static_cast<float*>(ws);
   if (variant_id == 0 || nsplit == 1) {
     // unpooled output into the workspace (a variant without split needs none of its own)
-    int rc = run_conv(in, filt, bias, scratch, s, relu, nullptr, 0, false, st, variant_id);
-    if (rc != BCONV_OK) return rc;
+    int rc = run_conv_launch(in, filt, bias, scratch, s, relu, nullptr, 0, false, st, variant_id, false,
+                             dry, nullptr);
+    if (rc != BCONV_OK || dry) return rc;
     return launch_maxpool(scratch, out, s.N, s.K, s.P, s.Q, ksz, pstride, (s.P - ksz) / pstride + 1,
                           (s.Q - ksz) / pstride + 1, st) == hipSuccess
                ? BCONV_OK
@@ -334,6 +415,7 @@ static int run_conv_pool(const float* in, const float* filt, const float* bias, 
   if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
   if (kTiles[t].AV == 4 && !aligned16) return BCONV_EVARIANT;
   if (kTiles[t].BV == kModeCompact4 && !in_aligned16) return BCONV_EVARIANT;
+  if (dry) return BCONV_OK;
   pl.p.in = in;
   pl.p.filt = filt;
   pl.p.bias = bias;
@@ -345,6 +427,25 @@ static int run_conv_pool(const float* in, const float* filt, const float* bias, 
                                    pstride, relu, st) == hipSuccess
              ? BCONV_OK
              : BCONV_ELAUNCH;
+}
+
+static int run_conv_pool(const float* in, const float* filt, const float* bias, float* out,
+                         const Shape& s, int relu, int ksz, int pstride, void* ws, size_t ws_bytes,
+                         hipStream_t st, int variant_id) {
+  const int per = images_per_launch(s);
+  if (per >= s.N)
+    return run_conv_pool_launch(in, filt, bias, out, s, relu, ksz, pstride, ws, ws_bytes, st, variant_id,
+                                false);
+  const size_t in_img = (size_t)s.C * s.H * s.W * sizeof(float);
+  const size_t out_img = (size_t)s.K * ((s.P - ksz) / pstride + 1) * ((s.Q - ksz) / pstride + 1) * sizeof(float);
+  for (int pass = 0; pass < 2; ++pass)
+    for (int n0 = 0; n0 < s.N; n0 += per) {
+      const Shape run = batch_of(s, s.N - n0 < per ? s.N - n0 : per);
+      int rc = run_conv_pool_launch(byte_offset(in, n0 * in_img), filt, bias, byte_offset(out, n0 * out_img),
+                                    run, relu, ksz, pstride, ws, ws_bytes, st, variant_id, pass == 0);
+      if (rc != BCONV_OK) return rc;
+    }
+  return BCONV_OK;
 }
 
 // ------------------------------------------------------------------ audit
@@ -528,10 +629,8 @@ int conv_pool_fwd_ex(const float* in, const float* filt, const float* bias, floa
                        workspace_bytes, static_cast<hipStream_t>(hip_stream), variant_id);
 }
 
-size_t conv_pool_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
-                                     int pad, int variant_id) {
-  Shape s;
-  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+// Workspace of one run shape (see run_shapes); 0 when a forced variant cannot run it.
+static size_t conv_pool_need_any_alignment(const Shape& s, int variant_id) {
   if (variant_id >= 0) return variant_id < kNumVariants ? conv_pool_need(s, variant_id) : 0;
   size_t need = 0;
   for (int mask = 0; mask < 4; ++mask) {     // whichever loads the pointers turn out to allow
@@ -544,6 +643,19 @@ size_t conv_pool_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, i
   return need;
 }
 
+size_t conv_pool_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                     int pad, int variant_id) {
+  Shape s, runs[2];
+  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+  size_t need = 0;
+  for (int i = 0, n = run_shapes(s, runs); i < n; ++i) {
+    const size_t b = conv_pool_need_any_alignment(runs[i], variant_id);
+    if (b == 0) return 0;                    // (a conv + pool call always needs a workspace)
+    if (b > need) need = b;
+  }
+  return need;
+}
+
 int conv_pool_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                                int pool_ksz, int pool_stride) {
   Shape s;
@@ -551,15 +663,14 @@ int conv_pool_selected_variant(int N, int C, int H, int W, int K, int R, int S, 
   if (rc != BCONV_OK) return rc;
   if (pool_ksz <= 0 || pool_stride <= 0) return BCONV_EINVAL;
   if (s.P < pool_ksz || s.Q < pool_ksz) return BCONV_ESHAPE;
-  return select_pool_variant(s, pool_ksz, pool_stride, true, true);
+  return select_pool_variant(batch_of(s, images_per_launch(s)), pool_ksz, pool_stride, true, true);
 }
 
-size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
-                                int pad, int variant_id) {
-  Shape s;
-  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+// Workspace of one run shape; *ok = false when a forced variant cannot run it.
+static size_t conv_need_any_alignment(const Shape& s, int variant_id, bool* ok) {
   int t, nsplit;
   Plan pl;
+  *ok = true;
   if (variant_id < 0) {
     // the choice depends on whether in / filt allow the wide loads, which this call
     // cannot know: enough for whichever of the four cases the pointers turn out to be
@@ -571,8 +682,26 @@ size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
     }
     return need;
   }
-  if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return 0;
+  if (variant_id == 0) return 0;
+  if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) {
+    *ok = false;
+    return 0;
+  }
   return pl.ws_bytes;
+}
+
+size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                int pad, int variant_id) {
+  Shape s, runs[2];
+  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+  size_t need = 0;
+  for (int i = 0, n = run_shapes(s, runs); i < n; ++i) {
+    bool ok;
+    const size_t b = conv_need_any_alignment(runs[i], variant_id, &ok);
+    if (!ok) return 0;
+    if (b > need) need = b;
+  }
+  return need;
 }
 
 // C[M x N] = A[M x K] * B[K x N] is the pointwise convolution of one "image" whose
@@ -609,7 +738,7 @@ int conv_selected_variant(int N, int C, int H, int W, int K, int R, int S, int s
   Shape s;
   int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
   if (rc != BCONV_OK) return rc;
-  return select_variant(s);
+  return select_variant(batch_of(s, images_per_launch(s)));
 }
 
 int conv_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -620,8 +749,11 @@ int conv_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int
   if (variant_id == 0) return 1;
   int t, nsplit;
   Plan pl;
+  Shape runs[2];
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
-  return plan_tconv(s, kTiles[t], nsplit, &pl) ? 1 : 0;
+  for (int i = 0, n = run_shapes(s, runs); i < n; ++i)
+    if (!plan_tconv(runs[i], kTiles[t], nsplit, &pl)) return 0;
+  return 1;
 }
 
 long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -633,8 +765,13 @@ long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int
   int t, nsplit;
   Plan pl;
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
-  if (!plan_tconv(s, kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
-  return audit(s, kTiles[t], pl);
+  Shape runs[2];
+  long long bad = 0;
+  for (int i = 0, n = run_shapes(s, runs); i < n; ++i) {
+    if (!plan_tconv(runs[i], kTiles[t], nsplit, &pl)) return BCONV_EVARIANT;
+    bad += audit(runs[i], kTiles[t], pl);
+  }
+  return bad;
 }
 
 double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -643,6 +780,7 @@ double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, i
   if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return -1.0;
   int t, nsplit;
   Plan pl;
+  s = batch_of(s, images_per_launch(s));    // the estimate is per launch
   if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return -1.0;
   return variant_cost(kTiles[t], pl);
 }

@@ -203,3 +203,29 @@ def test_pooled_selection_table_rows_and_fallback():
     assert lib.conv_pool_selected_variant(*dims, 3, 0) == -1
     assert lib.conv_pool_selected_variant(*dims, 14, 1) == -3
     assert lib.conv_pool_selected_variant(1, 0, 13, 11, 40, 3, 3, 1, 1, 3, 2) < 0
+
+
+def test_batches_beyond_one_launch_are_planned_as_runs_of_images():
+    """An input above 2 GiB with more than one image is not a case for the direct kernel:
+    the queries describe near-equal runs of whole images, each within one launch's reach."""
+    layer = (3, 227, 227, 96, 11, 11, 4, 0)                 # 618 KB per image: 3472 images fit one launch
+    one = binding.conv_selected_variant(2000, *layer)
+    assert binding.conv_variant_name(one) != "direct"
+    assert binding.conv_selected_variant(4000, *layer) == one   # two runs of 2000
+    assert binding.conv_variant_applicable(4000, *layer, one) == 1
+    assert binding.conv_fwd_workspace_bytes(4000, *layer, -1) == binding.conv_fwd_workspace_bytes(2000, *layer, -1)
+    split = binding.variant_ids_by_name()["k11s4_32x128_k2_np/s2"]
+    assert binding.conv_fwd_workspace_bytes(4000, *layer, split) == \
+        binding.conv_fwd_workspace_bytes(2000, *layer, split) > 0
+    # 3473 images: one run of 1737 and one of 1736; the workspace covers the larger
+    assert binding.conv_fwd_workspace_bytes(3473, *layer, split) == \
+        binding.conv_fwd_workspace_bytes(1737, *layer, split)
+    assert binding.conv_pool_fwd_workspace_bytes(3473, *layer, split) == \
+        binding.conv_pool_fwd_workspace_bytes(1737, *layer, split)
+    # the unpooled output of one run, not of the whole batch
+    unsplit = binding.variant_ids_by_name()["k11s4_32x128_k2_np/s1"]
+    assert binding.conv_pool_fwd_workspace_bytes(4000, *layer, unsplit) == 2000 * 96 * 55 * 55 * 4
+    # one image that is too large by itself: still the direct kernel
+    assert binding.conv_variant_name(binding.conv_selected_variant(2, 16, 6000, 6000, 2, 3, 3, 1, 0)) == "direct"
+    # small shapes are untouched: an audit over a toy batch counts one launch
+    assert binding.bconv_debug_audit(3, 5, 9, 9, 7, 3, 3, 1, 1, binding.conv_selected_variant(3, 5, 9, 9, 7, 3, 3, 1, 1)) == 0

@@ -696,6 +696,87 @@ def test_input_beyond_two_gib_falls_back_to_64_bit_indexing():
         assert abs(float(got[0, k, p, q]) - float(ref)) <= max(ATOL, RTOL * abs(float(ref))), (k, p, q)
 
 
+def test_batch_beyond_two_gib_runs_as_consecutive_launches():
+    """70 images of 32 MiB (2.3 GiB of input): two runs of 35 images through a tiled kernel,
+    not the direct kernel.  Sampled outputs against the oracle one window at a time, in both
+    runs and on both sides of the seam; the convolution + pooling call on the same tensors
+    equals pooling the convolution's output; half-precision storage takes the same path."""
+    N, C, H, W, K, R, S, stride, pad = 70, 8, 1024, 1024, 4, 3, 3, 2, 0
+    dims = (N, C, H, W, K, R, S, stride, pad)
+    assert N * C * H * W * 4 > 2 ** 31
+    v = binding.conv_selected_variant(*dims)
+    assert v == binding.conv_selected_variant(35, *dims[1:]) and binding.conv_variant_name(v) != "direct"
+    rng = np.random.default_rng(77)
+    x = rng.random((N, C, H, W), dtype=np.float32)
+    f = (rng.standard_normal((K, C, R, S), dtype=np.float32) * np.float32(0.1)).astype(np.float32)
+    b = rng.random(K, dtype=np.float32)
+    dev = torch.device("cuda:0")
+    xd, fd, bd = torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev)
+    P, Q = binding.conv_out_dims(H, W, R, S, stride, pad)
+    out = torch.full((N, K, P, Q), float("nan"), dtype=torch.float32, device=dev)
+    need = binding.conv_fwd_workspace_bytes(*dims, -1)
+    ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+    binding.conv_fwd_ex(xd, fd, bd, out, stride, pad, True, workspace=ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert not np.isnan(got).any()
+    pts = [(0, 0, 0, 0), (34, K - 1, P - 1, Q - 1), (35, 0, 0, 0), (35, 1, P - 1, 0), (69, K - 1, P - 1, Q - 1)] + \
+          [(int(rng.integers(N)), int(rng.integers(K)), int(rng.integers(P)), int(rng.integers(Q)))
+           for _ in range(80)]
+
+    def window(arr, n, p, q):
+        return np.ascontiguousarray(arr[n:n + 1, :, p * stride:p * stride + R, q * stride:q * stride + S])
+
+    for n, k, p, q in pts:
+        ref = oracle.conv_fwd(window(x, n, p, q), f[k:k + 1], b[k:k + 1], stride=1, pad=0, relu=True)[0, 0, 0, 0]
+        assert abs(float(got[n, k, p, q]) - float(ref)) <= max(ATOL, RTOL * abs(float(ref))), (n, k, p, q)
+    # a forced split variant: partial sums and the reduction kernel per run
+    split = binding.variant_ids_by_name()["k3s2_64x64_k12/s2"]
+    assert binding.conv_variant_applicable(*dims, split)
+    need = binding.conv_fwd_workspace_bytes(*dims, split)
+    ws2 = torch.zeros((need + 3) // 4, dtype=torch.float32, device=dev)
+    out2 = torch.full((N, K, P, Q), float("nan"), dtype=torch.float32, device=dev)
+    binding.conv_fwd_ex(xd, fd, bd, out2, stride, pad, True, workspace=ws2, variant=split)
+    torch.cuda.synchronize()
+    got2 = out2.cpu().numpy()
+    for n, k, p, q in pts:
+        assert abs(float(got2[n, k, p, q]) - float(got[n, k, p, q])) <= max(ATOL, RTOL * abs(float(got[n, k, p, q])))
+    # the same variant through the convolution + pooling call: pooling inside each run's reduction
+    pooled_ref = torch.empty((N, K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1), dtype=torch.float32, device=dev)
+    binding.maxpool_fwd(out2, pooled_ref, 3, 2)
+    pooled = torch.full(pooled_ref.shape, float("nan"), dtype=torch.float32, device=dev)
+    assert binding.conv_pool_fwd_workspace_bytes(*dims, split) == need
+    binding.conv_pool_fwd_ex(xd, fd, bd, pooled, stride, pad, True, 3, 2, ws2, variant=split)
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled_ref)
+    del ws2, out2
+    # convolution + pooling over the same runs, the library's own choice
+    pooled_ref = torch.empty((N, K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1), dtype=torch.float32, device=dev)
+    binding.maxpool_fwd(out, pooled_ref, 3, 2)
+    pooled = torch.full(pooled_ref.shape, float("nan"), dtype=torch.float32, device=dev)
+    vp = binding.conv_pool_selected_variant(*dims, 3, 2)
+    assert vp == v
+    need = binding.conv_pool_fwd_workspace_bytes(*dims, -1)
+    assert 0 < need <= 35 * K * P * Q * 4
+    wsp = torch.zeros((need + 3) // 4, dtype=torch.float32, device=dev)
+    binding.conv_pool_fwd_ex(xd, fd, bd, pooled, stride, pad, True, 3, 2, wsp)
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled_ref)
+    del out, pooled, pooled_ref, wsp, xd
+    # half-precision storage (the run length is the fp32 one)
+    xh, fh = x.astype(np.float16), f.astype(np.float16)
+    del x
+    xhd, fhd = torch.from_numpy(xh).to(dev), torch.from_numpy(fh).to(dev)
+    outh = torch.full((N, K, P, Q), float("nan"), dtype=torch.float16, device=dev)
+    binding.conv_fwd_f16_ex(xhd, fhd, bd, outh, stride, pad, True, workspace=ws)
+    torch.cuda.synchronize()
+    goth = outh.cpu().numpy()
+    assert not np.isnan(goth).any()
+    for n, k, p, q in pts:
+        ref = oracle.conv_fwd_f16(window(xh, n, p, q), fh[k:k + 1], b[k:k + 1], stride=1, pad=0, relu=True)[0, 0, 0, 0]
+        assert abs(float(goth[n, k, p, q]) - float(ref)) <= max(1e-5, 2.0 ** -10 * abs(float(ref))), (n, k, p, q)
+
+
 def test_mfma_loop_measurement_aid_runs_and_validates_arguments():
     buf = torch.zeros(8 * 256, dtype=torch.float32, device="cuda:0")
     assert binding.bconv_debug_mfma_loop(buf, 8, 3) == 8 * 4 * 3 * 16 * 4096
