@@ -22,6 +22,10 @@
  *   - Calls only enqueue work on a HIP stream and return; they never
  *     synchronise it.  `hip_stream` is a hipStream_t passed as void* (NULL = the
  *     null stream).
+ *   - Host threads: every entry point may be called from several threads at once.
+ *     Calls that share a workspace, or write the same tensor, must be ordered by
+ *     the caller (one stream, or events); conv_fwd / conv_fwd_f16 / sgemm share the
+ *     library's workspace and order themselves on the null stream.
  *   - Return value: BCONV_OK (0) or a negative bconv_status; on error nothing
  *     has been launched.  No C++ exception crosses the boundary.
  *   - Tensor sizes: up to 2^40 elements each.  One launch of a tiled kernel addresses

@@ -266,6 +266,7 @@ struct DeviceWorkspace {
 };
 static DeviceWorkspace g_ws[64];
 static std::mutex g_ws_mutex;
+static std::mutex g_own_ws_call_mutex;   // held by a call from workspace lookup to its last launch
 
 static int internal_workspace(size_t need, void** out) {
   int dev = 0;
@@ -350,6 +351,10 @@ static int run_conv_launch(const float* in, const float* filt, const float* bias
 static int run_conv(const float* in, const float* filt, const float* bias, float* out,
                     const Shape& s, int relu, void* ws, size_t ws_bytes, bool own_ws,
                     hipStream_t st, int variant_id, bool f16 = false) {
+  // The library's own workspace may be regrown (synchronise, free, allocate) by another host
+  // thread: growing and enqueueing the kernels that use it are one critical section.
+  std::unique_lock<std::mutex> own_ws_lock(g_own_ws_call_mutex, std::defer_lock);
+  if (own_ws) own_ws_lock.lock();
   const int per = images_per_launch(s);
   if (per >= s.N)
     return run_conv_launch(in, filt, bias, out, s, relu, ws, ws_bytes, own_ws, st, variant_id, f16,

@@ -450,6 +450,18 @@ def test_concurrent_host_threads_and_streams():
             for i in order:
                 if not torch.equal(outs[i], alone[i]):
                     errors.append("shape %d differs" % i)
+            # the simple entry point: null stream, the library's own (shared) workspace
+            for o in outs:
+                o.fill_(-1.0)
+            torch.cuda.synchronize()
+            for rep in range(5):
+                for i in order:
+                    xd, fd, bd, stride, pad, _, _ = jobs[i]
+                    binding.conv_fwd(xd, fd, bd, outs[i], stride, pad, True)
+            torch.cuda.synchronize()
+            for i in order:
+                if not torch.equal(outs[i], alone[i]):
+                    errors.append("shape %d differs through conv_fwd" % i)
         except Exception as e:      # reported by the main thread
             errors.append(repr(e))
 
