@@ -202,6 +202,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--big-batch", type=int, default=128,
+                    help="batch of the supplementary per-layer table (0: skip it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer-table", action="store_true")
     ap.add_argument("--cpu-baseline-batch", type=int, default=32)
@@ -276,6 +278,17 @@ def main():
                                    "cold"))
             del p1, pc
     for row in table:
+        log(json.dumps(row))
+
+    # ---- the same layers at a production-size batch (context beside the metric's batch 1
+    # and 32; not part of `value`): more rounds of workgroups, less lost to the last one
+    table_big = []
+    if not args.no_layer_table and args.big_batch > 0:
+        for l in layers:
+            pb = LayerProblem(l, args.big_batch)
+            table_big.append(layer_row(pb, graph_time_us(pb.launch, launches=5, replays=3) * 1e-3, "warm"))
+            del pb
+    for row in table_big:
         log(json.dumps(row))
 
     # ---- the same layers with half-precision storage (fp32 arithmetic): same variants,
@@ -361,7 +374,8 @@ def main():
                                if not args.layers else
                                "layers %s at batch %d, bias + ReLU fused" % (args.layers, args.batch),
                    "batch": args.batch, "gflop_per_step": round(total_flops / 1e9, 2)},
-        "roofline": roof, "cpu_baseline": cpu, "layers": table, "layers_f16_storage": table_f16, "stack": stack, "sgemm": sgemm, "single_launch": single,
+        "roofline": roof, "cpu_baseline": cpu, "layers": table, "layers_batch_%d" % args.big_batch: table_big,
+        "layers_f16_storage": table_f16, "stack": stack, "sgemm": sgemm, "single_launch": single,
         "measured_peaks": measured,
     }), flush=True)
 

@@ -81,6 +81,19 @@ def test_benchmark_layers_batch1(layer):
     assert_close(got, np.maximum(ref, 0), layer.name + " relu=1")
 
 
+@pytest.mark.parametrize("N", [64, 128, 256])
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS[1:], ids=lambda l: l.name)
+def test_benchmark_layers_large_batches_sampled_images(layer, N):
+    """The selection table's rows for batch 64, 128 and 256 (large tiles, many rounds of
+    workgroups): first, middle and last image against the oracle."""
+    x, f, b, s, p = _layer_case(layer, N)
+    got = gpu_conv(x, f, b, s, p, True)
+    for n in (0, N // 2 + 1, N - 1):
+        ref = oracle.conv_fwd(x[n:n + 1], f, b, stride=s, pad=p, relu=True)
+        assert_close(got[n:n + 1], ref, "%s N=%d image %d" % (layer.name, N, n))
+    assert np.isfinite(got).all()
+
+
 @pytest.mark.parametrize("layer", workloads.ALL_LAYERS[1:], ids=lambda l: l.name)
 def test_benchmark_layers_batch32_sampled_images(layer):
     """Full-size launch (the configuration the benchmark times); the oracle
