@@ -91,15 +91,13 @@ def test_f16_benchmark_layers_batch1(layer):
 
 
 @pytest.mark.parametrize("layer", workloads.ALL_LAYERS[1:], ids=lambda l: l.name)
-def test_f16_benchmark_layers_batch32_sampled_images(layer):
+def test_f16_benchmark_layers_batch32_every_image(layer):
     N = 32
     x, f, b, s, p = _layer_case(layer, N)
     for relu in (False, True):
         got = gpu_conv_f16(x, f, b, s, p, relu)
-        for n in (0, 13, 31):
-            ref = oracle.conv_fwd_f16(x[n:n + 1], f, b, stride=s, pad=p, relu=relu)
-            assert_close_f16(got[n:n + 1], ref, "%s N=32 image %d relu=%d" % (layer.name, n, relu))
-        assert np.isfinite(got).all()
+        ref = oracle.conv_fwd_f16(x, f, b, stride=s, pad=p, relu=relu)
+        assert_close_f16(got, ref, "%s N=32 relu=%d" % (layer.name, relu))
 
 
 def test_f16_simple_entry_direct_kernel_and_missing_bias():
