@@ -150,8 +150,8 @@ double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, i
 
 /* Convolution + bias + optional ReLU followed by max pooling (window pool_ksz, step
  * pool_stride, no padding, floor extents) in one call: the next operation of the
- * chain in the networks the paper draws its layers from (Section I-A lists pooling
- * among the deployment primitives).  out is the POOLED tensor N*K*PP*PQ with
+ * chain in the networks the paper draws its layers from (Section II lists pooling
+ * among the operations of a deployed network).  out is the POOLED tensor N*K*PP*PQ with
  * PP = floor((P-pool_ksz)/pool_stride)+1; the unpooled result is never written to
  * `out`.  When the variant splits the reduction the pooling is folded into the
  * reduction kernel (two kernels in all instead of three); otherwise the convolution
@@ -185,8 +185,8 @@ int conv_pool_selected_variant(int N, int C, int H, int W, int K, int R, int S, 
 int bconv_debug_mfma_loop(float* out, int workgroups, int iters, void* hip_stream);
 
 /* Max pooling over ksz x ksz windows stepped by `stride`, no padding, floor
- * extents (the pooling primitive the paper names in Section I-A among the
- * deployment operations; used to chain the five-layer stack).
+ * extents (the pooling operation the paper names in Section II among the
+ * operations of a deployed network; used to chain the five-layer stack).
  * in N*C*H*W -> out N*C*P*Q with P = floor((H-ksz)/stride)+1. */
 int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz,
                 int stride, void* hip_stream);

@@ -150,7 +150,7 @@ int oracle_conv_fwd_exact(const float *in, const float *filt, const float *bias,
     return 0;
 }
 
-/* Max-pooling, named in Section I-A as a deployment primitive; textbook
+/* Max-pooling, named in Section II among the operations of a deployed network; textbook
  * definition: window ksz x ksz, step `stride`, no padding, floor extents.
  * in: N*C*H*W, out: N*C*P*Q with P = floor((H-ksz)/stride)+1. */
 int oracle_maxpool_fwd(const float *in, float *out, int N, int C, int H, int W,

@@ -51,13 +51,11 @@ hipError_t launch_direct_conv(const float* in, const float* filt, const float* b
   long long blocks = (total + 255) / 256;
   if (blocks > 65536 * 16) blocks = 65536 * 16;
   if (f16)
-    hipLaunchKernelGGL(direct_conv_kernel<_Float16>, dim3((unsigned)blocks), dim3(256), 0, st,
-                       reinterpret_cast<const _Float16*>(in), reinterpret_cast<const _Float16*>(filt),
-                       bias, reinterpret_cast<_Float16*>(out), s, relu, total);
-  else
-    hipLaunchKernelGGL(direct_conv_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, in, filt,
+    return launch_kernel(direct_conv_kernel<_Float16>, dim3((unsigned)blocks), dim3(256), 0, st,
+                         reinterpret_cast<const _Float16*>(in), reinterpret_cast<const _Float16*>(filt),
+                         bias, reinterpret_cast<_Float16*>(out), s, relu, total);
+  return launch_kernel(direct_conv_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, in, filt,
                        bias, out, s, relu, total);
-  return hipGetLastError();
 }
 
 // Filter index of output element e of an N x K x PQ tensor: (e / PQ) % K, the two divisions
@@ -159,22 +157,18 @@ hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* 
     if (blocks > 16384) blocks = 16384;
     const float4* p4 = reinterpret_cast<const float4*>(partial);
     if (f16)
-      hipLaunchKernelGGL(splitk_reduce4_kernel<Half4>, dim3(blocks), dim3(256), 0, st, p4, bias,
-                         reinterpret_cast<Half4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK);
-    else
-      hipLaunchKernelGGL(splitk_reduce4_kernel<float4>, dim3(blocks), dim3(256), 0, st, p4, bias,
+      return launch_kernel(splitk_reduce4_kernel<Half4>, dim3(blocks), dim3(256), 0, st, p4, bias,
+                           reinterpret_cast<Half4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK);
+    return launch_kernel(splitk_reduce4_kernel<float4>, dim3(blocks), dim3(256), 0, st, p4, bias,
                          reinterpret_cast<float4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK);
-    return hipGetLastError();
   }
   int blocks = (out_elems + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   if (f16)
-    hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, st, partial, bias,
-                       reinterpret_cast<_Float16*>(out), nsplit, out_elems, K, PQ, relu, fdPQ, fdK);
-  else
-    hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, st, partial, bias, out,
+    return launch_kernel(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, st, partial, bias,
+                         reinterpret_cast<_Float16*>(out), nsplit, out_elems, K, PQ, relu, fdPQ, fdK);
+  return launch_kernel(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, st, partial, bias, out,
                        nsplit, out_elems, K, PQ, relu, fdPQ, fdK);
-  return hipGetLastError();
 }
 
 // Split reduction with the pooling folded in: one thread per pooled output point takes the
@@ -269,14 +263,12 @@ hipError_t launch_splitk_reduce_pool(const float* partial, const float* bias, fl
   const FastDiv fdPQ2 = make_fastdiv((unsigned)PQ2), fdPP = make_fastdiv((unsigned)PP),
                 fdK = make_fastdiv((unsigned)K);
   if (ksz == 3 && pstride == 2)
-    hipLaunchKernelGGL((splitk_reduce_pool_fixed_kernel<3, 2>), dim3((unsigned)blocks), dim3(256), 0, st,
-                       partial, bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, relu, total, fdPQ2, fdPP,
-                       fdK);
-  else
-    hipLaunchKernelGGL(splitk_reduce_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, partial,
+    return launch_kernel(splitk_reduce_pool_fixed_kernel<3, 2>, dim3((unsigned)blocks), dim3(256), 0, st,
+                         partial, bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, relu, total, fdPQ2,
+                         fdPP, fdK);
+  return launch_kernel(splitk_reduce_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, st, partial,
                        bias, out, nsplit, out_elems, K, P, Q, PP, PQ2, ksz, pstride, relu, total, fdPQ2,
                        fdPP, fdK);
-  return hipGetLastError();
 }
 
 // One (image, channel) plane per blockIdx.y (strided when there are more planes than the
@@ -339,14 +331,12 @@ hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int 
     constexpr int kPpt = 4;
     const long long groups = (planes + kPpt - 1) / kPpt;
     const unsigned gy = (unsigned)(groups < 65535 ? groups : 65535);
-    hipLaunchKernelGGL((maxpool_fixed_kernel<3, 2, kPpt>), dim3(gx, gy), dim3(256), 0, st, in, out, H,
-                       W, P, Q, (int)planes);
-    return hipGetLastError();
+    return launch_kernel(maxpool_fixed_kernel<3, 2, kPpt>, dim3(gx, gy), dim3(256), 0, st, in, out, H,
+                         W, P, Q, (int)planes);
   }
   const unsigned gy = (unsigned)(planes < 65535 ? planes : 65535);
-  hipLaunchKernelGGL(maxpool_kernel, dim3(gx, gy), dim3(256), 0, st, in, out, H, W, ksz, stride, P,
-                     Q, (int)planes);
-  return hipGetLastError();
+  return launch_kernel(maxpool_kernel, dim3(gx, gy), dim3(256), 0, st, in, out, H, W, ksz, stride, P,
+                       Q, (int)planes);
 }
 
 // Register-only MFMA loop (no memory traffic in the loop): each wave issues
@@ -371,8 +361,7 @@ void mfma_loop_kernel(float* __restrict__ out, int iters) {
 }
 
 hipError_t launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st) {
-  hipLaunchKernelGGL(mfma_loop_kernel, dim3(workgroups), dim3(256), 0, st, out, iters);
-  return hipGetLastError();
+  return launch_kernel(mfma_loop_kernel, dim3(workgroups), dim3(256), 0, st, out, iters);
 }
 
 }  // namespace bconv

@@ -2,9 +2,23 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "bconv_plan.h"
 
 namespace bconv {
+
+// Launches `kernel` and returns the status of this launch alone.  (A launch written with the
+// triple-bracket syntax reports through hipGetLastError, which also hands back an error that
+// an earlier, unrelated call left behind in the thread: the caller would then be told that
+// nothing was enqueued when the kernel was.)  Arguments convert to the kernel's own
+// parameter types.
+template <typename... P>
+inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes,
+                                hipStream_t st, std::common_type_t<P>... args) {
+  void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, st);
+}
 
 typedef hipError_t (*TileLaunchFn)(const TconvParams& p, dim3 grid, size_t lds_bytes,
                                    hipStream_t st);

@@ -30,8 +30,7 @@ static hipError_t launch_tile_kernel(KernelT kernel, int nthr, const TconvParams
     if (e != hipSuccess) { report("hipFuncSetAttribute", e); (void)hipGetLastError(); return e; }
     lds_allowed[dev].store(lds_bytes, std::memory_order_relaxed);
   }
-  hipLaunchKernelGGL(kernel, grid, dim3(nthr), lds_bytes, st, p);
-  e = hipGetLastError();
+  e = launch_kernel(kernel, grid, dim3(nthr), lds_bytes, st, p);
   if (e != hipSuccess) report("kernel launch", e);
   return e;
 }
