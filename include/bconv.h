@@ -83,6 +83,24 @@ int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* ou
                 int relu, void* workspace, size_t workspace_bytes, void* hip_stream,
                 int variant_id);
 
+/* conv_fwd_ex for callers that cannot allocate device memory or let a library do so: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, same selection-table choice (variant_id = -1), same results bit for bit as
+ * conv_fwd_ex with that variant; the partial sums of a split reduction go to a fixed array of
+ * BCONV_NOALLOC_MAX_WORKSPACE_BYTES = 32 MiB of device memory that is part of the
+ * library's code object (every GPU the library runs on holds one until the process ends).
+ * The call allocates and frees nothing, on the device or through any library.  A shape whose
+ * chosen variant needs more partial-sum space than the array holds
+ * (conv_fwd_workspace_bytes(..., -1) > the maximum) gives BCONV_EWORKSPACE and launches
+ * nothing.  All calls on one GPU share that GPU's array: nothing in it has to start at zero
+ * (every partial sum that is read was written by the same call), but two calls that overlap
+ * in time on one GPU -- different streams, or host threads without ordering -- race on it;
+ * order them on one stream or with events.  Other errors as conv_fwd_ex. */
+#define BCONV_NOALLOC_MAX_WORKSPACE_BYTES ((size_t)32 << 20)
+int conv_fwd_noalloc(const float* in, const float* filt, const float* bias, float* out,
+                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                     int relu, void* hip_stream);
+
 /* The same layer with half-precision storage (Section VII names smaller storage
  * types, half floats, as the next step for bandwidth-limited cases; the arithmetic
  * stays fp32).  in, filt and out are DEVICE pointers to dense IEEE binary16 tensors

@@ -19,6 +19,7 @@ EXPORTS = {
     "conv_out_dims": ([_i] * 6 + [ctypes.POINTER(_i)] * 2, _i),
     "conv_fwd": ([_vp] * 4 + [_i] * 10, _i),
     "conv_fwd_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
+    "conv_fwd_noalloc": ([_vp] * 4 + [_i] * 10 + [_vp], _i),
     "conv_fwd_f16": ([_vp] * 4 + [_i] * 10, _i),
     "conv_fwd_f16_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
     "conv_fwd_workspace_bytes": ([_i] * 10, _sz),
@@ -132,6 +133,22 @@ def conv_fwd(inp, filt, bias, out, stride, pad, relu):
                           _dev_ptr(out, "out"), N, C, H, W, K, R, S, stride, pad,
                           1 if relu else 0), "conv_fwd")
     return out
+
+
+def conv_fwd_noalloc(inp, filt, bias, out, stride, pad, relu, stream=None):
+    """conv_fwd_noalloc of the C ABI (selection table, partial sums in the library's static
+    device array, no allocation); enqueues on `stream` (default: torch's current stream)."""
+    N, C, H, W, K, R, S = _dims(inp, filt)
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    if tuple(out.shape) != (N, K, P, Q):
+        raise ValueError("out must have shape %s" % ((N, K, P, Q),))
+    _check(lib().conv_fwd_noalloc(_dev_ptr(inp, "in"), _dev_ptr(filt, "filt"), _dev_ptr(bias, "bias"),
+                                  _dev_ptr(out, "out"), N, C, H, W, K, R, S, stride, pad,
+                                  1 if relu else 0, _stream_handle(stream)), "conv_fwd_noalloc")
+    return out
+
+
+NOALLOC_MAX_WORKSPACE_BYTES = 32 << 20   # BCONV_NOALLOC_MAX_WORKSPACE_BYTES of include/bconv.h
 
 
 def conv_fwd_f16_ex(inp, filt, bias, out, stride, pad, relu, workspace=None, stream=None,

@@ -292,6 +292,30 @@ static int internal_workspace(size_t need, void** out) {
   return BCONV_OK;
 }
 
+// ------------------------------------------------------------------ static scratch
+// Device memory for the partial sums of conv_fwd_noalloc: part of the library's code object,
+// so every GPU that loads the library holds its own copy until the process ends and no call
+// ever allocates.  In host code the array's name is only a handle for the runtime's symbol
+// lookup, never an address: the per-device address comes from hipGetSymbolAddress, once per
+// device with that device current, and that pointer is what kernels are given.
+constexpr size_t kStaticScratchBytes = BCONV_NOALLOC_MAX_WORKSPACE_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[64];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BCONV_ELAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return BCONV_ELAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return BCONV_OK;
+}
+
 // ------------------------------------------------------------------ run
 // f16: in, filt and out hold _Float16 elements (passed through float pointers); the
 // tiles' 4-element loads then need 8-byte instead of 16-byte alignment.
@@ -595,6 +619,23 @@ int conv_fwd(const float* in, const float* filt, const float* bias, float* out, 
   int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 4, &s);
   if (rc != BCONV_OK) return rc;
   return run_conv(in, filt, bias, out, s, relu, nullptr, 0, true, nullptr, -1);
+}
+
+// conv_fwd_ex with the partial sums in the library's static device array; see include/bconv.h.
+int conv_fwd_noalloc(const float* in, const float* filt, const float* bias, float* out, int N, int C,
+                     int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                     void* hip_stream) {
+  Shape s;
+  int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 4, &s);
+  if (rc != BCONV_OK) return rc;
+  // the need is known before anything is looked up on the device: beyond the array -> refused
+  if (conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, -1) > kStaticScratchBytes)
+    return BCONV_EWORKSPACE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != BCONV_OK) return rc;
+  return run_conv(in, filt, bias, out, s, relu, ws, kStaticScratchBytes, false,
+                  static_cast<hipStream_t>(hip_stream), -1);
 }
 
 // Half-precision storage: the same layer with in, filt and out as IEEE binary16.
