@@ -12,8 +12,10 @@ PEAK_HBM_GBPS = 8000.0
 
 
 def conv_out_dims(H, W, R, S, stride, pad):
-    """Output extent, floor reading of the Section II size rule."""
-    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    """Output extent: the library's own answer (conv_out_dims of the C ABI, host only), so
+    that the accounting can never disagree with what the kernels compute."""
+    from . import binding
+    return binding.conv_out_dims(H, W, R, S, stride, pad)
 
 
 def conv_flops(N, C, H, W, K, R, S, stride, pad, flops_per_mac=2):

@@ -31,7 +31,7 @@ def sweep_layer(layer, N, check=True, max_split=32):
     x, f, b = workloads.make_layer_inputs(layer, N)
     xd, fd, bd = (None if a is None else torch.from_numpy(a).to(dev) for a in (x, f, b))
     dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
-    P, Q = workloads.out_hw(layer)
+    P, Q = binding.conv_out_dims(layer.H, layer.W, layer.R, layer.S, layer.stride, layer.pad)
     out = torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)
     ref = torch.empty_like(out)
     binding.conv_fwd_ex(xd, fd, bd, ref, layer.stride, layer.pad, True, variant=0)
@@ -68,10 +68,10 @@ def sweep_layer_pooled(layer, N, max_split=32, ksz=3, pstride=2):
     x, f, b = workloads.make_layer_inputs(layer, N)
     xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
     dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
-    P, Q = workloads.out_hw(layer)
+    P, Q = binding.conv_out_dims(layer.H, layer.W, layer.R, layer.S, layer.stride, layer.pad)
     conv = torch.empty((N, layer.K, P, Q), dtype=torch.float32, device=dev)
     binding.conv_fwd_ex(xd, fd, bd, conv, layer.stride, layer.pad, True, variant=0)
-    ref = torch.empty((N, layer.K, (P - ksz) // pstride + 1, (Q - ksz) // pstride + 1),
+    ref = torch.empty((N, layer.K) + binding.conv_out_dims(P, Q, ksz, ksz, pstride, 0),
                       dtype=torch.float32, device=dev)
     binding.maxpool_fwd(conv, ref, ksz, pstride)
     out = torch.empty_like(ref)

@@ -400,7 +400,7 @@ def gpu_stack(img, params):
         acts.append((cur, out))
         cur = out
         if li in workloads.STACK_POOL_AFTER:
-            pooled = torch.empty((N, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1),
+            pooled = torch.empty((N, layer.K) + binding.conv_out_dims(P, Q, 3, 3, 2, 0),
                                  dtype=torch.float32, device=dev)
             binding.maxpool_fwd(cur, pooled, 3, 2)
             cur = pooled
@@ -490,7 +490,7 @@ def test_stack_captured_in_a_graph_replays_like_eager_launches():
         pooled = li in workloads.STACK_POOL_AFTER
         need = (binding.conv_pool_fwd_workspace_bytes if pooled else binding.conv_fwd_workspace_bytes)(*dims, -1)
         ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
-        shape = (n, layer.K, (P - 3) // 2 + 1, (Q - 3) // 2 + 1) if pooled else (n, layer.K, P, Q)
+        shape = (n, layer.K) + (binding.conv_out_dims(P, Q, 3, 3, 2, 0) if pooled else (P, Q))
         out = torch.empty(shape, dtype=torch.float32, device=dev)
         plan.append((cur, torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev), out, layer, ws, pooled))
         cur = out

@@ -75,13 +75,6 @@ EXTRA_LAYERS = [
 BY_NAME = {l.name: l for l in ALL_LAYERS + SGEMM_LAYERS + EXTRA_LAYERS}
 
 
-def out_hw(layer):
-    """Output height/width of a layer (floor form of the Section II size rule)."""
-    P = (layer.H + 2 * layer.pad - layer.R) // layer.stride + 1
-    Q = (layer.W + 2 * layer.pad - layer.S) // layer.stride + 1
-    return P, Q
-
-
 def _draw(rng, dist, shape):
     if dist == "u01":
         return rng.random(shape, dtype=np.float32)
