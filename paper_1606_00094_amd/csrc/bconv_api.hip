@@ -17,13 +17,13 @@ namespace bconv {
 
 // ------------------------------------------------------------------ catalogue
 static const TileLaunchFn kLaunch[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) launch_##name,
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS) launch_##name,
 #include "variants.def"
 #undef X
 };
 // the same tiles for tensors stored in half precision
 static const TileLaunchFn kLaunchF16[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) launch_f16_##name,
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS) launch_f16_##name,
 #include "variants.def"
 #undef X
 };
@@ -136,14 +136,16 @@ static double model_cost(const TileDesc& v, const Plan& pl) {
   const TconvParams& p = pl.p;
   const int nw = v.WM * v.WN * v.KS;
   const int S = p.S;
-  const double steps = (double)(v.KR / 2 / v.KS) * S;                 // MFMA steps per chunk and wave
-  const double chunk_mfma = steps * v.MT * v.NT * 64.0;
+  const double steps = (double)(v.KR / v.KSL() / v.KS) * S;           // MFMA steps per chunk and wave
+  const double tile_frac = v.MS * v.MS / 1024.0;                      // a 16x16 tile is a quarter of a 32x32 one
+  const double chunk_mfma = steps * v.MT * v.NT * (v.MS == 32 ? 64.0 : 32.0);
   const double tiles = (double)pl.gx * pl.gy * pl.gz;
   // residency: LDS, wave slots, registers (accumulators + PD staging sets + addressing)
   const int agrp = v.KR * (v.S ? v.S : kSmaxGeneric) / v.AV;
   const int na = (v.BM() * agrp + v.NTHR() - 1) / v.NTHR();
   const int npl = p.halo ? v.KR / p.R : v.KR;
-  const int regs = v.MT * v.NT * 16 + v.PD * (na * v.AV + npl * v.EPT) + 72;
+  const int nb = v.BV == kModeHaloFlat ? npl / v.EPT : npl * v.EPT;   // input load items per thread
+  const int regs = v.MT * v.NT * (v.MS * v.MS / 64) + v.PD * (na * v.AV + nb) + 72;
   int resident = (int)(kLdsLimitBytes / pl.lds_bytes);
   const int by_regs = (512 / regs) * 4 / nw, by_waves = 32 / nw;
   if (by_regs < resident) resident = by_regs;
@@ -159,12 +161,13 @@ static double model_cost(const TileDesc& v, const Plan& pl) {
   // (input loads that keep per-load address selects -- slot staging of a padded layer --
   // count one and a half times)
   const bool scalar_in = p.halo || v.BV == kModeSlotsNoPad || (v.R == 1 && v.S == 1 && v.STR == 1);
-  const double stage_instr = (double)v.BM() * v.KR * S / v.NTHR() / v.AV +
-                             in_words / v.NTHR() / (v.BV == kModeCompact4 ? 4.0 : 1.0) *
-                                 (scalar_in ? 1.0 : 1.5);
+  // (flat halo staging: a thread's load count does not depend on how full the planes are)
+  const double in_instr = v.BV == kModeHaloFlat ? (double)nb
+                                                : in_words / v.NTHR() / (v.BV == kModeCompact4 ? 4.0 : 1.0);
+  const double stage_instr = (double)v.BM() * v.KR * S / v.NTHR() / v.AV + in_instr * (scalar_in ? 1.0 : 1.5);
   const double chunk_time = std::max(300.0, pipe_waves * chunk_mfma / eff) + 80.0 * stage_instr * pipe_waves;
-  const double wg_time = p.chunks_per_split * chunk_time + 1200.0 * v.MT * v.NT +
-                         1170.0 * (v.KS - 1) * v.MT * v.NT;
+  const double wg_time = p.chunks_per_split * chunk_time + 1200.0 * v.MT * v.NT * tile_frac +
+                         1170.0 * (v.KS - 1) * v.MT * v.NT * tile_frac;
   double t = 6000.0 + rounds * wg_time;
   if (p.nsplit > 1) t += 3900.0 + 730.0 * p.nsplit + (double)(2 * p.nsplit + 2) * p.out_elems * 4.0 / 2000.0;
   return t;
@@ -490,7 +493,7 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
       pl.lds_bytes)
     ++bad;
   if (v.KS > 1 && (size_t)BM * BN * 4 > pl.lds_bytes) ++bad;
-  if ((long long)ncell > (long long)v.EPT * NTHR * p.bv) ++bad;
+  if ((long long)ncell > v.cell_capacity(p.bv)) ++bad;
   for (unsigned bx = 0; bx < pl.gx; ++bx) {
     PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q, p.fdQ);
     if (t.cnt < 1 || t.cnt > BN) ++bad;

@@ -265,13 +265,15 @@ BCONV_HD int tap_off(int s, int STR, int phst) {
   return (s % STR) * phst + s / STR;
 }
 
-// Words per LDS read of a lane's filter run: the run of reduction group g inside
-// half-chunk h starts at word h*(KR/2)*S + g*(KR/2/KS)*S of a filter row, so the
-// read width is limited by the alignment of both terms.  Run-time S (S = 0): 1.
-BCONV_HD constexpr int a_read_width(int KR, int S, int KS) {
+// Words per LDS read of a lane's filter run.  One MFMA consumes KSL reduction rows (2 for
+// 32x32x2, 4 for 16x16x4), lane slice h taking its row from the h-th of KSL equal parts of
+// the chunk; the run of reduction group g inside part h starts at word
+// h*(KR/KSL)*S + g*(KR/KSL/KS)*S of a filter row, so the read width is limited by the
+// alignment of both terms.  Run-time S (S = 0): 1.
+BCONV_HD constexpr int a_read_width(int KR, int S, int KS, int KSL) {
   return S <= 0 ? 1
-         : ((((KR / 2) * S) % 4 == 0 && ((KR / 2 / KS) * S) % 4 == 0) ? 4
-            : ((((KR / 2) * S) % 2 == 0 && ((KR / 2 / KS) * S) % 2 == 0) ? 2 : 1));
+         : ((((KR / KSL) * S) % 4 == 0 && ((KR / KSL / KS) * S) % 4 == 0) ? 4
+            : ((((KR / KSL) * S) % 2 == 0 && ((KR / KSL / KS) * S) % 2 == 0) ? 2 : 1));
 }
 
 // LDS stride (words) between filter rows holding KRS words each: a multiple of
@@ -284,6 +286,12 @@ BCONV_HD constexpr int a_row_stride(int KRS, int vw) {
 // Row of a 32x32 MFMA accumulator tile held by (lane, register i), i in [0,16).
 BCONV_HD int acc_row_32(int lane, int i) {
   return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+}
+
+// Row of an MS x MS accumulator tile held by (lane, register i): the 32x32x2 map above, or
+// for 16x16x4 (four registers per lane) row 4*(lane/16) + i; the column is lane % MS in both.
+BCONV_HD int acc_row(int lane, int i, int MS) {
+  return MS == 32 ? acc_row_32(lane, i) : 4 * (lane >> 4) + i;
 }
 
 }  // namespace bconv

@@ -26,7 +26,7 @@ typedef hipError_t (*TileLaunchFn)(const TconvParams& p, dim3 grid, size_t lds_b
 // launch_<tile>: fp32 tensors; launch_f16_<tile>: half-precision tensors behind the same
 // argument block (its float pointers then address _Float16 elements; bias and partial
 // sums stay fp32).
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) \
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS) \
   hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st); \
   hipError_t launch_f16_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st);
 #include "variants.def"

@@ -13,26 +13,6 @@ struct Shape {
   int N, C, H, W, K, R, S, stride, pad, P, Q;
 };
 
-// One row of variants.def.
-struct TileDesc {
-  const char* name;
-  int R, S, STR;            // 0 = run-time value
-  int WM, WN, MT, NT, KR, EPT, AV, KS, BV;
-  int PD;                   // register sets of the software pipeline (chunks in flight + 1)
-  int WPE;                  // waves per SIMD the compiler is asked to make room for (1: no demand)
-  int BM() const { return WM * MT * 32; }
-  int BN() const { return WN * NT * 32; }
-  int NTHR() const { return WM * WN * KS * 64; }
-};
-
-static const TileDesc kTileDescs[] = {
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE) \
-  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE},
-#include "variants.def"
-#undef X
-};
-constexpr int kNumTiles = (int)(sizeof(kTileDescs) / sizeof(kTileDescs[0]));
-
 constexpr size_t kLdsLimitBytes = 160 * 1024;
 constexpr int kSmaxGeneric = 16;   // widest kernel the run-time generic tiles take
 // input staging mode of a tile (last column of variants.def)
@@ -40,7 +20,39 @@ constexpr int kModeSlots = 1;      // one copy of an input row per kernel row an
 constexpr int kModeCompact4 = 4;   // compact cells of four pixels, 16-byte loads (flattened pointwise)
 constexpr int kModeHalo = 2;       // whole padded rows per channel, staged once
 constexpr int kModeSlotsNoPad = 3; // kModeSlots for layers without padding (every staged row is inside the image)
+// kModeHalo for tiles whose halo has far fewer cells than the workgroup has threads: the
+// threads form EPT groups, group g staging planes g, g + EPT, ... of a chunk, one cell per
+// thread (the EPT column of variants.def is the number of groups here), so that few lanes
+// issue masked loads
+constexpr int kModeHaloFlat = 5;
 constexpr int kLdsTrashWords = 16; // LDS words (in front of the filter buffers, behind each input buffer) that absorb masked stores
+
+// One row of variants.def.
+struct TileDesc {
+  const char* name;
+  int R, S, STR;            // 0 = run-time value
+  int WM, WN, MT, NT, KR, EPT, AV, KS, BV;
+  int PD;                   // register sets of the software pipeline (chunks in flight + 1)
+  int WPE;                  // waves per SIMD the compiler is asked to make room for (1: no demand)
+  int MS;                   // edge of one MFMA accumulator tile: 32 (32x32x2) or 16 (16x16x4)
+  int BM() const { return WM * MT * MS; }
+  int BN() const { return WN * NT * MS; }
+  int NTHR() const { return WM * WN * KS * 64; }
+  int KSL() const { return 64 / MS; }                 // reduction rows one MFMA consumes
+  bool halo() const { return BV == kModeHalo || BV == kModeHaloFlat; }
+  // input cells of one LDS plane that the workgroup's threads can stage
+  long long cell_capacity(int bv) const {
+    return BV == kModeHaloFlat ? NTHR() / EPT : (long long)EPT * NTHR() * bv;
+  }
+};
+
+static const TileDesc kTileDescs[] = {
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS) \
+  {#name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS},
+#include "variants.def"
+#undef X
+};
+constexpr int kNumTiles = (int)(sizeof(kTileDescs) / sizeof(kTileDescs[0]));
 
 struct Plan {
   TconvParams p;
@@ -80,10 +92,11 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   if (v.BV == kModeSlotsNoPad && (s.pad != 0 || (s.S == 1 && s.stride == 1))) return false;
   // halo staging needs kernel sizes fixed at compile time, a kernel wider than one
   // column or a stride, and half-chunks / reduction groups made of whole channels
-  if (v.BV == kModeHalo &&
-      !(v.R > 0 && v.S > 0 && v.STR > 0 && !(s.S == 1 && s.stride == 1) && (v.KR / 2) % v.R == 0 &&
-        (v.KR / 2 / v.KS) % v.R == 0))
+  if (v.halo() &&
+      !(v.R > 0 && v.S > 0 && v.STR > 0 && !(s.S == 1 && s.stride == 1) && (v.KR / v.KSL()) % v.R == 0 &&
+        (v.KR / v.KSL() / v.KS) % v.R == 0))
     return false;
+  if (v.BV == kModeHaloFlat && !(v.NTHR() % v.EPT == 0 && (v.KR / v.R) % v.EPT == 0)) return false;
   TconvParams& p = pl->p;
   std::memset(&p, 0, sizeof(p));
   p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.R = s.R; p.S = s.S;
@@ -102,7 +115,7 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   p.gbias = s.pad * s.W + s.pad;
   p.compact = (s.S == 1 && s.stride == 1) ? 1 : 0;
   p.bv = (p.compact && v.BV == kModeCompact4) ? 4 : 1;
-  p.halo = (v.BV == kModeHalo) ? 1 : 0;
+  p.halo = v.halo() ? 1 : 0;
   int planes = v.KR;                 // LDS planes per input buffer
   if (p.halo) {
     p.hp = s.H + 2 * s.pad;
@@ -131,8 +144,8 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   p.plane = p.nrows * p.rowst;
   p.fdRowst = make_fastdiv((unsigned)p.rowst);
   if (!p.halo) p.fdHp = make_fastdiv(1);
-  if ((long long)p.nrows * p.rowst > (long long)v.EPT * v.NTHR() * p.bv) return false;
-  p.ast = a_row_stride(v.KR * s.S, a_read_width(v.KR, v.S, v.KS));
+  if ((long long)p.nrows * p.rowst > v.cell_capacity(p.bv)) return false;
+  p.ast = a_row_stride(v.KR * s.S, a_read_width(v.KR, v.S, v.KS, v.KSL()));
   size_t lds = (size_t)(2 * BM * p.ast + 2 * (planes * p.plane + kLdsTrashWords) + kLdsTrashWords) * sizeof(float);
   if (v.KS > 1 && lds < (size_t)BM * BN * sizeof(float)) lds = (size_t)BM * BN * sizeof(float);
   if (lds > kLdsLimitBytes) return false;

@@ -35,15 +35,15 @@ static hipError_t launch_tile_kernel(KernelT kernel, int nthr, const TconvParams
   return e;
 }
 
-#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE)                                          \
+#define X(name, R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS)                                          \
   hipError_t launch_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st) { \
     static std::atomic<size_t> lds_allowed[64];                                                        \
-    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE>,  \
+    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS>,  \
                               WM * WN * KS * 64, p, grid, lds_bytes, st, lds_allowed);                \
   }                                                                                             \
   hipError_t launch_f16_##name(const TconvParams& p, dim3 grid, size_t lds_bytes, hipStream_t st) { \
     static std::atomic<size_t> lds_allowed[64];                                                        \
-    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, _Float16>,  \
+    return launch_tile_kernel(tconv_mfma_kernel<R, S, STR, WM, WN, MT, NT, KR, EPT, AV, KS, BV, PD, WPE, MS, _Float16>,  \
                               WM * WN * KS * 64, p, grid, lds_bytes, st, lds_allowed);                \
   }
 #include "variants.def"

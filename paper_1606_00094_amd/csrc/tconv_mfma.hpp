@@ -81,42 +81,61 @@ constexpr int cdiv_c(int a, int b) { return (a + b - 1) / b; }
 // in the staging registers and widened when they are stored to LDS; LDS, the MFMAs and
 // the partial sums of a split reduction are fp32 either way; the result is rounded to
 // T (to nearest even) once, after bias and ReLU.
+//
+// MS is the edge of one accumulator tile: 32 (v_mfma_f32_32x32x2_f32, two reduction rows per
+// instruction) or 16 (v_mfma_f32_16x16x4_f32, four).  Both run at the same rate; the small
+// tile quarters the work of one wave-tile, so that a layer with few output points (batch 1)
+// still cuts into enough workgroups to fill the chip in ONE kernel, the reduction split over
+// the KS wave groups of a workgroup instead of over the grid with partial sums in HBM.
+// Everywhere below "pair" means the KSL = 64 / MS reduction rows one MFMA consumes: lane slice
+// h = lane / MS takes row h * (KR / KSL) + i of the chunk.
 template <int R_, int S_, int STR_, int WM, int WN, int MT, int NT, int KR, int EPT, int AV, int KS, int BV, int PD, int WPE,
-          typename T = float>
+          int MS = 32, typename T = float>
 __global__ __launch_bounds__(WM * WN * KS * 64, WPE)
 void tconv_mfma_kernel(const TconvParams p) {
   constexpr int NW = WM * WN;              // waves per reduction group
   constexpr int NTHR = NW * KS * 64;
-  static_assert(KR % 2 == 0, "reduction rows are consumed in pairs");
-  static_assert((KR / 2) % KS == 0, "row pairs of a chunk must divide among the reduction groups");
-  constexpr int NPAIR = KR / 2 / KS;       // row pairs per chunk and group
-  constexpr int BM = WM * MT * 32, BN = WN * NT * 32;
+  static_assert(MS == 32 || MS == 16, "accumulator tiles are 32x32 or 16x16");
+  constexpr int KSL = 64 / MS;             // reduction rows per MFMA
+  constexpr int ACCN = MS * MS / 64;       // accumulator registers per tile and lane
+  static_assert(KR % KSL == 0, "reduction rows are consumed KSL at a time");
+  static_assert((KR / KSL) % KS == 0, "row groups of a chunk must divide among the reduction groups");
+  constexpr int NPAIR = KR / KSL / KS;     // row groups per chunk and reduction group
+  constexpr int BM = WM * MT * MS, BN = WN * NT * MS;
   constexpr int SP = S_ > 0 ? S_ : kSmaxGeneric;   // filter columns per reduction row (bound)
   constexpr int KRSP = KR * SP;
   static_assert(AV == 1 || (AV == 4 && S_ > 0 && KRSP % 4 == 0), "vector filter loads need KR*S % 4 == 0");
   constexpr int AGRP = KRSP / AV;                      // load groups per filter row
   constexpr int NA = (BM * AGRP + NTHR - 1) / NTHR;    // filter load items per thread
-  // BV is the input staging mode: kModeSlots, kModeSlotsNoPad, kModeCompact4 or kModeHalo
-  constexpr bool HALO = (BV == kModeHalo);
+  // BV is the input staging mode: kModeSlots, kModeSlotsNoPad, kModeCompact4, kModeHalo or
+  // kModeHaloFlat
+  constexpr bool HFLAT = (BV == kModeHaloFlat);
+  constexpr bool HALO = (BV == kModeHalo) || HFLAT;
   constexpr int BVW = (BV == kModeCompact4) ? 4 : 1;   // words per input load
-  static_assert(BV == kModeSlots || BV == kModeSlotsNoPad || BV == kModeCompact4 || BV == kModeHalo,
+  static_assert(BV == kModeSlots || BV == kModeSlotsNoPad || BV == kModeCompact4 || HALO,
                 "unknown staging mode");
   static_assert(BV != kModeCompact4 || (S_ == 1 && STR_ == 1), "16-byte input loads are for pointwise tiles");
-  static_assert(!HALO || (R_ > 0 && S_ > 0 && STR_ > 0 && (KR / 2) % (R_ > 0 ? R_ : 1) == 0 &&
-                          (KR / 2 / KS) % (R_ > 0 ? R_ : 1) == 0),
-                "halo staging needs whole channels per half-chunk and reduction group");
+  static_assert(!HALO || (R_ > 0 && S_ > 0 && STR_ > 0 && (KR / KSL) % (R_ > 0 ? R_ : 1) == 0 &&
+                          (KR / KSL / KS) % (R_ > 0 ? R_ : 1) == 0),
+                "halo staging needs whole channels per chunk part and reduction group");
   constexpr int RDIV = R_ > 0 ? R_ : 1;
   constexpr int NPL = HALO ? KR / RDIV : KR;           // LDS planes per input buffer
   // Flat staging (pointwise tiles whose pixel tile has fewer cells than the workgroup
   // has threads): every thread owns one cell and stages it for the planes
   // kl0, kl0 + PSTEP, ... with kl0 = tid / CPP, so that no thread issues masked loads.
   constexpr int CPP = BN / BVW;                        // cells per plane of a pointwise tile
-  constexpr bool FLAT = !HALO && R_ == 1 && S_ == 1 && STR_ == 1 && CPP < NTHR && NTHR % CPP == 0 &&
-                        KR % (NTHR / CPP) == 0;
-  constexpr int PSTEP = FLAT ? NTHR / CPP : 1;
-  constexpr int NB = FLAT ? KR / PSTEP : NPL * EPT;    // input load items per thread (BVW words each)
+  constexpr bool PFLAT = !HALO && R_ == 1 && S_ == 1 && STR_ == 1 && CPP < NTHR && NTHR % CPP == 0 &&
+                         KR % (NTHR / CPP) == 0;
+  // The same for a halo tile with few cells per channel plane (kModeHaloFlat): EPT thread
+  // groups of NTHR / EPT threads, group g staging planes g, g + EPT, ... of the chunk.
+  static_assert(!HFLAT || (NTHR % EPT == 0 && NPL % EPT == 0), "plane groups must divide threads and planes");
+  constexpr bool FLAT = PFLAT || HFLAT;
+  constexpr int PSTEP = PFLAT ? NTHR / CPP : (HFLAT ? EPT : 1);
+  constexpr int FCELLS = PFLAT ? CPP : (HFLAT ? NTHR / EPT : 1);   // cells per plane under flat staging
+  constexpr int NCELL = FLAT ? 1 : EPT;                // staged cells per thread and plane
+  constexpr int NB = FLAT ? NPL / PSTEP : NPL * EPT;   // input load items per thread (BVW words each)
   constexpr int NL = NA + NB;
-  constexpr int VW = a_read_width(KR, S_, KS);         // words per LDS read of the filter operand
+  constexpr int VW = a_read_width(KR, S_, KS, KSL);    // words per LDS read of the filter operand
   constexpr int SW = (AV == 4) ? VW : 1;               // words per LDS store of the filter operand
   constexpr bool WHOLE_CH = R_ > 0 && (KR % (R_ > 0 ? R_ : 1)) == 0;   // chunks hold whole channels
   // Scalar addressing: a load's per-lane offset is a register computed once before the
@@ -140,7 +159,7 @@ void tconv_mfma_kernel(const TconvParams p) {
   const int S = S_ > 0 ? S_ : p.S;
   const int STR = STR_ > 0 ? STR_ : p.stride;
   const int KRS = KR * S;            // valid filter words per row per chunk
-  const int HALF = (KR / 2) * S;     // words of one half-chunk of a filter row
+  const int HALF = (KR / KSL) * S;   // words of one lane slice's part of a filter row
   const int RUN = NPAIR * S;         // words of this group's run inside a half-chunk
   const int ast = S_ > 0 ? a_row_stride(KR * (S_ > 0 ? S_ : 1), VW) : p.ast;
   const int plane = p.plane;
@@ -159,7 +178,7 @@ void tconv_mfma_kernel(const TconvParams p) {
   const int kgrp = wave / NW;
   const int wv = wave - kgrp * NW;
   const int wm = wv / WN, wn = wv % WN;
-  const int l32 = lane & 31, h = lane >> 5;
+  const int l32 = lane & (MS - 1), h = lane / MS;     // row / column inside the tile, lane slice
 
   const BlockTile bt = xcd_tile(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), gridDim.x,
                                 gridDim.y, gridDim.z);
@@ -168,12 +187,12 @@ void tconv_mfma_kernel(const TconvParams p) {
   const int m0 = bt.y * BM;
 
   // ---- per-thread staging cells of the input tile (fixed for the whole loop)
-  int c_lds[EPT], c_pl[EPT], c_goff[EPT], c_ih0[EPT];
+  int c_lds[NCELL], c_pl[NCELL], c_goff[NCELL], c_ih0[NCELL];
   const int ncell = p.nrows * p.rowst;
-  const int kl0 = FLAT ? tid / CPP : 0;
+  const int kl0 = FLAT ? tid / FCELLS : 0;
 #pragma unroll
-  for (int i = 0; i < EPT; ++i) {
-    int e = FLAT ? tid - kl0 * CPP : tid + i * NTHR;
+  for (int i = 0; i < NCELL; ++i) {
+    int e = FLAT ? tid - kl0 * FCELLS : tid + i * NTHR;
     const bool in_tile = e * BVW < ncell;
     BCell c = HALO ? h_cell(p, ht, in_tile ? e : 0, STR) : b_cell(p, t, in_tile ? e : 0, S, STR);
     // LDS word offset from Bs of the cell in plane 0 and the plane stride to add per
@@ -197,20 +216,21 @@ void tconv_mfma_kernel(const TconvParams p) {
   int laneB[NT], outoff[NT], colvalid[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    BLane bl = HALO ? h_lane(p, t, ht, (wn * NT + nt) * 32 + l32) : b_lane(p, t, (wn * NT + nt) * 32 + l32);
-    laneB[nt] = bl.ldsbase + (HALO ? (h * (KR / 2) + kgrp * NPAIR) / RDIV : h * (KR / 2) + kgrp * NPAIR) * plane;
+    BLane bl = HALO ? h_lane(p, t, ht, (wn * NT + nt) * MS + l32) : b_lane(p, t, (wn * NT + nt) * MS + l32);
+    laneB[nt] = bl.ldsbase + (HALO ? (h * (KR / KSL) + kgrp * NPAIR) / RDIV : h * (KR / KSL) + kgrp * NPAIR) * plane;
     outoff[nt] = bl.outoff;
     colvalid[nt] = bl.valid;
   }
-  const int laneA = (wm * MT * 32 + l32) * ast + h * HALF + kgrp * RUN;
+  const int laneA = (wm * MT * MS + l32) * ast + h * HALF + kgrp * RUN;
 
-  floatx16 acc[MT][NT];
+  typedef float acc_t __attribute__((ext_vector_type(ACCN)));
+  acc_t acc[MT][NT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
+      for (int i = 0; i < ACCN; ++i) acc[mt][nt][i] = 0.0f;
 
   const bool split = p.nsplit > 1;
   // bias through a buffer descriptor that is empty when there is none to add (no bias,
@@ -222,13 +242,13 @@ void tconv_mfma_kernel(const TconvParams p) {
   constexpr bool BIAS_EARLY = (MT * NT == 1);
   const __amdgpu_buffer_rsrc_t rsrc_bias = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(p.bias), 0, (!split && p.bias) ? p.K * 4 : 0, 0x00020000);
-  float bvals[MT][16];
+  float bvals[MT][ACCN];
   auto load_bias = [&]() {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
+      for (int i = 0; i < ACCN; ++i) {
+        const int k = m0 + (wm * MT + mt) * MS + acc_row(lane, i, MS);
         bvals[mt][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_bias, k * 4, 0, 0));
       }
   };
@@ -348,7 +368,10 @@ void tconv_mfma_kernel(const TconvParams p) {
       int c, r;
       bool ok;
       if constexpr (HALO) {
-        // plane kl is channel ch*NPL + kl; the cell offset already encodes padding
+        // plane kl is channel ch*NPL + kl; the cell offset already encodes padding.  (Flat
+        // halo staging: the thread's own plane kl0 is folded into its offsets and may carry
+        // it past the last channel in the last chunk; those cells are zeroed in LDS after
+        // the store, as under flat pointwise staging.)
         c = ch * NPL + kl;
         r = 0;
         ok = chok && (c < p.C);
@@ -445,7 +468,7 @@ void tconv_mfma_kernel(const TconvParams p) {
       float* B = Bs + buf * bbuf;
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
-        if (ch * KR + kl0 + j * PSTEP >= p.CRrows) {
+        if (HFLAT ? (ch * NPL + kl0 + j * PSTEP >= p.C) : (ch * KR + kl0 + j * PSTEP >= p.CRrows)) {
 #pragma unroll
           for (int u = 0; u < BVW; ++u) B[j * PSTEP * c_pl[0] + c_lds[0] + u] = 0.0f;
         }
@@ -481,7 +504,10 @@ void tconv_mfma_kernel(const TconvParams p) {
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+        if constexpr (MS == 32)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+        else
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
     if constexpr (MFMA_PRIO) __builtin_amdgcn_s_setprio(0);
   };
 
@@ -513,7 +539,7 @@ void tconv_mfma_kernel(const TconvParams p) {
       auto read_a = [&](int g, float (&dst)[MT][VW]) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          avec_t v = *reinterpret_cast<const avec_t*>(A + laneA + mt * 32 * ast + g * VW);
+          avec_t v = *reinterpret_cast<const avec_t*>(A + laneA + mt * MS * ast + g * VW);
           if constexpr (VW == 1) {
             dst[mt][0] = v;
           } else {
@@ -567,7 +593,7 @@ void tconv_mfma_kernel(const TconvParams p) {
         for (int s = 0; s < S; ++s) {
           float a[MT], b[NT];
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) a[mt] = A[laneA + mt * 32 * ast + i * S + s];
+          for (int mt = 0; mt < MT; ++mt) a[mt] = A[laneA + mt * MS * ast + i * S + s];
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) b[nt] = B[laneB[nt] + i * plane + ph * phst + xq];
           mfma_tile(a, b);
@@ -647,8 +673,8 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-              red[(((wv * MT + mt) * NT + nt) * 16 + i) * 64 + lane] = acc[mt][nt][i];
+            for (int i = 0; i < ACCN; ++i)
+              red[(((wv * MT + mt) * NT + nt) * ACCN + i) * 64 + lane] = acc[mt][nt][i];
       }
       __syncthreads();
       if (kgrp == 0) {
@@ -657,8 +683,8 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-              acc[mt][nt][i] += red[(((wv * MT + mt) * NT + nt) * 16 + i) * 64 + lane];
+            for (int i = 0; i < ACCN; ++i)
+              acc[mt][nt][i] += red[(((wv * MT + mt) * NT + nt) * ACCN + i) * 64 + lane];
       }
     }
   }
@@ -675,8 +701,8 @@ void tconv_mfma_kernel(const TconvParams p) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
+      for (int i = 0; i < ACCN; ++i) {
+        const int k = m0 + (wm * MT + mt) * MS + acc_row(lane, i, MS);
         if (k < p.K) {
           const float bv = bvals[mt][i];
 #pragma unroll

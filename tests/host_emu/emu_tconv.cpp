@@ -3,9 +3,9 @@
 // It walks the same index functions (bconv_geom.h) and the same launch plan
 // (bconv_plan.h) as the device kernel, thread by thread and chunk by chunk, with
 // every LDS and global access bounds-checked and LDS poisoned with NaN before
-// each chunk, and models v_mfma_f32_32x32x2_f32 by its definition
-// (D[i][j] += sum_k A[i][k]*B[k][j], lane l supplying A[l%32][l/32] and
-// B[l/32][l%32]).  It checks the kernel's indexing and staging logic on the CPU;
+// each chunk, and models v_mfma_f32_32x32x2_f32 and v_mfma_f32_16x16x4_f32 by their
+// definition (D[i][j] += sum_k A[i][k]*B[k][j] over an MS x MS tile, lane l supplying
+// A[l%MS][l/MS] and B[l/MS][l%MS]).  It checks the kernel's indexing and staging logic on the CPU;
 // it is not part of the library and the library never calls it.
 #include <cmath>
 #include <cstdio>
@@ -121,7 +121,29 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
               for (int u = 0; u < AV; ++u) As[m * p.ast + j + u] = 0.0f;
           }
         }
-        if (p.halo) {
+        if (v.BV == kModeHaloFlat) {
+          // flat halo staging: EPT thread groups, group kl0 staging planes kl0, kl0 + EPT, ...;
+          // one cell per thread.  What the lanes of a load share (chunk, first plane of the
+          // group's stride) decides whether the load is issued at all; a thread whose own
+          // plane lies past the last channel then reads the next image (or zeros past the end
+          // of the tensor) and the cell is zeroed after the store.
+          const int PST = v.EPT, CAP = NTHR / PST;
+          const int kl0 = tid / CAP, e = tid - kl0 * CAP;
+          if (e < ncell) {
+            BCell cell = h_cell(p, ht, e, STR);
+            for (int j = 0; j < NPL / PST; ++j) {
+              const int kl = kl0 + j * PST;
+              const bool sok = ch * NPL + j * PST < p.C;
+              long long gi = (long long)cell.goff + (long long)(ch * NPL + kl) * p.HW;
+              const bool ok = sok && cell.ih0 != kNeverValid && gi < in_elems;
+              if (ok && gi < 0) { oob.hit("in", gi, in_elems); continue; }
+              float val = ok ? in[gi] : 0.0f;
+              if (ch * NPL + kl >= p.C) val = 0.0f;             // tail cleanup
+              if (cell.lds < 0 || cell.lds >= p.plane || kl >= NPL) oob.hit("B lds", cell.lds, p.plane);
+              else Bs[(long long)kl * p.plane + cell.lds] = val;
+            }
+          }
+        } else if (p.halo) {
           for (int j = 0; j < NPL; ++j) {
             const int c = ch * NPL + j;
             for (int i = 0; i < EPT; ++i) {
@@ -193,7 +215,8 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
         const int kgrp = wave / NW, wv = wave % NW;
         const int wm = wv / v.WN, wn = wv % v.WN;
         float* accg = acc.data() + (size_t)kgrp * BM * BN;
-        const int NPAIR = KR / 2 / KS, HALF = (KR / 2) * Sk, RUN = NPAIR * Sk;
+        const int MS = v.MS, KSL = v.KSL();
+        const int NPAIR = KR / KSL / KS, HALF = (KR / KSL) * Sk, RUN = NPAIR * Sk;
         for (int j = 0; j < NPAIR; ++j)
         for (int s = 0; s < Sk; ++s) {
           const int aoff = j * Sk + s;
@@ -203,22 +226,22 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
           for (int nt = 0; nt < v.NT; ++nt) {
             float a[64], b[64];
             for (int lane = 0; lane < 64; ++lane) {
-              const int l32 = lane & 31, h = lane >> 5;
-              const int laneA = (wm * v.MT * 32 + l32) * p.ast + h * HALF + kgrp * RUN;
-              BLane bl = p.halo ? h_lane(p, t, ht, (wn * v.NT + nt) * 32 + l32)
-                                : b_lane(p, t, (wn * v.NT + nt) * 32 + l32);
-              const int hk = h * (KR / 2) + kgrp * NPAIR;
+              const int l32 = lane % MS, h = lane / MS;
+              const int laneA = (wm * v.MT * MS + l32) * p.ast + h * HALF + kgrp * RUN;
+              BLane bl = p.halo ? h_lane(p, t, ht, (wn * v.NT + nt) * MS + l32)
+                                : b_lane(p, t, (wn * v.NT + nt) * MS + l32);
+              const int hk = h * (KR / KSL) + kgrp * NPAIR;
               const int laneB = bl.ldsbase + (p.halo ? hk / p.R : hk) * p.plane;
-              long long ai = (long long)laneA + mt * 32 * p.ast + aoff;
+              long long ai = (long long)laneA + mt * MS * p.ast + aoff;
               long long bi = (long long)laneB + boff;
               if (ai < 0 || ai >= abuf) { oob.hit("A read", ai, abuf); a[lane] = 0; } else a[lane] = As[ai];
               if (bi < 0 || bi >= bbuf) { oob.hit("B read", bi, bbuf); b[lane] = 0; } else b[lane] = Bs[bi];
             }
-            for (int i = 0; i < 32; ++i)
-              for (int jn = 0; jn < 32; ++jn) {
-                float d = accg[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn];
-                for (int k = 0; k < 2; ++k) d = std::fmaf(a[k * 32 + i], b[k * 32 + jn], d);
-                accg[(size_t)((wm * v.MT + mt) * 32 + i) * BN + (wn * v.NT + nt) * 32 + jn] = d;
+            for (int i = 0; i < MS; ++i)
+              for (int jn = 0; jn < MS; ++jn) {
+                float d = accg[(size_t)((wm * v.MT + mt) * MS + i) * BN + (wn * v.NT + nt) * MS + jn];
+                for (int k = 0; k < KSL; ++k) d = std::fmaf(a[k * MS + i], b[k * MS + jn], d);
+                accg[(size_t)((wm * v.MT + mt) * MS + i) * BN + (wn * v.NT + nt) * MS + jn] = d;
               }
           }
         }
@@ -233,12 +256,12 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
       const int wm = wave / v.WN, wn = wave % v.WN;
       for (int lane = 0; lane < 64; ++lane)
       for (int mt = 0; mt < v.MT; ++mt)
-      for (int i = 0; i < 16; ++i) {
-        const int row = (wm * v.MT + mt) * 32 + acc_row_32(lane, i);
+      for (int i = 0; i < v.MS * v.MS / 64; ++i) {
+        const int row = (wm * v.MT + mt) * v.MS + acc_row(lane, i, v.MS);
         const int k = m0 + row;
         if (k >= p.K) continue;
         for (int nt = 0; nt < v.NT; ++nt) {
-          const int col = (wn * v.NT + nt) * 32 + (lane & 31);
+          const int col = (wn * v.NT + nt) * v.MS + lane % v.MS;
           BLane bl = p.halo ? h_lane(p, t, ht, col) : b_lane(p, t, col);
           if (!bl.valid) continue;
           long long oi = (long long)bl.outoff + (long long)k * p.PQ;

@@ -114,9 +114,10 @@ def test_direct_variant_on_toy_and_first_layer():
 # ------------------------------------------------------------------ exact-integer, every tile
 FAMILY_SHAPES = {
     # (R, S, stride) of a tile family -> list of (N, C, H, W, K, pad)
-    (3, 3, 1): [(2, 13, 13, 13, 70, 1), (1, 5, 30, 31, 129, 1), (3, 4, 7, 5, 33, 0)],
-    (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2), (1, 8, 27, 27, 70, 2)],
-    (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0), (5, 8, 6, 6, 33, 0)],
+    (3, 3, 1): [(2, 13, 13, 13, 70, 1), (1, 5, 30, 31, 129, 1), (3, 4, 7, 5, 33, 0), (1, 44, 13, 13, 40, 1)],
+    (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2), (1, 8, 27, 27, 70, 2), (1, 20, 14, 14, 20, 2)],
+    (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0), (5, 8, 6, 6, 33, 0),
+                (2, 132, 7, 7, 40, 0)],
     (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
     (7, 7, 2): [(2, 3, 37, 41, 70, 3), (1, 3, 224, 224, 64, 3), (1, 2, 30, 29, 33, 0)],
     (1, 1, 2): [(2, 20, 14, 14, 70, 0), (1, 36, 28, 27, 130, 0), (3, 8, 7, 9, 33, 1)],
