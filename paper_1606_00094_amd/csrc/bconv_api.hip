@@ -33,11 +33,18 @@ static const TileDesc* const kTiles = kTileDescs;
 static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
 constexpr int kNumSplits = (int)(sizeof(kSplits) / sizeof(kSplits[0]));
 
-// variant id 0 = direct kernel; 1 + tile*kNumSplits + split_index otherwise.
-constexpr int kNumVariants = 1 + kNumTiles * kNumSplits;
+// variant id 0 = direct kernel; 1 + tile*kNumSplits + split_index for the MFMA tiles; the
+// vector-FMA first-layer kernels follow them.
+constexpr int kNumTileVariants = 1 + kNumTiles * kNumSplits;
+static int num_variants() { return kNumTileVariants + fma_num_variants(); }
+
+// Index into the FMA catalogue, or -1.
+static int fma_index(int id) {
+  return (id >= kNumTileVariants && id < num_variants()) ? id - kNumTileVariants : -1;
+}
 
 static bool decode_variant(int id, int* tile, int* nsplit) {
-  if (id < 1 || id >= kNumVariants) return false;
+  if (id < 1 || id >= kNumTileVariants) return false;
   *tile = (id - 1) / kNumSplits;
   *nsplit = kSplits[(id - 1) % kNumSplits];
   return true;
@@ -114,6 +121,8 @@ static const TableRow kPoolTable[] = {
     {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
 
 static int find_variant(const char* tile, int nsplit) {
+  for (int f = 0; f < fma_num_variants(); ++f)
+    if (nsplit == 1 && std::strcmp(fma_variant_name(f), tile) == 0) return kNumTileVariants + f;
   for (int t = 0; t < kNumTiles; ++t)
     if (std::strcmp(kTiles[t].name, tile) == 0)
       for (int i = 0; i < kNumSplits; ++i)
@@ -221,6 +230,7 @@ static int table_lookup(const TableRow* table, const Shape& s, bool filt_aligned
       int id = find_variant(r->tile, r->nsplit);
       int t, ns;
       Plan pl;
+      if (fma_index(id) >= 0 && fma_conv_applicable(fma_index(id), s)) return id;
       if (id > 0 && decode_variant(id, &t, &ns) && (filt_aligned16 || kTiles[t].AV == 1) &&
           (in_aligned16 || kTiles[t].BV != kModeCompact4) &&
           plan_tconv(s, kTiles[t], ns, &pl))
@@ -338,6 +348,13 @@ static int run_conv_launch(const float* in, const float* filt, const float* bias
     return launch_direct_conv(in, filt, bias, out, s, relu, f16, st) == hipSuccess ? BCONV_OK
                                                                                    : BCONV_ELAUNCH;
   }
+  if (fma_index(variant_id) >= 0) {
+    if (f16 || !fma_conv_applicable(fma_index(variant_id), s)) return BCONV_EVARIANT;
+    if (dry) return BCONV_OK;
+    return launch_fma_conv(fma_index(variant_id), in, filt, bias, out, s, relu, st) == hipSuccess
+               ? BCONV_OK
+               : BCONV_ELAUNCH;
+  }
   int t, nsplit;
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
   Plan pl;
@@ -417,6 +434,7 @@ static size_t conv_pool_need(const Shape& s, int variant_id) {
   int t, nsplit;
   Plan pl;
   if (variant_id == 0) return conv_bytes;
+  if (fma_index(variant_id) >= 0) return fma_conv_applicable(fma_index(variant_id), s) ? conv_bytes : 0;
   if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return 0;
   return nsplit > 1 ? pl.ws_bytes : conv_bytes;
 }
@@ -431,7 +449,8 @@ static int run_conv_pool_launch(const float* in, const float* filt, const float*
   if (need == 0) return BCONV_EVARIANT;
   if (!ws || ws_bytes < need) return BCONV_EWORKSPACE;
   int t = 0, nsplit = 1;
-  if (variant_id > 0 && !decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
+  if (variant_id > 0 && fma_index(variant_id) < 0 && !decode_variant(variant_id, &t, &nsplit))
+    return BCONV_EVARIANT;
   float* const scratch = static_cast<float*>(ws);
   if (variant_id == 0 || nsplit == 1) {
     // unpooled output into the workspace (a variant without split needs none of its own)
@@ -611,7 +630,7 @@ int conv_fwd_ex(const float* in, const float* filt, const float* bias, float* ou
   Shape s;
   int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 4, &s);
   if (rc != BCONV_OK) return rc;
-  if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
+  if (variant_id < -1 || variant_id >= num_variants()) return BCONV_EVARIANT;
   return run_conv(in, filt, bias, out, s, relu, workspace, workspace_bytes, false,
                   static_cast<hipStream_t>(hip_stream), variant_id);
 }
@@ -648,7 +667,7 @@ int conv_fwd_f16_ex(const void* in, const void* filt, const float* bias, void* o
   Shape s;
   int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 2, &s);
   if (rc != BCONV_OK) return rc;
-  if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
+  if (variant_id < -1 || variant_id >= num_variants()) return BCONV_EVARIANT;
   return run_conv(static_cast<const float*>(in), static_cast<const float*>(filt), bias,
                   static_cast<float*>(out), s, relu, workspace, workspace_bytes, false,
                   static_cast<hipStream_t>(hip_stream), variant_id, true);
@@ -673,14 +692,14 @@ int conv_pool_fwd_ex(const float* in, const float* filt, const float* bias, floa
   if (rc != BCONV_OK) return rc;
   if (pool_ksz <= 0 || pool_stride <= 0) return BCONV_EINVAL;
   if (s.P < pool_ksz || s.Q < pool_ksz) return BCONV_ESHAPE;
-  if (variant_id < -1 || variant_id >= kNumVariants) return BCONV_EVARIANT;
+  if (variant_id < -1 || variant_id >= num_variants()) return BCONV_EVARIANT;
   return run_conv_pool(in, filt, bias, out, s, relu, pool_ksz, pool_stride, workspace,
                        workspace_bytes, static_cast<hipStream_t>(hip_stream), variant_id);
 }
 
 // Workspace of one run shape (see run_shapes); 0 when a forced variant cannot run it.
 static size_t conv_pool_need_any_alignment(const Shape& s, int variant_id) {
-  if (variant_id >= 0) return variant_id < kNumVariants ? conv_pool_need(s, variant_id) : 0;
+  if (variant_id >= 0) return variant_id < num_variants() ? conv_pool_need(s, variant_id) : 0;
   size_t need = 0;
   for (int mask = 0; mask < 4; ++mask) {     // whichever loads the pointers turn out to allow
     // (the pooling window is not known here: enough for the pooled table's choice too)
@@ -732,6 +751,10 @@ static size_t conv_need_any_alignment(const Shape& s, int variant_id, bool* ok) 
     return need;
   }
   if (variant_id == 0) return 0;
+  if (fma_index(variant_id) >= 0) {
+    *ok = fma_conv_applicable(fma_index(variant_id), s);
+    return 0;
+  }
   if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) {
     *ok = false;
     return 0;
@@ -769,12 +792,16 @@ size_t sgemm_workspace_bytes(int M, int N, int K, int variant_id) {
   return conv_fwd_workspace_bytes(1, K, 1, N, M, 1, 1, 1, 0, variant_id);
 }
 
-int conv_num_variants(void) { return kNumVariants; }
+int conv_num_variants(void) { return num_variants(); }
 
 int conv_variant_name(int variant_id, char* buf, size_t buflen) {
   if (!buf || buflen == 0) return BCONV_ENULL;
   if (variant_id == 0) {
     std::snprintf(buf, buflen, "direct");
+    return BCONV_OK;
+  }
+  if (fma_index(variant_id) >= 0) {
+    std::snprintf(buf, buflen, "%s/s1", fma_variant_name(fma_index(variant_id)));
     return BCONV_OK;
   }
   int t, nsplit;
@@ -799,6 +826,11 @@ int conv_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int
   int t, nsplit;
   Plan pl;
   Shape runs[2];
+  if (fma_index(variant_id) >= 0) {
+    for (int i = 0, n = run_shapes(s, runs); i < n; ++i)
+      if (!fma_conv_applicable(fma_index(variant_id), runs[i])) return 0;
+    return 1;
+  }
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
   for (int i = 0, n = run_shapes(s, runs); i < n; ++i)
     if (!plan_tconv(runs[i], kTiles[t], nsplit, &pl)) return 0;
@@ -813,6 +845,8 @@ long long bconv_debug_audit(int N, int C, int H, int W, int K, int R, int S, int
   if (variant_id == 0) return 0;
   int t, nsplit;
   Plan pl;
+  // (the FMA kernels test every global index against the image bounds themselves)
+  if (fma_index(variant_id) >= 0) return fma_conv_applicable(fma_index(variant_id), s) ? 0 : BCONV_EVARIANT;
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
   Shape runs[2];
   long long bad = 0;

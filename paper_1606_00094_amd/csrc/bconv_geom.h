@@ -74,28 +74,39 @@ struct TconvParams {
   int ast;                             // LDS stride between filter rows (odd)
   int nchunks, chunks_per_split, nsplit;
   int out_elems;                       // N*K*P*Q
+  int filter_major;                    // order of the block-to-tile map, see xcd_tile
   FastDiv fdQ, fdP, fdRowst, fdHp;     // divisions by Q, P, rowst and hp (hp: halo mode)
 };
 
 // Which tile a workgroup computes, from its position in dispatch order (x fastest, then
 // y, then z).  Consecutive workgroups go to the eight accelerator dies in turn, and each
-// die has its own L2; this map hands each die one contiguous run of the tile list
-// ordered (reduction split, pixel tile, filter tile), so that the workgroups that
-// share an input tile, and the filter slices of one reduction split, meet in one L2
-// instead of being fetched by all eight.  It is a bijection on the grid.
+// die has its own L2; this map hands each die one contiguous run of the tile list, so that
+// workgroups that share an operand tile meet in one L2 instead of every die fetching it.
+// The list is ordered (reduction split, pixel tile, filter tile) when the input is the
+// larger operand (filter_major = 0: a die's run shares few input tiles and reads all the
+// filters, which are small) and (reduction split, filter tile, pixel tile) when the filters
+// are (filter_major = 1, the small batches: each die then reads an eighth of the filters
+// and the whole, small, input).  With a run at least one row of the list long, the bytes
+// the eight L2s fetch are 8 F + I in the first order and F + 8 I in the second (F, I the
+// filter and input bytes), so the larger operand decides.  It is a bijection on the grid.
 struct BlockTile {
   int x, y, z;        // pixel tile, filter tile, reduction split
 };
 
-BCONV_HD BlockTile xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz) {
+BCONV_HD BlockTile xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz, int filter_major) {
   const unsigned kDies = 8;
   const unsigned total = gx * gy * gz;
   const unsigned die = lin % kDies, slot = lin / kDies;
   const unsigned q = total / kDies, r = total % kDies;
   const unsigned n = die * q + (die < r ? die : r) + slot;   // position in the tile list
   BlockTile b;
-  b.y = (int)(n % gy);
-  b.x = (int)((n / gy) % gx);
+  if (filter_major) {
+    b.x = (int)(n % gx);
+    b.y = (int)((n / gx) % gy);
+  } else {
+    b.y = (int)(n % gy);
+    b.x = (int)((n / gy) % gx);
+  }
   b.z = (int)(n / (gx * gy));
   return b;
 }

@@ -46,4 +46,12 @@ hipError_t launch_maxpool(const float* in, float* out, int N, int C, int H, int 
 
 hipError_t launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st);
 
+// Register-blocked vector-FMA kernels for first-layer shapes (fma_conv.hip); `which` indexes
+// its small catalogue.  fp32 storage only, no reduction split, no workspace.
+int fma_num_variants();
+const char* fma_variant_name(int which);
+bool fma_conv_applicable(int which, const Shape& s);
+hipError_t launch_fma_conv(int which, const float* in, const float* filt, const float* bias, float* out,
+                           const Shape& s, int relu, hipStream_t st);
+
 }  // namespace bconv

@@ -108,6 +108,7 @@ inline bool plan_tconv(const Shape& s0, const TileDesc& v, int nsplit, Plan* pl)
   p.CRS = s.C * s.R * s.S;
   p.CRrows = s.C * s.R;
   p.out_elems = s.N * s.K * p.PQ;
+  p.filter_major = (long long)s.K * s.C * s.R * s.S > (long long)s.N * s.C * s.H * s.W ? 1 : 0;
   p.fdQ = make_fastdiv((unsigned)p.Q);
   p.fdP = make_fastdiv((unsigned)p.P);
   const int BN = v.BN(), BM = v.BM();

@@ -181,7 +181,7 @@ void tconv_mfma_kernel(const TconvParams p) {
   const int l32 = lane & (MS - 1), h = lane / MS;     // row / column inside the tile, lane slice
 
   const BlockTile bt = xcd_tile(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), gridDim.x,
-                                gridDim.y, gridDim.z);
+                                gridDim.y, gridDim.z, p.filter_major);
   const PixTile t = pix_tile(bt.x, BN, p.NPQ, p.Q, p.fdQ);
   const HaloTile ht = HALO ? halo_tile(p, t) : HaloTile{0, 0};
   const int m0 = bt.y * BM;

@@ -12,6 +12,7 @@ Each candidate is timed as a HIP graph of back-to-back launches (no host launch
 overhead in the figure) and its output is compared with the direct kernel's.
 """
 import argparse
+import re
 import json
 import sys
 
@@ -26,7 +27,9 @@ def _split_of(name):
     return int(name.rsplit("/s", 1)[1])
 
 
-def sweep_layer(layer, N, check=True, max_split=32):
+def sweep_layer(layer, N, check=True, max_split=32, only=None):
+    """Times every applicable variant (with `only`, a compiled regular expression: the
+    variants whose name matches it, plus the one the library selects today)."""
     dev = torch.device("cuda:0")
     x, f, b = workloads.make_layer_inputs(layer, N)
     xd, fd, bd = (None if a is None else torch.from_numpy(a).to(dev) for a in (x, f, b))
@@ -37,10 +40,13 @@ def sweep_layer(layer, N, check=True, max_split=32):
     binding.conv_fwd_ex(xd, fd, bd, ref, layer.stride, layer.pad, True, variant=0)
     flops = roofline.conv_flops(*dims)
     rows = []
+    selected = binding.conv_selected_variant(*dims)
     for v in range(1, binding.conv_num_variants()):
         if not binding.conv_variant_applicable(*dims, v):
             continue
-        if _split_of(binding.conv_variant_name(v)) > max_split:
+        if v != selected and _split_of(binding.conv_variant_name(v)) > max_split:
+            continue
+        if only is not None and v != selected and not only.search(binding.conv_variant_name(v)):
             continue
         need = binding.conv_fwd_workspace_bytes(*dims, v)
         ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
@@ -143,6 +149,9 @@ def main():
     ap.add_argument("--pool", action="store_true",
                     help="sweep the convolution + pooling call instead (rows for pool_selection_table.inc)")
     ap.add_argument("--max-split", type=int, default=0, help="largest reduction split to try (0: by batch)")
+    ap.add_argument("--only", default="",
+                    help="regular expression: sweep only the variants whose name matches, against "
+                         "the variant selected today (a partial re-sweep after adding tiles)")
     args = ap.parse_args()
     batches = [int(t) for t in args.batches.split(",")]
     names = [t for t in args.layers.split(",") if t]
@@ -157,7 +166,8 @@ def main():
         for N in (batches if not layer.name.startswith("sgemm_") else [1]):
             # large batches have enough tiles; deep reduction splits only cost traffic there
             big = layer.name.startswith("sgemm_") and layer.C >= 768
-            rows = sweep_layer(layer, N, max_split=args.max_split or (4 if big else 32 if N <= 2 else 12 if N <= 8 else 6))
+            rows = sweep_layer(layer, N, max_split=args.max_split or (4 if big else 32 if N <= 2 else 12 if N <= 8 else 6),
+                               only=re.compile(args.only) if args.only else None)
             good = [r for r in rows if r["ok"]]
             best = good[0] if good else None
             # what the library would run for this shape (table row, else the heuristic)

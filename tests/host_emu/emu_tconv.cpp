@@ -60,7 +60,7 @@ extern "C" long long emu_tconv(const float* in, const float* filt, const float* 
   const int ncell = p.nrows * p.rowst;
 
   for (unsigned lin = 0; lin < pl.gx * pl.gy * pl.gz; ++lin) {
-    const BlockTile bt = xcd_tile(lin, pl.gx, pl.gy, pl.gz);
+    const BlockTile bt = xcd_tile(lin, pl.gx, pl.gy, pl.gz, p.filter_major);
     const unsigned bx = (unsigned)bt.x, by = (unsigned)bt.y, bz = (unsigned)bt.z;
     const PixTile t = pix_tile((int)bx, BN, p.NPQ, p.Q, p.fdQ);
     const HaloTile ht = p.halo ? halo_tile(p, t) : HaloTile{0, 0};
@@ -290,7 +290,8 @@ extern "C" long long emu_fastdiv_check(const int* n, const int* d, long long cou
   return -1;
 }
 
-extern "C" void emu_xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz, int* x, int* y, int* z) {
-  bconv::BlockTile b = bconv::xcd_tile(lin, gx, gy, gz);
+extern "C" void emu_xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz, int filter_major, int* x,
+                             int* y, int* z) {
+  bconv::BlockTile b = bconv::xcd_tile(lin, gx, gy, gz, filter_major);
   *x = b.x; *y = b.y; *z = b.z;
 }

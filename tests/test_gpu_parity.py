@@ -160,6 +160,10 @@ def _family_of(tile):
         return (7, 1, 1)
     if tile.startswith("gen_"):
         return (0, 0, 0)
+    if tile.startswith("fmaq4_"):      # vector-FMA first-layer kernels, lanes split by the stride
+        return (11, 11, 4)
+    if tile.startswith("fmaq2_"):
+        return (7, 7, 2)
     raise KeyError(tile)
 
 
@@ -338,15 +342,22 @@ def test_conv_pool_on_the_stack_layers(layer, N):
 
 def test_conv_pool_rows_of_the_pooled_table():
     """Shapes whose convolution + pooling choice differs from the convolution's own (variant
-    -1 takes the pooled table's row): against the oracle's convolution followed by its pooling."""
-    for layer, N in ((workloads.CONV1, 2), (workloads.CONV2, 4), (workloads.CONV5, 1)):
-        dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
-        assert binding.conv_pool_selected_variant(*dims, 3, 2) != binding.conv_selected_variant(*dims)
-        x, f, b, s, p = _layer_case(layer, N)
-        got = gpu_conv_pool(x, f, b, s, p, True, 3, 2)
-        for n in sorted({0, N - 1}):
-            ref = oracle.maxpool_fwd(oracle.conv_fwd(x[n:n + 1], f, b, stride=s, pad=p, relu=True), 3, 2)
-            assert_close(got[n:n + 1], ref, "%s N=%d image %d" % (layer.name, N, n))
+    -1 takes the pooled table's row; every row is run in test_gpu_table_rows.py): here the
+    first listed batch of each pooled layer, first and last image against the oracle."""
+    seen = 0
+    for layer in workloads.POOLED_LAYERS:
+        for N in (1, 2, 4, 5, 8, 16, 20, 32):
+            dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+            if binding.conv_pool_selected_variant(*dims, 3, 2) == binding.conv_selected_variant(*dims):
+                continue
+            x, f, b, s, p = _layer_case(layer, N)
+            got = gpu_conv_pool(x, f, b, s, p, True, 3, 2)
+            for n in sorted({0, N - 1}):
+                ref = oracle.maxpool_fwd(oracle.conv_fwd(x[n:n + 1], f, b, stride=s, pad=p, relu=True), 3, 2)
+                assert_close(got[n:n + 1], ref, "%s N=%d image %d" % (layer.name, N, n))
+            seen += 1
+            break
+    assert seen >= 2
 
 
 def test_conv_pool_forced_variants_windows_and_no_relu():
@@ -705,7 +716,8 @@ def test_fuzz_random_variants_exact_on_integers():
     rng = np.random.default_rng(9416)
     nv = binding.conv_num_variants()
     fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2),
-           "pws2": (1, 1, 2), "k3s2": (3, 3, 2), "k1x7": (1, 7, 1), "k7x1": (7, 1, 1)}
+           "pws2": (1, 1, 2), "k3s2": (3, 3, 2), "k1x7": (1, 7, 1), "k7x1": (7, 1, 1),
+           "fmaq4": (11, 11, 4), "fmaq2": (7, 7, 2)}
     ran = 0
     for it in range(500):
         v = int(rng.integers(1, nv))

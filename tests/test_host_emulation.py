@@ -229,20 +229,23 @@ def test_fast_division_matches_integer_division(emu):
     assert bad == -1, (int(ns[bad]), int(dd[bad]))
 
 
+@pytest.mark.parametrize("filter_major", [0, 1])
 @pytest.mark.parametrize("grid", [(183, 8, 1), (85, 6, 1), (3, 6, 8), (1, 1, 1), (5, 3, 4), (757, 1, 1), (7, 11, 3)])
-def test_block_to_tile_map_is_a_bijection_that_groups_tiles_by_die(emu, grid):
+def test_block_to_tile_map_is_a_bijection_that_groups_tiles_by_die(emu, grid, filter_major):
     """Every tile of the grid is computed exactly once, and the workgroups of one die
-    (dispatch position mod 8) cover one contiguous run of the (split, pixel, filter) list."""
+    (dispatch position mod 8) cover one contiguous run of the (split, pixel, filter) list, or
+    of the (split, filter, pixel) list in the filter-major order."""
     gx, gy, gz = grid
-    emu.emu_xcd_tile.argtypes = [ctypes.c_uint] * 4 + [ctypes.POINTER(ctypes.c_int)] * 3
+    emu.emu_xcd_tile.argtypes = [ctypes.c_uint] * 4 + [ctypes.c_int] + [ctypes.POINTER(ctypes.c_int)] * 3
     emu.emu_xcd_tile.restype = None
     seen, by_die = set(), {}
     for lin in range(gx * gy * gz):
         x, y, z = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-        emu.emu_xcd_tile(lin, gx, gy, gz, ctypes.byref(x), ctypes.byref(y), ctypes.byref(z))
+        emu.emu_xcd_tile(lin, gx, gy, gz, filter_major, ctypes.byref(x), ctypes.byref(y), ctypes.byref(z))
         assert 0 <= x.value < gx and 0 <= y.value < gy and 0 <= z.value < gz
         seen.add((x.value, y.value, z.value))
-        by_die.setdefault(lin % 8, []).append((z.value * gx + x.value) * gy + y.value)
+        pos = (z.value * gy + y.value) * gx + x.value if filter_major else (z.value * gx + x.value) * gy + y.value
+        by_die.setdefault(lin % 8, []).append(pos)
     assert len(seen) == gx * gy * gz
     for die, idx in by_die.items():
         assert idx == list(range(idx[0], idx[0] + len(idx)))
