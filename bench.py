@@ -44,8 +44,12 @@ class LayerProblem:
         self.bytes = roofline.conv_bytes(*self.dims)
         if half:   # in, filt, out stored as fp16; the bias stays fp32
             self.bytes = (self.bytes - 4 * layer.K) // 2 + 4 * layer.K
-        self.variant = binding.conv_selected_variant(*self.dims)
-        need = binding.conv_fwd_workspace_bytes(*self.dims, self.variant)
+        if half:
+            self.variant = binding.conv_fwd_f16_selected_variant(*self.dims)
+            need = binding.conv_fwd_f16_workspace_bytes(*self.dims, self.variant)
+        else:
+            self.variant = binding.conv_selected_variant(*self.dims)
+            need = binding.conv_fwd_workspace_bytes(*self.dims, self.variant)
         self.ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
         xd, fd, bd = (torch.from_numpy(a).to(dev) for a in (x, f, b))
         store = torch.float16 if half else torch.float32

@@ -107,8 +107,8 @@ int conv_fwd_noalloc(const float* in, const float* filt, const float* bias, floa
  * (same NCHW / KCRS layouts, 2-byte alignment is enough); bias stays fp32 (or NULL).
  * Elements are widened exactly, products and sums are fp32 on the matrix cores, bias
  * and ReLU are applied in fp32 and the result is rounded to binary16 once, to nearest
- * even.  Variant ids, the workspace size (conv_fwd_workspace_bytes: partial sums are
- * fp32) and all error codes are those of conv_fwd / conv_fwd_ex; a pointer that is not
+ * even.  Variant ids and all error codes are those of conv_fwd / conv_fwd_ex; the workspace
+ * size comes from conv_fwd_f16_workspace_bytes (below); a pointer that is not
  * 2-byte aligned gives BCONV_EINVAL.  A variant with 4-element loads needs 8-byte
  * aligned in / filt here; the table's choice degrades silently to its narrow twin,
  * a forced one gives BCONV_EVARIANT. */
@@ -119,6 +119,24 @@ int conv_fwd_f16_ex(const void* in, const void* filt, const float* bias, void* o
                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                     int relu, void* workspace, size_t workspace_bytes, void* hip_stream,
                     int variant_id);
+
+/* Queries for the half-precision entry points.  Their catalogue is that of the fp32 entry
+ * points (the same tiles with fp32 arithmetic, widening the elements on the way into LDS; the
+ * vector-FMA first-layer kernels excepted) plus the tiles that multiply on the fp16 matrix
+ * cores (names h16...: exact fp16 x fp16 products, fp32 sums, so the same numerical contract;
+ * stride 1, kernels 1x1 / 3x3 / 5x5, C a multiple of eight).  Those need device scratch for the
+ * filters re-laid into their reduction order, every call, and are what variant_id = -1 picks
+ * for launches large enough to fill the chip; conv_fwd_ex gives BCONV_EVARIANT for them.
+ *   conv_fwd_f16_selected_variant: the variant conv_fwd_f16 / conv_fwd_f16_ex(-1) would run.
+ *   conv_fwd_f16_variant_applicable: 1 / 0, negative status on bad arguments.
+ *   conv_fwd_f16_workspace_bytes: what conv_fwd_f16_ex needs for (shape, variant_id); for -1
+ *     it covers the choice for any pointer alignment. */
+int conv_fwd_f16_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                  int pad);
+int conv_fwd_f16_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                    int pad, int variant_id);
+size_t conv_fwd_f16_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                    int pad, int variant_id);
 
 /* Bytes of workspace conv_fwd_ex needs for this shape and variant (0 if none;
  * also 0 for arguments conv_fwd_ex would reject).  For variant_id = -1 the figure

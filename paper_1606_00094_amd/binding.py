@@ -23,6 +23,9 @@ EXPORTS = {
     "conv_fwd_f16": ([_vp] * 4 + [_i] * 10, _i),
     "conv_fwd_f16_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
     "conv_fwd_workspace_bytes": ([_i] * 10, _sz),
+    "conv_fwd_f16_selected_variant": ([_i] * 9, _i),
+    "conv_fwd_f16_variant_applicable": ([_i] * 10, _i),
+    "conv_fwd_f16_workspace_bytes": ([_i] * 10, _sz),
     "conv_pool_fwd_ex": ([_vp] * 4 + [_i] * 12 + [_vp, _sz, _vp, _i], _i),
     "conv_pool_fwd_workspace_bytes": ([_i] * 10, _sz),
     "conv_pool_selected_variant": ([_i] * 11, _i),
@@ -270,6 +273,24 @@ def conv_pool_selected_variant(N, C, H, W, K, R, S, stride, pad, pool_ksz, pool_
     if v < 0:
         raise BconvError(v, "conv_pool_selected_variant")
     return v
+
+
+def conv_fwd_f16_selected_variant(N, C, H, W, K, R, S, stride, pad):
+    v = int(lib().conv_fwd_f16_selected_variant(N, C, H, W, K, R, S, stride, pad))
+    if v < 0:
+        raise BconvError(v, "conv_fwd_f16_selected_variant")
+    return v
+
+
+def conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, variant):
+    v = int(lib().conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, int(variant)))
+    if v < 0:
+        raise BconvError(v, "conv_fwd_f16_variant_applicable")
+    return bool(v)
+
+
+def conv_fwd_f16_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant=-1):
+    return int(lib().conv_fwd_f16_workspace_bytes(N, C, H, W, K, R, S, stride, pad, int(variant)))
 
 
 def conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, variant):

@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 def _units():
     units = [("bconv_api.hip", "bconv_api.o", []), ("aux_kernels.hip", "aux_kernels.o", []),
-             ("fma_conv.hip", "fma_conv.o", [])]
+             ("fma_conv.hip", "fma_conv.o", []), ("hconv_mfma.hip", "hconv_mfma.o", [])]
     for g in range(NUM_GROUPS):
         units.append(("tconv_instances.hip", "tconv_instances_g%d.o" % g, ["-DBCONV_GROUP=%d" % g]))
     return units

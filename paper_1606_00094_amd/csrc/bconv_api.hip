@@ -36,11 +36,30 @@ constexpr int kNumSplits = (int)(sizeof(kSplits) / sizeof(kSplits[0]));
 // variant id 0 = direct kernel; 1 + tile*kNumSplits + split_index for the MFMA tiles; the
 // vector-FMA first-layer kernels follow them.
 constexpr int kNumTileVariants = 1 + kNumTiles * kNumSplits;
-static int num_variants() { return kNumTileVariants + fma_num_variants(); }
+static int num_variants() { return kNumTileVariants + fma_num_variants() + hconv_num_variants(); }
 
 // Index into the FMA catalogue, or -1.
 static int fma_index(int id) {
-  return (id >= kNumTileVariants && id < num_variants()) ? id - kNumTileVariants : -1;
+  return (id >= kNumTileVariants && id < kNumTileVariants + fma_num_variants()) ? id - kNumTileVariants : -1;
+}
+
+// Index into the catalogue of the fp16-matrix-core kernels (half-precision storage only), or -1.
+static int hconv_index(int id) {
+  const int first = kNumTileVariants + fma_num_variants();
+  return (id >= first && id < num_variants()) ? id - first : -1;
+}
+
+// What the half-precision entry points run when asked to choose: an fp16-matrix-core tile
+// where one applies and the launch is large enough to fill the chip with it, else the
+// choice of the fp32 entry points (the same tiles, widening on the way into LDS).
+static int select_variant(const Shape& s, bool filt_aligned16, bool in_aligned16);
+static int f16_table_lookup(const Shape& s);
+static int select_variant_f16(const Shape& s, bool filt_aligned, bool in_aligned) {
+  const int listed = f16_table_lookup(s);
+  if (listed > 0) return listed;
+  const int h = hconv_select(s);
+  if (h >= 0) return kNumTileVariants + fma_num_variants() + h;
+  return select_variant(s, filt_aligned, in_aligned);
 }
 
 static bool decode_variant(int id, int* tile, int* nsplit) {
@@ -120,9 +139,18 @@ static const TableRow kPoolTable[] = {
 #include "pool_selection_table.inc"
     {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
 
+// Measured choices of the half-precision entry points (fp16-matrix-core tiles), where they beat
+// what those entry points would otherwise run.
+static const TableRow kF16Table[] = {
+#include "f16_selection_table.inc"
+    {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
+
 static int find_variant(const char* tile, int nsplit) {
   for (int f = 0; f < fma_num_variants(); ++f)
     if (nsplit == 1 && std::strcmp(fma_variant_name(f), tile) == 0) return kNumTileVariants + f;
+  for (int h = 0; h < hconv_num_variants(); ++h)
+    if (nsplit == 1 && std::strcmp(hconv_variant_name(h), tile) == 0)
+      return kNumTileVariants + fma_num_variants() + h;
   for (int t = 0; t < kNumTiles; ++t)
     if (std::strcmp(kTiles[t].name, tile) == 0)
       for (int i = 0; i < kNumSplits; ++i)
@@ -240,6 +268,18 @@ static int table_lookup(const TableRow* table, const Shape& s, bool filt_aligned
   return -1;
 }
 
+// The half-precision table's fp16-matrix-core tile for this exact shape, or -1.
+static int f16_table_lookup(const Shape& s) {
+  for (const TableRow* r = kF16Table; r->tile; ++r) {
+    if (r->N == s.N && r->C == s.C && r->H == s.H && r->W == s.W && r->K == s.K && r->R == s.R &&
+        r->S == s.S && r->stride == s.stride && r->pad == s.pad) {
+      const int id = find_variant(r->tile, r->nsplit);
+      if (hconv_index(id) >= 0 && hconv_applicable(hconv_index(id), s)) return id;
+    }
+  }
+  return -1;
+}
+
 // Convolution + pooling in one call: the pooled table covers windows of 3 with step 2
 // (the pooling of the benchmark stack); everything else takes the convolution's choice.
 static int select_pool_variant(const Shape& s, int ksz, int pstride, bool filt_aligned16,
@@ -341,8 +381,25 @@ static int run_conv_launch(const float* in, const float* filt, const float* bias
   const uintptr_t vec_mask = f16 ? 7u : 15u;
   const bool aligned16 = (reinterpret_cast<uintptr_t>(filt) & vec_mask) == 0;
   const bool in_aligned16 = (reinterpret_cast<uintptr_t>(in) & vec_mask) == 0;
-  if (variant_id < 0) variant_id = select_variant(s, aligned16, in_aligned16);
+  if (variant_id < 0)
+    variant_id = f16 ? select_variant_f16(s, aligned16, in_aligned16) : select_variant(s, aligned16, in_aligned16);
   if (need_out) *need_out = 0;
+  if (hconv_index(variant_id) >= 0) {
+    const int h = hconv_index(variant_id);
+    if (!f16 || !hconv_applicable(h, s)) return BCONV_EVARIANT;
+    const size_t need = hconv_workspace_bytes(h, s);
+    if (need_out) *need_out = need;
+    if (own_ws) {
+      if (!dry) {
+        int rc = internal_workspace(need, &ws);
+        if (rc != BCONV_OK) return rc;
+      }
+    } else if (!ws || ws_bytes < need) {
+      return BCONV_EWORKSPACE;
+    }
+    if (dry) return BCONV_OK;
+    return launch_hconv(h, in, filt, bias, out, s, relu, ws, st) == hipSuccess ? BCONV_OK : BCONV_ELAUNCH;
+  }
   if (variant_id == 0) {
     if (dry) return BCONV_OK;
     return launch_direct_conv(in, filt, bias, out, s, relu, f16, st) == hipSuccess ? BCONV_OK
@@ -776,6 +833,46 @@ size_t conv_fwd_workspace_bytes(int N, int C, int H, int W, int K, int R, int S,
   return need;
 }
 
+// ---- queries of the half-precision entry points (their choice and catalogue include the
+// fp16-matrix-core tiles, which the fp32 entry points cannot run)
+int conv_fwd_f16_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  return select_variant_f16(batch_of(s, images_per_launch(s)), true, true);
+}
+
+int conv_fwd_f16_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                    int variant_id) {
+  Shape s, runs[2];
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (hconv_index(variant_id) >= 0) {
+    for (int i = 0, n = run_shapes(s, runs); i < n; ++i)
+      if (!hconv_applicable(hconv_index(variant_id), runs[i])) return 0;
+    return 1;
+  }
+  if (fma_index(variant_id) >= 0) return 0;
+  return conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, variant_id);
+}
+
+size_t conv_fwd_f16_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                    int variant_id) {
+  Shape s, runs[2];
+  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+  if (variant_id >= 0 && hconv_index(variant_id) < 0)
+    return conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant_id);
+  size_t need = variant_id < 0 ? conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, -1) : 0;
+  for (int i = 0, n = run_shapes(s, runs); i < n; ++i) {
+    const int h = variant_id < 0 ? hconv_index(select_variant_f16(runs[i], true, true)) : hconv_index(variant_id);
+    if (h < 0) continue;
+    if (!hconv_applicable(h, runs[i])) return 0;
+    const size_t b = hconv_workspace_bytes(h, runs[i]);
+    if (b > need) need = b;
+  }
+  return need;
+}
+
 // C[M x N] = A[M x K] * B[K x N] is the pointwise convolution of one "image" whose
 // N columns are the pixels: filters = rows of A, channels = the reduction index.
 int sgemm_ex(const float* A, const float* B, float* C, int M, int N, int K, void* workspace,
@@ -804,6 +901,10 @@ int conv_variant_name(int variant_id, char* buf, size_t buflen) {
     std::snprintf(buf, buflen, "%s/s1", fma_variant_name(fma_index(variant_id)));
     return BCONV_OK;
   }
+  if (hconv_index(variant_id) >= 0) {
+    std::snprintf(buf, buflen, "%s/s1", hconv_variant_name(hconv_index(variant_id)));
+    return BCONV_OK;
+  }
   int t, nsplit;
   if (!decode_variant(variant_id, &t, &nsplit)) return BCONV_EVARIANT;
   std::snprintf(buf, buflen, "%s/s%d", kTiles[t].name, nsplit);
@@ -823,6 +924,7 @@ int conv_variant_applicable(int N, int C, int H, int W, int K, int R, int S, int
   int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
   if (rc != BCONV_OK) return rc;
   if (variant_id == 0) return 1;
+  if (hconv_index(variant_id) >= 0) return 0;   // half-precision entry points only
   int t, nsplit;
   Plan pl;
   Shape runs[2];

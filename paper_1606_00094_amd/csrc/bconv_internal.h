@@ -54,4 +54,15 @@ bool fma_conv_applicable(int which, const Shape& s);
 hipError_t launch_fma_conv(int which, const float* in, const float* filt, const float* bias, float* out,
                            const Shape& s, int relu, hipStream_t st);
 
+// Half-precision convolution on the fp16 matrix cores (hconv_mfma.hip); `which` indexes its
+// catalogue.  fp16 storage only; needs hconv_workspace_bytes of device scratch for the re-laid
+// filters.
+int hconv_num_variants();
+const char* hconv_variant_name(int which);
+bool hconv_applicable(int which, const Shape& s);
+size_t hconv_workspace_bytes(int which, const Shape& s);
+int hconv_select(const Shape& s);
+hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
+                        const Shape& s, int relu, void* ws, hipStream_t st);
+
 }  // namespace bconv

@@ -1,0 +1,441 @@
+// Half-precision convolution on the fp16 matrix cores (v_mfma_f32_32x32x16_f16): the second
+// stage of the paper's Section VII outlook (smaller storage types, here with the matrix
+// arithmetic in that type too: fp16 x fp16 products are exact in fp32 and the sums are fp32,
+// so the contract of the fp32-arithmetic path -- exact products, fp32 accumulation, one
+// rounding to fp16 after bias and ReLU -- is unchanged).  Stride-1 layers with a 1x1, 3x3 or
+// 5x5 kernel and a channel count that is a multiple of eight; everything else stays on the
+// tiled kernel that widens to fp32.
+//
+// One MFMA consumes 16 reduction elements; lanes 0-31 carry eight of them, lanes 32-63 the other
+// eight, as one 16-byte register quad per operand.  The reduction is therefore ordered
+// (kernel row, kernel column, channel) with the channel innermost, and both operands are held
+// in LDS as "octets" -- eight consecutive channels of one filter tap, or of one input position,
+// in 16 bytes -- so that every operand read is one ds_read_b128:
+//   * filters: re-laid once per call by a small kernel from KCRS into
+//     [filter][chunk][tap][CC channels] (CC channels per staged chunk, zero beyond C), from
+//     where a workgroup's rows of a chunk are contiguous 16-byte units;
+//   * input: the tile's halo (every padded input position its pixels touch, as in the fp32
+//     kernel's halo staging) is staged per chunk position by position: a thread gathers the
+//     eight channels of one position from the NCHW planes (each of the eight loads is
+//     coalesced over the positions of a wave), packs them and writes one octet.  The kernel
+//     taps are then offsets of the LDS read, uniform over the lanes.
+// Software pipeline: the global loads of chunk i+1 are in flight while chunk i is multiplied
+// out of one LDS buffer, and are written to the other buffer afterwards; one barrier per chunk.
+#include <atomic>
+#include <cstdint>
+#include <cstring>
+
+#include "bconv_internal.h"
+
+namespace bconv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float hacc_t __attribute__((ext_vector_type(16)));
+typedef unsigned uquad __attribute__((ext_vector_type(4)));
+
+struct HconvParams {
+  TconvParams g;            // shape and halo geometry; g.in / g.out address _Float16 elements
+  const _Float16* filt2;    // re-laid filters [K][nch][taps][CC]
+  int nch;                  // chunks of CC channels
+  int npos;                 // staged positions per octet plane
+  int coct;                 // C / 8
+};
+
+template <int R_, int S_, int WM, int WN, int MT, int NT, int CC, int EPB>
+__global__ __launch_bounds__(WM * WN * 64)
+void hconv_mfma_kernel(const HconvParams hp) {
+  constexpr int NTHR = WM * WN * 64;
+  constexpr int BM = WM * MT * 32, BN = WN * NT * 32;
+  constexpr int TAPS = R_ * S_;
+  constexpr int NOCT = CC / 8;            // octets per position (or tap) and chunk
+  constexpr int NJ = CC / 16;             // MFMAs per tap and chunk
+  constexpr int AROW = TAPS * NOCT;       // 16-byte units per filter row and chunk
+  constexpr int AST = AROW | 1;           // LDS row stride (odd: rows spread over the banks)
+  constexpr int NA = (BM * AROW + NTHR - 1) / NTHR;
+  constexpr bool PW = (R_ == 1 && S_ == 1);
+  static_assert(CC % 16 == 0, "a chunk is a whole number of MFMAs");
+  const TconvParams& p = hp.g;
+  const int npos = hp.npos;
+
+  extern __shared__ __attribute__((aligned(16))) uquad hsm[];
+  uquad* const As = hsm;                           // [2][BM][AST]
+  uquad* const Bs = hsm + 2 * BM * AST;            // [2][NOCT][npos]
+  const int abuf = BM * AST, bbuf = NOCT * npos;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, gq = lane >> 5;
+
+  const BlockTile bt = xcd_tile(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x, gridDim.y, 1, p.filter_major);
+  const PixTile t = pix_tile(bt.x, BN, p.NPQ, p.Q, p.fdQ);
+  const HaloTile ht = PW ? HaloTile{0, 0} : halo_tile(p, t);
+  const int m0 = bt.y * BM;
+  constexpr unsigned kOob = 0x80000000u;
+
+  // ---- input staging items of this thread: (octet o, position pos), fixed for the whole loop
+  unsigned b_voff[EPB];
+  int b_lds[EPB], b_oct[EPB];
+#pragma unroll
+  for (int i = 0; i < EPB; ++i) {
+    int e = tid + i * NTHR;
+    int o = 0;
+    while (o < NOCT && e >= npos) { e -= npos; ++o; }
+    const bool item = o < NOCT;
+    int goff = 0;
+    bool ok = item;
+    if (PW) {
+      // compact: position = pixel of the tile; a flattened image is one row of H*W pixels
+      ok = ok && (e < t.cnt);
+      const int gp = t.g0 + (ok ? e : 0);
+      const int img = fd_div(gp, p.fdQ);
+      goff = img * p.CHW + (gp - img * p.Q);
+    } else {
+      BCell c = h_cell(p, ht, item ? e : 0, 1);
+      ok = ok && (c.ih0 != kNeverValid);
+      goff = c.goff;
+    }
+    b_oct[i] = item ? o : NOCT;                    // NOCT: no item (never loads, stores nowhere)
+    b_lds[i] = item ? o * npos + e : 0;
+    b_voff[i] = ok ? (unsigned)((goff + o * 8 * p.HW) * 2) : kOob;
+  }
+  // ---- filter staging items: 16-byte unit j of filter row m
+  unsigned a_voff[NA];
+  int a_lds[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int e = tid + i * NTHR;
+    const int m = e / AROW, j = e - m * AROW;
+    const bool ok = (e < BM * AROW) && (m0 + m < p.K);
+    a_voff[i] = ok ? (unsigned)((((m0 + m) * hp.nch) * AROW + j) * 16) : kOob;
+    a_lds[i] = (e < BM * AROW) ? m * AST + j : -1;
+  }
+  const __amdgpu_buffer_rsrc_t rsrc_in = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(p.in), 0, p.N * p.CHW * 2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_f = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<_Float16*>(hp.filt2), 0, p.K * hp.nch * AROW * 16, 0x00020000);
+
+  // ---- per-lane operand bases (16-byte units)
+  const int laneA = (wm * MT * 32 + l32) * AST + gq;
+  int laneB[NT], outoff[NT], colvalid[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int col = (wn * NT + nt) * 32 + l32;
+    if (PW) {
+      const bool v = col < t.cnt;
+      const int cc = v ? col : t.cnt - 1;
+      const int gp = t.g0 + cc;
+      const int img = fd_div(gp, p.fdQ);
+      laneB[nt] = cc + gq * npos;
+      outoff[nt] = img * p.K * p.PQ + (gp - img * p.Q);
+      colvalid[nt] = v;
+    } else {
+      BLane bl = h_lane(p, t, ht, col);
+      laneB[nt] = bl.ldsbase + gq * npos;
+      outoff[nt] = bl.outoff;
+      colvalid[nt] = bl.valid;
+    }
+  }
+
+  hacc_t acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
+
+  uquad ra[NA];
+  unsigned short rb[EPB][8];
+  auto load_chunk = [&](int ch) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+      ra[i] = __builtin_bit_cast(uquad, __builtin_amdgcn_raw_buffer_load_b128(rsrc_f, a_voff[i], ch * AROW * 16, 0));
+#pragma unroll
+    for (int i = 0; i < EPB; ++i) {
+      // an octet past the last channel reads nothing (C is a multiple of eight)
+      const unsigned voff = (ch * NOCT + b_oct[i] < hp.coct) ? b_voff[i] : kOob;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        rb[i][u] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_in, voff, (ch * CC + u) * p.HW * 2, 0);
+    }
+  };
+  auto store_chunk = [&](int buf) {
+    uquad* A = As + buf * abuf;
+    uquad* B = Bs + buf * bbuf;
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+      if (a_lds[i] >= 0) A[a_lds[i]] = ra[i];
+#pragma unroll
+    for (int i = 0; i < EPB; ++i) {
+      if (b_oct[i] < NOCT) {
+        uquad v;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) v[w] = (unsigned)rb[i][2 * w] | ((unsigned)rb[i][2 * w + 1] << 16);
+        B[b_lds[i]] = v;
+      }
+    }
+  };
+  auto compute_chunk = [&](int buf) {
+    const uquad* A = As + buf * abuf;
+    const uquad* B = Bs + buf * bbuf;
+#pragma unroll
+    for (int tap = 0; tap < TAPS; ++tap) {
+      const int toff = PW ? 0 : (tap / S_) * p.rowst + (tap % S_);
+#pragma unroll
+      for (int jj = 0; jj < NJ; ++jj) {
+        half8 a[MT], b[NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          a[mt] = __builtin_bit_cast(half8, A[laneA + mt * 32 * AST + tap * NOCT + 2 * jj]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          b[nt] = __builtin_bit_cast(half8, B[laneB[nt] + 2 * jj * npos + toff]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+      }
+    }
+  };
+
+  load_chunk(0);
+  store_chunk(0);
+  __syncthreads();
+  for (int ch = 0; ch < hp.nch; ++ch) {
+    const bool more = ch + 1 < hp.nch;
+    if (more) load_chunk(ch + 1);
+    compute_chunk(ch & 1);
+    if (more) store_chunk((ch + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: bias + optional ReLU, one rounding to fp16, store
+  _Float16* const out = reinterpret_cast<_Float16*>(p.out);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
+      if (k < p.K) {
+        const float bv = p.bias ? p.bias[k] : 0.0f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          if (colvalid[nt]) {
+            float v = acc[mt][nt][i] + bv;
+            if (p.relu) v = v > 0.0f ? v : 0.0f;
+            out[outoff[nt] + k * p.PQ] = (_Float16)v;
+          }
+        }
+      }
+    }
+  }
+}
+
+// filt KCRS (fp16) -> [K][nch][R*S][CC], zeros for channels past C
+__global__ __launch_bounds__(256)
+void hconv_repack_kernel(const _Float16* __restrict__ filt, _Float16* __restrict__ filt2, int K, int C,
+                         int taps, int CC, int nch, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int cc = (int)(idx % CC);
+    long long r = idx / CC;
+    const int tap = (int)(r % taps);
+    r /= taps;
+    const int ch = (int)(r % nch);
+    const int k = (int)(r / nch);
+    const int c = ch * CC + cc;
+    filt2[idx] = c < C ? filt[((long long)k * C + c) * taps + tap] : (_Float16)0.0f;
+  }
+}
+
+// ------------------------------------------------------------------ catalogue and planning
+struct HTile {
+  const char* name;
+  int R, S, WM, WN, MT, NT, CC, EPB;
+  int BM() const { return WM * MT * 32; }
+  int BN() const { return WN * NT * 32; }
+  int NTHR() const { return WM * WN * 64; }
+};
+#define HCONV_TILES(X)                         \
+  X(h16k3_128x128_c16, 3, 3, 2, 2, 2, 2, 16, 3) \
+  X(h16k3_64x128_c16, 3, 3, 2, 2, 1, 2, 16, 3)  \
+  X(h16k3_128x64_c16, 3, 3, 2, 2, 2, 1, 16, 2)  \
+  X(h16k3_64x64_c16, 3, 3, 2, 2, 1, 1, 16, 2)   \
+  X(h16k3_64x128_c32, 3, 3, 2, 2, 1, 2, 32, 6)  \
+  X(h16k5_64x128_c16, 5, 5, 2, 2, 1, 2, 16, 4)  \
+  X(h16k5_64x64_c16, 5, 5, 2, 2, 1, 1, 16, 3)   \
+  X(h16k5_32x128_c16, 5, 5, 1, 4, 1, 1, 16, 4)  \
+  X(h16pw_128x128_c32, 1, 1, 2, 2, 2, 2, 32, 2) \
+  X(h16pw_64x128_c32, 1, 1, 2, 2, 1, 2, 32, 2)  \
+  X(h16pw_128x64_c32, 1, 1, 2, 2, 2, 1, 32, 1)  \
+  X(h16pw_64x64_c32, 1, 1, 2, 2, 1, 1, 32, 1)   \
+  X(h16pw_64x64_c64, 1, 1, 2, 2, 1, 1, 64, 2)   \
+  X(h16k3_32x128_c16, 3, 3, 1, 4, 1, 1, 16, 3)  \
+  X(h16k3_32x64_c16, 3, 3, 1, 2, 1, 1, 16, 4)   \
+  X(h16k3_64x64_c32, 3, 3, 2, 2, 1, 1, 32, 4)   \
+  X(h16pw_32x128_c64, 1, 1, 1, 4, 1, 1, 64, 4)  \
+  X(h16pw_32x64_c64, 1, 1, 1, 2, 1, 1, 64, 4)   \
+  X(h16pw_64x32_c64, 1, 1, 2, 1, 1, 1, 64, 2)
+
+static const HTile kHTiles[] = {
+#define X(name, R, S, WM, WN, MT, NT, CC, EPB) {#name, R, S, WM, WN, MT, NT, CC, EPB},
+    HCONV_TILES(X)
+#undef X
+};
+constexpr int kNumHTiles = (int)(sizeof(kHTiles) / sizeof(kHTiles[0]));
+
+typedef hipError_t (*HLaunchFn)(const HconvParams&, dim3, size_t, hipStream_t);
+// (dynamic LDS above the default limit must be allowed per kernel and device; the largest
+// request so far is remembered, host threads may race on it harmlessly)
+template <typename KernelT>
+static hipError_t launch_h(KernelT kernel, int nthr, const HconvParams& hp, dim3 grid, size_t lds, hipStream_t st,
+                           std::atomic<size_t>* allowed) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (lds > 32768 && lds > allowed[dev].load(std::memory_order_relaxed)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds);
+    if (e != hipSuccess) { (void)hipGetLastError(); return e; }
+    allowed[dev].store(lds, std::memory_order_relaxed);
+  }
+  return launch_kernel(kernel, grid, dim3(nthr), lds, st, hp);
+}
+#define X(name, R, S, WM, WN, MT, NT, CC, EPB)                                                        \
+  static hipError_t hlaunch_##name(const HconvParams& hp, dim3 grid, size_t lds, hipStream_t st) {    \
+    static std::atomic<size_t> allowed[64];                                                           \
+    return launch_h(hconv_mfma_kernel<R, S, WM, WN, MT, NT, CC, EPB>, WM * WN * 64, hp, grid, lds, st, allowed); \
+  }
+HCONV_TILES(X)
+#undef X
+static const HLaunchFn kHLaunch[] = {
+#define X(name, R, S, WM, WN, MT, NT, CC, EPB) hlaunch_##name,
+    HCONV_TILES(X)
+#undef X
+};
+
+int hconv_num_variants() { return kNumHTiles; }
+const char* hconv_variant_name(int which) { return kHTiles[which].name; }
+
+struct HPlan {
+  HconvParams hp;
+  unsigned gx, gy;
+  size_t lds_bytes;
+  size_t filt2_bytes;
+};
+
+static bool plan_hconv(int which, const Shape& s0, HPlan* pl) {
+  const HTile& v = kHTiles[which];
+  Shape s = s0;
+  if (s.R != v.R || s.S != v.S || s.stride != 1 || s.C % 8 != 0) return false;
+  const long long i31 = (1LL << 31) - 1;
+  if ((long long)s.N * s.C * s.H * s.W * 2 > i31 || (long long)s.N * s.K * s.P * s.Q > i31) return false;
+  const bool pw = (s.R == 1 && s.S == 1);
+  if (pw && s.pad != 0) return false;
+  if (pw) {                        // per-image im2col is the identity: one row of H*W pixels
+    s.W = s.H * s.W; s.H = 1; s.Q = s.P * s.Q; s.P = 1;
+  }
+  TconvParams& p = pl->hp.g;
+  std::memset(&pl->hp, 0, sizeof(pl->hp));
+  p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.R = s.R; p.S = s.S;
+  p.stride = 1; p.pad = s.pad; p.P = s.P; p.Q = s.Q;
+  p.PQ = s.P * s.Q; p.NPQ = s.N * p.PQ; p.HW = s.H * s.W; p.CHW = s.C * p.HW;
+  p.CRS = s.C * s.R * s.S; p.CRrows = s.C * s.R;
+  p.out_elems = s.N * s.K * p.PQ;
+  p.fdQ = make_fastdiv((unsigned)p.Q); p.fdP = make_fastdiv((unsigned)p.P);
+  p.filter_major = (long long)s.K * s.C * s.R * s.S > (long long)s.N * s.C * s.H * s.W ? 1 : 0;
+  p.halo = 1;
+  p.hp = s.H + 2 * s.pad; p.wt = s.W + 2 * s.pad;
+  p.phst = p.wt; p.rowst = p.wt;
+  p.fdHp = make_fastdiv((unsigned)p.hp); p.fdRowst = make_fastdiv((unsigned)p.rowst);
+  const int BN = v.BN(), BM = v.BM();
+  const long long ntiles = ((long long)p.NPQ + BN - 1) / BN;
+  if (ntiles > i31) return false;
+  int npos = BN;
+  if (!pw) {
+    p.vr = 0;
+    for (long long ti = 0; ti < ntiles; ++ti) {
+      HaloTile h = halo_tile(p, pix_tile((int)ti, BN, p.NPQ, p.Q, p.fdQ));
+      if (h.vr > p.vr) p.vr = h.vr;
+    }
+    p.nrows = p.vr;
+    p.plane = p.nrows * p.rowst;
+    npos = p.plane;
+  }
+  const int noct = v.CC / 8;
+  if ((long long)noct * npos > (long long)v.EPB * v.NTHR()) return false;
+  const int arow = v.R * v.S * noct, ast = arow | 1;
+  const size_t lds = (size_t)16 * (2 * (size_t)BM * ast + 2 * (size_t)noct * npos);
+  if (lds > kLdsLimitBytes) return false;
+  pl->hp.nch = (s.C + v.CC - 1) / v.CC;
+  pl->hp.npos = npos;
+  pl->hp.coct = s.C / 8;
+  pl->filt2_bytes = (size_t)s.K * pl->hp.nch * arow * 16;
+  if ((long long)pl->filt2_bytes > i31) return false;
+  const long long gy = (s.K + BM - 1) / BM;
+  if (gy > 65535) return false;
+  pl->gx = (unsigned)ntiles;
+  pl->gy = (unsigned)gy;
+  pl->lds_bytes = lds;
+  return true;
+}
+
+bool hconv_applicable(int which, const Shape& s) {
+  HPlan pl;
+  return plan_hconv(which, s, &pl);
+}
+
+size_t hconv_workspace_bytes(int which, const Shape& s) {
+  HPlan pl;
+  return plan_hconv(which, s, &pl) ? pl.filt2_bytes : 0;
+}
+
+// The tile the half-precision entry points take for a shape the half-precision table does not
+// list, or -1 when the layer is better left to the widening kernel (not applicable, or too
+// few output points).  The kernel hides its LDS and memory latency with resident waves, not
+// with a deep software pipeline, so the small tiles win wherever the sweep looked (64x64 for
+// 3x3 and pointwise, 32x128 for 5x5): the workgroups of the busiest compute unit, run
+// `resident` at a time, each costing its tile's work plus a per-workgroup overhead.
+int hconv_select(const Shape& s) {
+  if ((long long)s.N * s.P * s.Q < 1024) return -1;
+  int best = -1;
+  double best_cost = 0.0;
+  for (int w = 0; w < kNumHTiles; ++w) {
+    HPlan pl;
+    if (!plan_hconv(w, s, &pl)) continue;
+    const HTile& v = kHTiles[w];
+    const double wgs = (double)pl.gx * pl.gy;
+    const double per_cu = (double)(((long long)wgs + 255) / 256);
+    int resident = (int)(kLdsLimitBytes / pl.lds_bytes);
+    if (resident > 8) resident = 8;
+    const double waves = (per_cu < resident ? per_cu : resident) * v.NTHR() / 256.0;   // per SIMD
+    const double eff = waves >= 3.0 ? 1.0 : (waves >= 2.0 ? 0.8 : 0.5);
+    const double cost = per_cu * ((double)v.BM() * v.BN() * (1.0 + 16.0 / v.BM() + 16.0 / v.BN()) + 3000.0) / eff;
+    if (best < 0 || cost < best_cost) { best = w; best_cost = cost; }
+  }
+  return best;
+}
+
+hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
+                        const Shape& s, int relu, void* ws, hipStream_t st) {
+  HPlan pl;
+  if (!plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
+  const HTile& v = kHTiles[which];
+  const long long total = (long long)(pl.filt2_bytes / 2);
+  long long blocks = (total + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipError_t e = launch_kernel(hconv_repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                               static_cast<const _Float16*>(filt),
+                               static_cast<_Float16*>(ws), s.K, s.C, v.R * v.S, v.CC, pl.hp.nch, total);
+  if (e != hipSuccess) return e;
+  pl.hp.g.in = static_cast<const float*>(in);
+  pl.hp.g.bias = bias;
+  pl.hp.g.out = static_cast<float*>(out);
+  pl.hp.g.relu = relu;
+  pl.hp.filt2 = static_cast<const _Float16*>(ws);
+  return kHLaunch[which](pl.hp, dim3(pl.gx, pl.gy), pl.lds_bytes, st);
+}
+
+}  // namespace bconv

@@ -137,6 +137,73 @@ def main_pooled(args, batches, names):
     return 0
 
 
+def sweep_layer_f16(layer, N):
+    """Half-precision storage: every tile on the fp16 matrix cores that applies, against what the
+    half-precision entry points would run without them (the fp32 table's choice, widening)."""
+    dev = torch.device("cuda:0")
+    x, f, b = workloads.make_layer_inputs(layer, N)
+    xd, fd = torch.from_numpy(x).to(dev).half(), torch.from_numpy(f).to(dev).half()
+    bd = None if b is None else torch.from_numpy(b).to(dev)
+    dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+    P, Q = binding.conv_out_dims(layer.H, layer.W, layer.R, layer.S, layer.stride, layer.pad)
+    out = torch.empty((N, layer.K, P, Q), dtype=torch.float16, device=dev)
+    ref = torch.empty_like(out)
+    base = binding.conv_selected_variant(*dims)
+    need = binding.conv_fwd_f16_workspace_bytes(*dims, base)
+    ws0 = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+    binding.conv_fwd_f16_ex(xd, fd, bd, ref, layer.stride, layer.pad, True, workspace=ws0, variant=base)
+    flops = roofline.conv_flops(*dims)
+    rows = []
+    for v in [base] + [v for v in range(1, binding.conv_num_variants())
+                       if binding.conv_variant_name(v).startswith("h16")]:
+        if not binding.conv_fwd_f16_variant_applicable(*dims, v):
+            continue
+        need = binding.conv_fwd_f16_workspace_bytes(*dims, v)
+        ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+
+        def run():
+            binding.conv_fwd_f16_ex(xd, fd, bd, out, layer.stride, layer.pad, True, workspace=ws, variant=v)
+        us = graph_time_us(run, best=True)
+        err = (out.float() - ref.float()).abs()
+        ok = bool((err <= torch.clamp(ref.float().abs() * 2.0 ** -9, min=1e-5)).all())
+        rows.append({"variant": binding.conv_variant_name(v), "us": round(us, 2),
+                     "tflops": round(flops / us / 1e6, 2), "ok": ok, "base": v == base})
+        del ws
+    rows.sort(key=lambda r: r["us"])
+    return rows
+
+
+def main_f16(args, batches, names):
+    """--f16: rows for f16_selection_table.inc where an fp16-matrix-core tile beats the
+    half-precision path's fallback by more than 2 %."""
+    layers = [l for l in workloads.ALL_LAYERS + workloads.EXTRA_LAYERS if (l.name in names if names else l in workloads.ALL_LAYERS)]
+    results, table = [], []
+    for layer in layers:
+        for N in batches:
+            rows = sweep_layer_f16(layer, N)
+            good = [r for r in rows if r["ok"]]
+            base_us = next((r["us"] for r in rows if r["base"]), None)
+            best = good[0] if good else None
+            results.append({"layer": layer.name, "N": N, "best": best, "all": rows})
+            print("%-18s N=%-3d f16 best %-22s %8.2f us %7.1f TFLOP/s; widening path %s (%d candidates, %d failed)"
+                  % (layer.name, N, best["variant"] if best else "-", best["us"] if best else 0,
+                     best["tflops"] if best else 0, "%.2f us" % base_us if base_us else "-", len(rows),
+                     len(rows) - len(good)), flush=True)
+            if best and not best["base"] and base_us and best["us"] < 0.98 * base_us:
+                tile, split = best["variant"].split("/s")
+                table.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, "%s", %s},  // %s N=%d: %.1f us (widening path %.1f)'
+                             % (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride,
+                                layer.pad, tile, split, layer.name, N, best["us"], base_us))
+    with open(args.out, "w") as fh:
+        json.dump(results, fh, indent=1)
+    with open(args.table, "w") as fh:
+        fh.write("// Variant choices of the half-precision entry points, written by the offline tuning sweep\n"
+                 "// (paper_1606_00094_amd/tune.py --f16): rows where a tile on the fp16 matrix cores is the measured best.\n"
+                 "// Row: {N, C, H, W, K, R, S, stride, pad, \"tile\", nsplit},\n")
+        fh.write("\n".join(table) + ("\n" if table else ""))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="tune.json")
@@ -148,6 +215,8 @@ def main():
     ap.add_argument("--sgemm", action="store_true", help="also sweep the square matrix products")
     ap.add_argument("--pool", action="store_true",
                     help="sweep the convolution + pooling call instead (rows for pool_selection_table.inc)")
+    ap.add_argument("--f16", action="store_true",
+                    help="sweep the half-precision entry points' fp16-matrix-core tiles (rows for f16_selection_table.inc)")
     ap.add_argument("--max-split", type=int, default=0, help="largest reduction split to try (0: by batch)")
     ap.add_argument("--only", default="",
                     help="regular expression: sweep only the variants whose name matches, against "
@@ -157,6 +226,8 @@ def main():
     names = [t for t in args.layers.split(",") if t]
     if args.pool:
         return main_pooled(args, batches, names)
+    if args.f16:
+        return main_f16(args, batches, names)
     # the square matrix products (batch 1 only) are swept when named, or with --sgemm
     pool = workloads.ALL_LAYERS + (workloads.SGEMM_LAYERS if args.sgemm or names else []) + \
         (workloads.EXTRA_LAYERS if args.extra or names else [])

@@ -114,10 +114,12 @@ def test_direct_variant_on_toy_and_first_layer():
 # ------------------------------------------------------------------ exact-integer, every tile
 FAMILY_SHAPES = {
     # (R, S, stride) of a tile family -> list of (N, C, H, W, K, pad)
-    (3, 3, 1): [(2, 13, 13, 13, 70, 1), (1, 5, 30, 31, 129, 1), (3, 4, 7, 5, 33, 0), (1, 44, 13, 13, 40, 1)],
-    (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2), (1, 8, 27, 27, 70, 2), (1, 20, 14, 14, 20, 2)],
+    (3, 3, 1): [(2, 13, 13, 13, 70, 1), (1, 5, 30, 31, 129, 1), (3, 4, 7, 5, 33, 0), (1, 44, 13, 13, 40, 1),
+                (2, 24, 13, 13, 70, 1), (1, 40, 28, 28, 130, 2)],
+    (5, 5, 1): [(2, 6, 27, 27, 40, 2), (1, 3, 9, 11, 130, 2), (1, 8, 27, 27, 70, 2), (1, 20, 14, 14, 20, 2),
+                (3, 16, 14, 14, 40, 2)],
     (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0), (5, 8, 6, 6, 33, 0),
-                (2, 132, 7, 7, 40, 0)],
+                (2, 132, 7, 7, 40, 0), (2, 72, 14, 14, 130, 0), (3, 40, 7, 7, 50, 0)],
     (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
     (7, 7, 2): [(2, 3, 37, 41, 70, 3), (1, 3, 224, 224, 64, 3), (1, 2, 30, 29, 33, 0)],
     (1, 1, 2): [(2, 20, 14, 14, 70, 0), (1, 36, 28, 27, 130, 0), (3, 8, 7, 9, 33, 1)],
@@ -140,11 +142,11 @@ def _tile_families():
 
 
 def _family_of(tile):
-    if tile.startswith("k3_"):
+    if tile.startswith(("k3_", "h16k3_")):
         return (3, 3, 1)
-    if tile.startswith("k5_"):
+    if tile.startswith(("k5_", "h16k5_")):
         return (5, 5, 1)
-    if tile.startswith("pw_"):
+    if tile.startswith(("pw_", "h16pw_")):
         return (1, 1, 1)
     if tile.startswith("k11s4_"):
         return (11, 11, 4)
@@ -167,7 +169,8 @@ def _family_of(tile):
     raise KeyError(tile)
 
 
-@pytest.mark.parametrize("tile", sorted(_tile_families()))
+# (the h16... tiles multiply on the fp16 matrix cores: half-precision entry points only)
+@pytest.mark.parametrize("tile", sorted(t for t in _tile_families() if not t.startswith("h16")))
 def test_every_tile_variant_exact_on_integers(tile):
     """Each compiled tile, unsplit and with every applicable reduction split, on
     shapes with ragged filter / pixel / channel tails: bitwise equal to the oracle."""
@@ -717,7 +720,7 @@ def test_fuzz_random_variants_exact_on_integers():
     nv = binding.conv_num_variants()
     fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2),
            "pws2": (1, 1, 2), "k3s2": (3, 3, 2), "k1x7": (1, 7, 1), "k7x1": (7, 1, 1),
-           "fmaq4": (11, 11, 4), "fmaq2": (7, 7, 2)}
+           "fmaq4": (11, 11, 4), "fmaq2": (7, 7, 2), "h16k3": (3, 3, 1), "h16k5": (5, 5, 1), "h16pw": (1, 1, 1)}
     ran = 0
     for it in range(500):
         v = int(rng.integers(1, nv))

@@ -63,7 +63,7 @@ def gpu_conv_f16(x, f, b, stride, pad, relu, variant=-1, use_simple_entry=False,
         binding.conv_fwd_f16(xd, fd, bd, out, stride, pad, relu)
     else:
         ws = None
-        need = binding.conv_fwd_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant)
+        need = binding.conv_fwd_f16_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant)
         if need:
             ws = torch.zeros((need + 3) // 4, dtype=torch.float32, device=dev)
         binding.conv_fwd_f16_ex(xd, fd, bd, out, stride, pad, relu, workspace=ws, variant=variant)
@@ -110,6 +110,33 @@ def test_f16_simple_entry_direct_kernel_and_missing_bias():
         assert_close_f16(gpu_conv_f16(x, f, None, s, p, False), ref, layer.name + " no bias")
 
 
+def test_f16_matrix_core_tiles_through_the_simple_entry_and_errors():
+    """A launch large enough for the fp16-matrix-core tiles through conv_fwd_f16 (library's own
+    workspace for the re-laid filters), without bias and without ReLU too; the fp32 entry point
+    refuses such a variant, and the half-precision one refuses it without its workspace."""
+    layer, N = workloads.RED3, 8
+    dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+    v = binding.conv_fwd_f16_selected_variant(*dims)
+    assert binding.conv_variant_name(v).startswith("h16")
+    assert not binding.conv_variant_applicable(*dims, v)
+    assert binding.conv_fwd_f16_workspace_bytes(*dims, v) > 0
+    x, f, b, s, p = _layer_case(layer, N)
+    ref = oracle.conv_fwd_f16(x, f, b, stride=s, pad=p, relu=True)
+    assert_close_f16(gpu_conv_f16(x, f, b, s, p, True, use_simple_entry=True), ref, "simple entry")
+    ref = oracle.conv_fwd_f16(x, f, None, stride=s, pad=p, relu=False)
+    assert_close_f16(gpu_conv_f16(x, f, None, s, p, False), ref, "no bias, no relu")
+    dev = torch.device("cuda:0")
+    xd, fd = torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev)
+    out = torch.zeros((N, layer.K, 28, 28), dtype=torch.float16, device=dev)
+    with pytest.raises(binding.BconvError) as e:
+        binding.conv_fwd_f16_ex(xd, fd, None, out, s, p, True, workspace=None, variant=v)
+    assert e.value.status == -4
+    with pytest.raises(binding.BconvError) as e:
+        binding.conv_fwd_ex(xd.float(), fd.float(), None, out.float(), s, p, True, variant=v)
+    assert e.value.status == -6
+    torch.cuda.synchronize()
+
+
 # (the vector-FMA first-layer kernels are fp32-storage only)
 @pytest.mark.parametrize("tile", sorted(t for t in _tile_families() if not t.startswith("fmaq")))
 def test_f16_every_tile_variant_exact_on_integers(tile):
@@ -127,7 +154,7 @@ def test_f16_every_tile_variant_exact_on_integers(tile):
         x, f = x.astype(np.float16), f.astype(np.float16)
         ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=False)
         for v in _tile_families()[tile]:
-            if not binding.conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+            if not binding.conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
                 continue
             got = gpu_conv_f16(x, f, b, stride, pad, False, variant=v)
             assert np.array_equal(got, ref), "%s on %s" % (binding.conv_variant_name(v), (shp,))

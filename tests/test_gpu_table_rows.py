@@ -19,6 +19,7 @@ import oracle
 import workloads
 from paper_1606_00094_amd import binding
 from tests.test_gpu_parity import assert_close, gpu_conv, gpu_conv_pool
+from tests.test_gpu_parity_f16 import assert_close_f16, gpu_conv_f16
 
 pytestmark = pytest.mark.gpu
 
@@ -74,6 +75,23 @@ def test_pool_selection_table_row(row):
     ref = oracle.maxpool_fwd(oracle.conv_fwd(x, f, b, stride=stride, pad=pad, relu=True), 3, 2)
     got = gpu_conv_pool(x, f, b, stride, pad, True, 3, 2)
     assert_close(got, ref, "%s + pool via %s" % (_row_id(row), chosen))
+
+
+@pytest.mark.parametrize("row", table_rows("f16_selection_table.inc"), ids=_row_id)
+def test_f16_selection_table_row(row):
+    """Rows of the half-precision table (tiles on the fp16 matrix cores): the half-precision
+    entry point picks the row's tile and gives the correctly rounded exact result to within one
+    fp16 spacing, every image."""
+    dims, tile, nsplit = row[:9], row[9], row[10]
+    N, C, H, W, K, R, S, stride, pad = dims
+    chosen = binding.conv_variant_name(binding.conv_fwd_f16_selected_variant(*dims))
+    assert chosen == "%s/s%d" % (tile, nsplit), "variant -1 resolves to %s" % chosen
+    layer = _layer_of(dims)
+    x, f, b = workloads.make_layer_inputs(layer, N, seed=workloads.BASE_SEED + 500000 + sum(dims))
+    x, f = x.astype(np.float16), f.astype(np.float16)
+    ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=True)
+    got = gpu_conv_f16(x, f, b, stride, pad, True)
+    assert_close_f16(got, ref, "%s via %s" % (_row_id(row), chosen))
 
 
 def test_rows_cover_the_batch_points():
