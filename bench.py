@@ -414,6 +414,19 @@ def main():
         r1 = by_key.get((l.name, 1, "cold"))
         per_layer[l.name] = [r32["us"], r32["frac_mfma"]] + (
             [r1["us"], r1["gbps"], r1["frac_hbm"], round(floor_us / r1["us"], 3)] if r1 and floor_us else [])
+    # half-precision storage (context, not part of `value`): time per layer at the benchmark batch
+    # and the largest one against the fp16 matrix peak (its kernel multiplies on those cores)
+    per_layer_f16, roof16 = {}, None
+    rows16 = [r for r in table_f16 if r["N"] == args.batch]
+    for r in rows16:
+        per_layer_f16[r["layer"]] = [r["us"], round(r["gflops"] / 1e3, 1)]
+    if rows16:
+        on_cores = [r for r in rows16 if r["variant"].startswith("h16")] or rows16
+        big = max(on_cores, key=lambda r: r["us"])
+        roof16 = {"bound": "mfma", "dtype": "f16 storage, fp32 accumulate", "achieved": round(big["gflops"] / 1e3, 1),
+                  "peak": roofline.PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                  "frac": round(big["gflops"] / 1e3 / roofline.PEAK_FP16_MFMA_TFLOPS, 4),
+                  "layer": big["layer"], "N": big["N"], "kernel": big["variant"], "us_per_launch": big["us"]}
     full = {"layers": table, "layers_batch_%d" % args.big_batch: table_big, "layers_f16_storage": table_f16,
             "stack": stack, "sgemm": sgemm, "single_launch": single, "measured_peaks": measured}
     log(json.dumps({"tables": full}))
@@ -437,6 +450,8 @@ def main():
         "per_layer": per_layer,
         "stack_ms": {str(r["N"]): r["ms"] for r in stack},
         "measured_peaks": measured,
+        "per_layer_f16_columns": ["us_b%d" % args.batch, "tflops"], "per_layer_f16": per_layer_f16,
+        "roofline_f16": roof16,
         "cpu_baseline": cpu, "roofline_batch1": roof1, "roofline": roof,
     }), flush=True)
 

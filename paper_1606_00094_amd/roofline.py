@@ -8,6 +8,7 @@ MAC (141 M for 10K x 96 x 147); ``flops_per_mac`` selects that reading.
 
 # MI355X published peaks used as roofline denominators.
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_FP16_MFMA_TFLOPS = 2500.0   # dense fp16 matrix peak (half-precision entry points)
 PEAK_HBM_GBPS = 8000.0
 
 
