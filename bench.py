@@ -60,9 +60,32 @@ class LayerProblem:
                               torch.empty((N, layer.K, P, Q), dtype=store, device=dev)))
         self.k = 0
 
+    def prepack(self):
+        """Half precision, fp16-matrix-core tile: re-lay the filters once (deployment keeps its
+        weights); launch() then runs the packed call.  Returns False when there is nothing to pack."""
+        import torch
+        from paper_1606_00094_amd import binding
+        nbytes = binding.conv_f16_packed_filter_bytes(*self.dims, self.variant) if self.half else 0
+        if not nbytes:
+            return False
+        self.packed = []
+        for x, f, b, o in self.sets:
+            pk = torch.empty((nbytes + 3) // 4, dtype=torch.float32, device=x.device)
+            binding.conv_f16_pack_filters(f, pk, self.N, self.layer.H, self.layer.W, self.layer.stride,
+                                          self.layer.pad, variant=self.variant)
+            self.packed.append(pk)
+        torch.cuda.synchronize()
+        return True
+
     def launch(self):
         from paper_1606_00094_amd import binding
         x, f, b, o = self.sets[self.k]
+        if getattr(self, "packed", None):
+            pk = self.packed[self.k]
+            self.k = (self.k + 1) % len(self.sets)
+            binding.conv_fwd_f16_packed_ex(x, pk, f.shape, b, o, self.layer.stride, self.layer.pad, True,
+                                           variant=self.variant)
+            return
         self.k = (self.k + 1) % len(self.sets)
         fn = binding.conv_fwd_f16_ex if self.half else binding.conv_fwd_ex
         fn(x, f, b, o, self.layer.stride, self.layer.pad, True, workspace=self.ws,
@@ -316,6 +339,8 @@ def main():
                 ph = LayerProblem(l, N, half=True)
                 row = layer_row(ph, graph_time_us(ph.launch, launches=10 if N > 1 else 20) * 1e-3, "warm")
                 row["storage"] = "f16"
+                if ph.prepack():       # the same layer with the filters re-laid once, not per call
+                    row["us_prepacked"] = round(graph_time_us(ph.launch, launches=10) , 2)
                 table_f16.append(row)
                 del ph
     for row in table_f16:
@@ -419,7 +444,7 @@ def main():
     per_layer_f16, roof16 = {}, None
     rows16 = [r for r in table_f16 if r["N"] == args.batch]
     for r in rows16:
-        per_layer_f16[r["layer"]] = [r["us"], round(r["gflops"] / 1e3, 1)]
+        per_layer_f16[r["layer"]] = [r["us"], round(r["gflops"] / 1e3, 1), r.get("us_prepacked")]
     if rows16:
         on_cores = [r for r in rows16 if r["variant"].startswith("h16")] or rows16
         big = max(on_cores, key=lambda r: r["us"])
@@ -450,7 +475,7 @@ def main():
         "per_layer": per_layer,
         "stack_ms": {str(r["N"]): r["ms"] for r in stack},
         "measured_peaks": measured,
-        "per_layer_f16_columns": ["us_b%d" % args.batch, "tflops"], "per_layer_f16": per_layer_f16,
+        "per_layer_f16_columns": ["us_b%d" % args.batch, "tflops", "us_filters_prepacked"], "per_layer_f16": per_layer_f16,
         "roofline_f16": roof16,
         "cpu_baseline": cpu, "roofline_batch1": roof1, "roofline": roof,
     }), flush=True)

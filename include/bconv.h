@@ -138,6 +138,29 @@ int conv_fwd_f16_variant_applicable(int N, int C, int H, int W, int K, int R, in
 size_t conv_fwd_f16_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
                                     int pad, int variant_id);
 
+/* Filter pre-packing for the fp16-matrix-core tiles.  The weights of a deployed network are
+ * constant (the paper's Section VI folds a layout transformation into a pre-pass for the same
+ * reason); those tiles need the filters re-laid from KCRS into their reduction order, which
+ * conv_fwd_f16_ex does on every call.  Here the caller does it once:
+ *   conv_f16_packed_filter_bytes: bytes of the packed copy for (shape, variant_id); 0 when the
+ *     variant (for -1: conv_fwd_f16_selected_variant's choice) is not such a tile or the batch
+ *     needs more than one launch -- then there is nothing to pack, use conv_fwd_f16_ex.
+ *   conv_f16_pack_filters: filt (device, fp16 KCRS) -> packed (device, 16-byte aligned, at least
+ *     that many bytes), enqueued on hip_stream.
+ *   conv_fwd_f16_packed_ex: conv_fwd_f16_ex on a packed copy made for the SAME shape and
+ *     variant_id (the layout depends on the tile; a copy made for another tile gives wrong
+ *     results without an error); no workspace; bit for bit the result of conv_fwd_f16_ex with
+ *     that variant.
+ * Errors as conv_fwd_f16_ex; BCONV_EVARIANT where conv_f16_packed_filter_bytes returns 0. */
+size_t conv_f16_packed_filter_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                    int pad, int variant_id);
+int conv_f16_pack_filters(const void* filt, void* packed, size_t packed_bytes, int N, int C, int H,
+                          int W, int K, int R, int S, int stride, int pad, void* hip_stream,
+                          int variant_id);
+int conv_fwd_f16_packed_ex(const void* in, const void* packed, const float* bias, void* out,
+                           int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           int relu, void* hip_stream, int variant_id);
+
 /* Bytes of workspace conv_fwd_ex needs for this shape and variant (0 if none;
  * also 0 for arguments conv_fwd_ex would reject).  For variant_id = -1 the figure
  * covers the table's choice for any pointer alignment (wide loads or their narrow

@@ -26,6 +26,9 @@ EXPORTS = {
     "conv_fwd_f16_selected_variant": ([_i] * 9, _i),
     "conv_fwd_f16_variant_applicable": ([_i] * 10, _i),
     "conv_fwd_f16_workspace_bytes": ([_i] * 10, _sz),
+    "conv_f16_packed_filter_bytes": ([_i] * 10, _sz),
+    "conv_f16_pack_filters": ([_vp, _vp, _sz] + [_i] * 9 + [_vp, _i], _i),
+    "conv_fwd_f16_packed_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _i], _i),
     "conv_pool_fwd_ex": ([_vp] * 4 + [_i] * 12 + [_vp, _sz, _vp, _i], _i),
     "conv_pool_fwd_workspace_bytes": ([_i] * 10, _sz),
     "conv_pool_selected_variant": ([_i] * 11, _i),
@@ -291,6 +294,36 @@ def conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, variant):
 
 def conv_fwd_f16_workspace_bytes(N, C, H, W, K, R, S, stride, pad, variant=-1):
     return int(lib().conv_fwd_f16_workspace_bytes(N, C, H, W, K, R, S, stride, pad, int(variant)))
+
+
+def conv_f16_packed_filter_bytes(N, C, H, W, K, R, S, stride, pad, variant=-1):
+    return int(lib().conv_f16_packed_filter_bytes(N, C, H, W, K, R, S, stride, pad, int(variant)))
+
+
+def conv_f16_pack_filters(filt, packed, N, H, W, stride, pad, stream=None, variant=-1):
+    """conv_f16_pack_filters of the C ABI: `filt` float16 K x C x R x S, `packed` any contiguous
+    device tensor of at least conv_f16_packed_filter_bytes bytes."""
+    K, C, R, S = filt.shape
+    _check(lib().conv_f16_pack_filters(_dev_ptr(filt, "filt", True), packed.data_ptr(),
+                                       packed.numel() * packed.element_size(), N, C, H, W, K, R, S, stride,
+                                       pad, _stream_handle(stream), int(variant)), "conv_f16_pack_filters")
+    return packed
+
+
+def conv_fwd_f16_packed_ex(inp, packed, filt_shape, bias, out, stride, pad, relu, stream=None, variant=-1):
+    """conv_fwd_f16_packed_ex of the C ABI; filt_shape = (K, C, R, S) of the filters `packed` was made from."""
+    N, C, H, W = inp.shape
+    K, C2, R, S = filt_shape
+    if C != C2:
+        raise ValueError("in has %d channels, the filters expect %d" % (C, C2))
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    if tuple(out.shape) != (N, K, P, Q):
+        raise ValueError("out must have shape %s" % ((N, K, P, Q),))
+    _check(lib().conv_fwd_f16_packed_ex(_dev_ptr(inp, "in", True), packed.data_ptr(), _dev_ptr(bias, "bias"),
+                                        _dev_ptr(out, "out", True), N, C, H, W, K, R, S, stride, pad,
+                                        1 if relu else 0, _stream_handle(stream), int(variant)),
+           "conv_fwd_f16_packed_ex")
+    return out
 
 
 def conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, variant):

@@ -873,6 +873,51 @@ size_t conv_fwd_f16_workspace_bytes(int N, int C, int H, int W, int K, int R, in
   return need;
 }
 
+// ---- filter pre-packing for the fp16-matrix-core tiles (weights are constant in deployment)
+// The tile a (shape, variant_id) pair means for the packed calls, or -1.
+static int packed_tile(const Shape& s, int variant_id) {
+  if (images_per_launch(s) < s.N) return -1;            // one launch only
+  const int id = variant_id < 0 ? select_variant_f16(s, true, true) : variant_id;
+  const int h = hconv_index(id);
+  return (h >= 0 && hconv_applicable(h, s)) ? h : -1;
+}
+
+size_t conv_f16_packed_filter_bytes(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                    int variant_id) {
+  Shape s;
+  if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
+  const int h = packed_tile(s, variant_id);
+  return h < 0 ? 0 : hconv_workspace_bytes(h, s);
+}
+
+int conv_f16_pack_filters(const void* filt, void* packed, size_t packed_bytes, int N, int C, int H, int W,
+                          int K, int R, int S, int stride, int pad, void* hip_stream, int variant_id) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (!filt || !packed) return BCONV_ENULL;
+  if (((reinterpret_cast<uintptr_t>(filt) & 1u) | (reinterpret_cast<uintptr_t>(packed) & 15u)) != 0) return BCONV_EINVAL;
+  const int h = packed_tile(s, variant_id);
+  if (h < 0) return BCONV_EVARIANT;
+  if (packed_bytes < hconv_workspace_bytes(h, s)) return BCONV_EWORKSPACE;
+  return launch_hconv_pack(h, filt, packed, s, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? BCONV_OK
+                                                                                                  : BCONV_ELAUNCH;
+}
+
+int conv_fwd_f16_packed_ex(const void* in, const void* packed, const float* bias, void* out, int N, int C,
+                           int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                           void* hip_stream, int variant_id) {
+  Shape s;
+  int rc = check_conv_args(in, packed, out, N, C, H, W, K, R, S, stride, pad, relu, 2, &s);
+  if (rc != BCONV_OK) return rc;
+  if ((reinterpret_cast<uintptr_t>(packed) & 15u) != 0) return BCONV_EINVAL;
+  const int h = packed_tile(s, variant_id);
+  if (h < 0) return BCONV_EVARIANT;
+  return launch_hconv_packed(h, in, packed, bias, out, s, relu, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
 // C[M x N] = A[M x K] * B[K x N] is the pointwise convolution of one "image" whose
 // N columns are the pixels: filters = rows of A, channels = the reduction index.
 int sgemm_ex(const float* A, const float* B, float* C, int M, int N, int K, void* workspace,

@@ -64,5 +64,8 @@ size_t hconv_workspace_bytes(int which, const Shape& s);
 int hconv_select(const Shape& s);
 hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
                         const Shape& s, int relu, void* ws, hipStream_t st);
+hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st);
+hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
+                               const Shape& s, int relu, hipStream_t st);
 
 }  // namespace bconv

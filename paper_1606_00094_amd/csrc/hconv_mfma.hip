@@ -418,24 +418,37 @@ int hconv_select(const Shape& s) {
   return best;
 }
 
-hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
-                        const Shape& s, int relu, void* ws, hipStream_t st) {
+// The filters re-laid for tile `which` into `packed` (hconv_workspace_bytes bytes).
+hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st) {
   HPlan pl;
   if (!plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
   const HTile& v = kHTiles[which];
   const long long total = (long long)(pl.filt2_bytes / 2);
   long long blocks = (total + 255) / 256;
   if (blocks > 8192) blocks = 8192;
-  hipError_t e = launch_kernel(hconv_repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                               static_cast<const _Float16*>(filt),
-                               static_cast<_Float16*>(ws), s.K, s.C, v.R * v.S, v.CC, pl.hp.nch, total);
-  if (e != hipSuccess) return e;
+  return launch_kernel(hconv_repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const _Float16*>(filt), static_cast<_Float16*>(packed), s.K, s.C,
+                       v.R * v.S, v.CC, pl.hp.nch, total);
+}
+
+// The convolution itself on filters that launch_hconv_pack re-laid for the same tile and shape.
+hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
+                               const Shape& s, int relu, hipStream_t st) {
+  HPlan pl;
+  if (!plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
   pl.hp.g.in = static_cast<const float*>(in);
   pl.hp.g.bias = bias;
   pl.hp.g.out = static_cast<float*>(out);
   pl.hp.g.relu = relu;
-  pl.hp.filt2 = static_cast<const _Float16*>(ws);
+  pl.hp.filt2 = static_cast<const _Float16*>(packed);
   return kHLaunch[which](pl.hp, dim3(pl.gx, pl.gy), pl.lds_bytes, st);
+}
+
+hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
+                        const Shape& s, int relu, void* ws, hipStream_t st) {
+  hipError_t e = launch_hconv_pack(which, filt, ws, s, st);
+  if (e != hipSuccess) return e;
+  return launch_hconv_packed(which, in, ws, bias, out, s, relu, st);
 }
 
 }  // namespace bconv

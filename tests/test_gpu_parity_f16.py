@@ -137,6 +137,43 @@ def test_f16_matrix_core_tiles_through_the_simple_entry_and_errors():
     torch.cuda.synchronize()
 
 
+def test_f16_prepacked_filters_equal_the_per_call_path_bit_for_bit():
+    """Filters re-laid once (conv_f16_pack_filters) and used by conv_fwd_f16_packed_ex on two
+    different inputs: the same bits as conv_fwd_f16_ex with that variant, and the oracle's values.
+    A shape whose choice is not an fp16-matrix-core tile has nothing to pack."""
+    dev = torch.device("cuda:0")
+    for layer, N, variant in ((workloads.CONV3, 16, -1), (workloads.PW_A, 32, -1), (workloads.CONV2, 8, None)):
+        dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+        if variant is None:     # a forced tile that is not the table's choice
+            variant = binding.variant_ids_by_name()["h16k5_64x64_c16/s1"]
+            assert variant != binding.conv_fwd_f16_selected_variant(*dims)
+        nbytes = binding.conv_f16_packed_filter_bytes(*dims, variant)
+        assert nbytes > 0 and nbytes == binding.conv_fwd_f16_workspace_bytes(
+            *dims, variant if variant >= 0 else binding.conv_fwd_f16_selected_variant(*dims))
+        x, f, b, s, p = _layer_case(layer, N)
+        fd, bd = torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev)
+        packed = torch.full(((nbytes + 3) // 4,), float("nan"), dtype=torch.float32, device=dev)
+        binding.conv_f16_pack_filters(fd, packed, N, layer.H, layer.W, s, p, variant=variant)
+        P, Q = binding.conv_out_dims(layer.H, layer.W, layer.R, layer.S, s, p)
+        for rep in range(2):
+            xr = x if rep == 0 else np.ascontiguousarray(x[::-1])
+            xd = torch.from_numpy(xr).to(dev)
+            got = torch.full((N, layer.K, P, Q), float("nan"), dtype=torch.float16, device=dev)
+            binding.conv_fwd_f16_packed_ex(xd, packed, f.shape, bd, got, s, p, True, variant=variant)
+            torch.cuda.synchronize()
+            want = gpu_conv_f16(xr, f, b, s, p, True, variant=variant)
+            assert np.array_equal(got.cpu().numpy(), want), (layer.name, rep)
+            if rep == 0:
+                assert_close_f16(want, oracle.conv_fwd_f16(xr, f, b, stride=s, pad=p, relu=True), layer.name)
+        with pytest.raises(binding.BconvError) as e:       # too small a buffer for the packed copy
+            binding.conv_f16_pack_filters(fd, packed[:8], N, layer.H, layer.W, s, p, variant=variant)
+        assert e.value.status == -4
+    layer = workloads.CONV1
+    dims = (4, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+    assert binding.conv_f16_packed_filter_bytes(*dims, -1) == 0
+    torch.cuda.synchronize()
+
+
 # (the vector-FMA first-layer kernels are fp32-storage only)
 @pytest.mark.parametrize("tile", sorted(t for t in _tile_families() if not t.startswith("fmaq")))
 def test_f16_every_tile_variant_exact_on_integers(tile):
