@@ -161,6 +161,36 @@ int conv_fwd_f16_packed_ex(const void* in, const void* packed, const float* bias
                            int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                            int relu, void* hip_stream, int variant_id);
 
+/* Activation layouts of the half-precision matrix-core path.  The paper's Section VI applies a
+ * transformation to the input of its pointwise and tiled variants so that global memory is read
+ * in a good pattern.  Here the input is NCHW or C8 = [N][C/8][H][W][8] -- the
+ * eight consecutive channels 8j .. 8j+7 of a pixel in 16 contiguous bytes, channel count a
+ * multiple of eight, the buffer 16-byte aligned.  C8 is what the fp16-matrix-core tiles stage
+ * and store best (one 16-byte load per eight channels of a position, 8-byte stores), so a chain
+ * of half-precision layers keeps its activations in it and converts at the ends.
+ *   f16_layout_convert: fp16 activations of N x C x H x W elements from in_layout to out_layout
+ *     (device pointers, distinct buffers, enqueued on hip_stream); BCONV_EINVAL unless the two
+ *     layouts differ and C % 8 == 0.
+ *   conv_fwd_f16_packed_layout_ex: conv_fwd_f16_packed_ex with the input in in_layout and the
+ *     output (N x K x P x Q) written in out_layout.  C8 output needs C8 input and K % 8 == 0
+ *     (else BCONV_EINVAL).  With both NCHW it is conv_fwd_f16_packed_ex; with C8 the result is
+ *     the same set of values, element (n, k, p, q) found at its C8 position.
+ *   conv_fwd_f16_c8_selected_variant: the measured (else estimated) best fp16-matrix-core tile
+ *     for this shape on C8 activations, to be passed as variant_id to the packing calls and to
+ *     conv_fwd_f16_packed_layout_ex (their -1 means the choice for NCHW activations, which can
+ *     be a different tile, or none for a small launch); BCONV_EVARIANT when no such tile
+ *     applies (stride > 1, a kernel other than 1x1 / 3x3 / 5x5, C not a multiple of eight). */
+#define BCONV_LAYOUT_NCHW 0
+#define BCONV_LAYOUT_C8 1
+int conv_fwd_f16_c8_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride,
+                                     int pad);
+int f16_layout_convert(const void* in, int in_layout, void* out, int out_layout, int N, int C,
+                       int H, int W, void* hip_stream);
+int conv_fwd_f16_packed_layout_ex(const void* in, int in_layout, const void* packed,
+                                  const float* bias, void* out, int out_layout, int N, int C,
+                                  int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                                  void* hip_stream, int variant_id);
+
 /* Bytes of workspace conv_fwd_ex needs for this shape and variant (0 if none;
  * also 0 for arguments conv_fwd_ex would reject).  For variant_id = -1 the figure
  * covers the table's choice for any pointer alignment (wide loads or their narrow

@@ -29,6 +29,9 @@ EXPORTS = {
     "conv_f16_packed_filter_bytes": ([_i] * 10, _sz),
     "conv_f16_pack_filters": ([_vp, _vp, _sz] + [_i] * 9 + [_vp, _i], _i),
     "conv_fwd_f16_packed_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _i], _i),
+    "conv_fwd_f16_packed_layout_ex": ([_vp, _i, _vp, _vp, _vp, _i] + [_i] * 10 + [_vp, _i], _i),
+    "f16_layout_convert": ([_vp, _i, _vp, _i] + [_i] * 4 + [_vp], _i),
+    "conv_fwd_f16_c8_selected_variant": ([_i] * 9, _i),
     "conv_pool_fwd_ex": ([_vp] * 4 + [_i] * 12 + [_vp, _sz, _vp, _i], _i),
     "conv_pool_fwd_workspace_bytes": ([_i] * 10, _sz),
     "conv_pool_selected_variant": ([_i] * 11, _i),
@@ -323,6 +326,52 @@ def conv_fwd_f16_packed_ex(inp, packed, filt_shape, bias, out, stride, pad, relu
                                         _dev_ptr(out, "out", True), N, C, H, W, K, R, S, stride, pad,
                                         1 if relu else 0, _stream_handle(stream), int(variant)),
            "conv_fwd_f16_packed_ex")
+    return out
+
+
+LAYOUT_NCHW, LAYOUT_C8 = 0, 1
+
+
+def conv_fwd_f16_c8_selected_variant(N, C, H, W, K, R, S, stride, pad):
+    v = int(lib().conv_fwd_f16_c8_selected_variant(N, C, H, W, K, R, S, stride, pad))
+    if v < 0:
+        raise BconvError(v, "conv_fwd_f16_c8_selected_variant")
+    return v
+
+
+def f16_layout_convert(inp, in_layout, out, out_layout, shape, stream=None):
+    """f16_layout_convert of the C ABI; `shape` = (N, C, H, W) of the logical tensor.  A C8 tensor
+    is passed as a tensor of shape (N, C // 8, H, W, 8)."""
+    N, C, H, W = shape
+    for t, lay, nm in ((inp, in_layout, "in"), (out, out_layout, "out")):
+        want = (N, C // 8, H, W, 8) if lay == LAYOUT_C8 else (N, C, H, W)
+        if tuple(t.shape) != want:
+            raise ValueError("%s must have shape %s" % (nm, want))
+    _check(lib().f16_layout_convert(_dev_ptr(inp, "in", True), int(in_layout), _dev_ptr(out, "out", True),
+                                    int(out_layout), N, C, H, W, _stream_handle(stream)), "f16_layout_convert")
+    return out
+
+
+def conv_fwd_f16_packed_layout_ex(inp, in_layout, packed, filt_shape, bias, out, out_layout, in_shape, stride, pad,
+                                  relu, stream=None, variant=-1):
+    """conv_fwd_f16_packed_layout_ex of the C ABI; in_shape = (N, C, H, W) of the logical input,
+    filt_shape = (K, C, R, S); C8 tensors have shape (N, channels // 8, height, width, 8)."""
+    N, C, H, W = in_shape
+    K, C2, R, S = filt_shape
+    if C != C2:
+        raise ValueError("in has %d channels, the filters expect %d" % (C, C2))
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    want_in = (N, C // 8, H, W, 8) if in_layout == LAYOUT_C8 else (N, C, H, W)
+    want_out = (N, K // 8, P, Q, 8) if out_layout == LAYOUT_C8 else (N, K, P, Q)
+    if tuple(inp.shape) != want_in:
+        raise ValueError("in must have shape %s" % (want_in,))
+    if tuple(out.shape) != want_out:
+        raise ValueError("out must have shape %s" % (want_out,))
+    _check(lib().conv_fwd_f16_packed_layout_ex(_dev_ptr(inp, "in", True), int(in_layout), packed.data_ptr(),
+                                               _dev_ptr(bias, "bias"), _dev_ptr(out, "out", True), int(out_layout),
+                                               N, C, H, W, K, R, S, stride, pad, 1 if relu else 0,
+                                               _stream_handle(stream), int(variant)),
+           "conv_fwd_f16_packed_layout_ex")
     return out
 
 

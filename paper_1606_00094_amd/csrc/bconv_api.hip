@@ -145,6 +145,11 @@ static const TableRow kF16Table[] = {
 #include "f16_selection_table.inc"
     {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
 
+// Measured choices among those tiles for octet-interleaved (C8) activations.
+static const TableRow kF16C8Table[] = {
+#include "f16_c8_selection_table.inc"
+    {0, 0, 0, 0, 0, 0, 0, 0, 0, nullptr, 0}};
+
 static int find_variant(const char* tile, int nsplit) {
   for (int f = 0; f < fma_num_variants(); ++f)
     if (nsplit == 1 && std::strcmp(fma_variant_name(f), tile) == 0) return kNumTileVariants + f;
@@ -268,9 +273,11 @@ static int table_lookup(const TableRow* table, const Shape& s, bool filt_aligned
   return -1;
 }
 
-// The half-precision table's fp16-matrix-core tile for this exact shape, or -1.
-static int f16_table_lookup(const Shape& s) {
-  for (const TableRow* r = kF16Table; r->tile; ++r) {
+// A half-precision table's fp16-matrix-core tile for this exact shape, or -1.
+static int f16_rows_lookup(const TableRow* rows, const Shape& s);
+static int f16_table_lookup(const Shape& s) { return f16_rows_lookup(kF16Table, s); }
+static int f16_rows_lookup(const TableRow* rows, const Shape& s) {
+  for (const TableRow* r = rows; r->tile; ++r) {
     if (r->N == s.N && r->C == s.C && r->H == s.H && r->W == s.W && r->K == s.K && r->R == s.R &&
         r->S == s.S && r->stride == s.stride && r->pad == s.pad) {
       const int id = find_variant(r->tile, r->nsplit);
@@ -882,6 +889,17 @@ static int packed_tile(const Shape& s, int variant_id) {
   return (h >= 0 && hconv_applicable(h, s)) ? h : -1;
 }
 
+int conv_fwd_f16_c8_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+  Shape s;
+  int rc = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+  if (rc != BCONV_OK) return rc;
+  if (images_per_launch(s) < s.N) return BCONV_EVARIANT;
+  const int listed = f16_rows_lookup(kF16C8Table, s);
+  if (listed > 0) return listed;
+  const int h = hconv_select(s, true);
+  return h < 0 ? BCONV_EVARIANT : kNumTileVariants + fma_num_variants() + h;
+}
+
 size_t conv_f16_packed_filter_bytes(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                                     int variant_id) {
   Shape s;
@@ -913,7 +931,49 @@ int conv_fwd_f16_packed_ex(const void* in, const void* packed, const float* bias
   if ((reinterpret_cast<uintptr_t>(packed) & 15u) != 0) return BCONV_EINVAL;
   const int h = packed_tile(s, variant_id);
   if (h < 0) return BCONV_EVARIANT;
-  return launch_hconv_packed(h, in, packed, bias, out, s, relu, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+  return launch_hconv_packed(h, in, packed, bias, out, s, relu, 0, 0, static_cast<hipStream_t>(hip_stream)) ==
+                 hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
+int conv_fwd_f16_packed_layout_ex(const void* in, int in_layout, const void* packed, const float* bias, void* out,
+                                  int out_layout, int N, int C, int H, int W, int K, int R, int S, int stride,
+                                  int pad, int relu, void* hip_stream, int variant_id) {
+  Shape s;
+  int rc = check_conv_args(in, packed, out, N, C, H, W, K, R, S, stride, pad, relu, 2, &s);
+  if (rc != BCONV_OK) return rc;
+  if ((in_layout != BCONV_LAYOUT_NCHW && in_layout != BCONV_LAYOUT_C8) ||
+      (out_layout != BCONV_LAYOUT_NCHW && out_layout != BCONV_LAYOUT_C8))
+    return BCONV_EINVAL;
+  // the octet-interleaved output is written by kernels that read the octet-interleaved input
+  if (out_layout == BCONV_LAYOUT_C8 && (in_layout != BCONV_LAYOUT_C8 || K % 8 != 0)) return BCONV_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(packed) & 15u) != 0) return BCONV_EINVAL;
+  if (in_layout == BCONV_LAYOUT_C8 && (reinterpret_cast<uintptr_t>(in) & 15u) != 0) return BCONV_EINVAL;
+  if (out_layout == BCONV_LAYOUT_C8 && (reinterpret_cast<uintptr_t>(out) & 15u) != 0) return BCONV_EINVAL;
+  const int h = packed_tile(s, variant_id);
+  if (h < 0) return BCONV_EVARIANT;
+  return launch_hconv_packed(h, in, packed, bias, out, s, relu, in_layout == BCONV_LAYOUT_C8,
+                             out_layout == BCONV_LAYOUT_C8, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
+int f16_layout_convert(const void* in, int in_layout, void* out, int out_layout, int N, int C, int H, int W,
+                       void* hip_stream) {
+  if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return BCONV_EINVAL;
+  if (!in || !out) return BCONV_ENULL;
+  if (in == out) return BCONV_EINVAL;
+  const bool to_c8 = in_layout == BCONV_LAYOUT_NCHW && out_layout == BCONV_LAYOUT_C8;
+  const bool from_c8 = in_layout == BCONV_LAYOUT_C8 && out_layout == BCONV_LAYOUT_NCHW;
+  if ((!to_c8 && !from_c8) || C % 8 != 0) return BCONV_EINVAL;
+  const void* c8 = to_c8 ? out : in;
+  const void* plain = to_c8 ? in : out;
+  if ((reinterpret_cast<uintptr_t>(c8) & 15u) != 0 || (reinterpret_cast<uintptr_t>(plain) & 1u) != 0)
+    return BCONV_EINVAL;
+  if ((long long)H * W > 0x7fffffffLL) return BCONV_ESHAPE;
+  return launch_f16_layout(in, out, (long long)N * C, H * W, to_c8 ? 1 : 0, static_cast<hipStream_t>(hip_stream)) ==
+                 hipSuccess
              ? BCONV_OK
              : BCONV_ELAUNCH;
 }

@@ -61,11 +61,16 @@ int hconv_num_variants();
 const char* hconv_variant_name(int which);
 bool hconv_applicable(int which, const Shape& s);
 size_t hconv_workspace_bytes(int which, const Shape& s);
-int hconv_select(const Shape& s);
+// (any_size: also for launches too small to fill the chip, where the widening kernel would win
+// on NCHW activations -- the octet-interleaved layout has no other kernel)
+int hconv_select(const Shape& s, bool any_size = false);
 hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
                         const Shape& s, int relu, void* ws, hipStream_t st);
 hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st);
 hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
-                               const Shape& s, int relu, hipStream_t st);
+                               const Shape& s, int relu, int in_c8, int out_c8, hipStream_t st);
+// fp16 activations between NCHW and the octet-interleaved layout [N][C/8][H*W][8]
+// (n_times_c = N * C, a multiple of eight); to_c8 = 1: NCHW -> C8, 0: back.
+hipError_t launch_f16_layout(const void* in, void* out, long long n_times_c, int HW, int to_c8, hipStream_t st);
 
 }  // namespace bconv

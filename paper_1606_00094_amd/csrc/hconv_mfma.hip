@@ -21,11 +21,26 @@
 //     taps are then offsets of the LDS read, uniform over the lanes.
 // Software pipeline: the global loads of chunk i+1 are in flight while chunk i is multiplied
 // out of one LDS buffer, and are written to the other buffer afterwards; one barrier per chunk.
+//
+// Activations come in one of two layouts: NCHW, or "C8" = [N][C/8][H][W][8], eight consecutive
+// channels of a pixel in 16 contiguous bytes.  C8 is the layout the staging wants (one 16-byte
+// load per octet instead of eight 2-byte loads from eight planes) and the one the accumulator
+// layout stores well (8-byte stores instead of 2-byte ones), so layers chained in half
+// precision keep their activations in it.  This file is compiled once per layout pair
+// (HCONV_LAYOUT 0: NCHW in and out; 1: C8 in, NCHW out; 2: C8 in and out); unit 0 also holds
+// the host side.
 #include <atomic>
 #include <cstdint>
 #include <cstring>
 
 #include "bconv_internal.h"
+
+#ifndef HCONV_LAYOUT
+#define HCONV_LAYOUT 0
+#endif
+#ifndef HCONV_PF
+#define HCONV_PF 2
+#endif
 
 namespace bconv {
 
@@ -41,7 +56,7 @@ struct HconvParams {
   int coct;                 // C / 8
 };
 
-template <int R_, int S_, int WM, int WN, int MT, int NT, int CC, int EPB>
+template <int R_, int S_, int WM, int WN, int MT, int NT, int CC, int EPB, bool C8I, bool C8O>
 __global__ __launch_bounds__(WM * WN * 64)
 void hconv_mfma_kernel(const HconvParams hp) {
   constexpr int NTHR = WM * WN * 64;
@@ -96,7 +111,13 @@ void hconv_mfma_kernel(const HconvParams hp) {
     }
     b_oct[i] = item ? o : NOCT;                    // NOCT: no item (never loads, stores nowhere)
     b_lds[i] = item ? o * npos + e : 0;
-    b_voff[i] = ok ? (unsigned)((goff + o * 8 * p.HW) * 2) : kOob;
+    if (C8I) {
+      // octet-interleaved input [N][C/8][H*W][8]: the octet of a position is 16 contiguous bytes
+      const int hw = ok ? (int)((unsigned)goff % (unsigned)p.CHW) : 0;
+      b_voff[i] = ok ? (unsigned)((goff + 7 * hw + o * 8 * p.HW) * 2) : kOob;
+    } else {
+      b_voff[i] = ok ? (unsigned)((goff + o * 8 * p.HW) * 2) : kOob;
+    }
   }
   // ---- filter staging items: 16-byte unit j of filter row m
   unsigned a_voff[NA];
@@ -136,6 +157,18 @@ void hconv_mfma_kernel(const HconvParams hp) {
     }
   }
 
+  if (C8O) {
+    // octet-interleaved output [N][K/8][P*Q][8]: pixel pq of image img starts at
+    // img*K*PQ + pq*8 (+ 8*PQ per octet of filters); this lane's half of an octet follows
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int kpq = p.K * p.PQ;
+      const int img = (int)((unsigned)outoff[nt] / (unsigned)kpq);
+      const int pq = outoff[nt] - img * kpq;
+      outoff[nt] = img * kpq + pq * 8 + gq * 4;
+    }
+  }
+
   hacc_t acc[MT][NT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -145,7 +178,8 @@ void hconv_mfma_kernel(const HconvParams hp) {
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
 
   uquad ra[NA];
-  unsigned short rb[EPB][8];
+  unsigned short rb[C8I ? 1 : EPB][8];
+  uquad rq[C8I ? EPB : 1];
   auto load_chunk = [&](int ch) {
 #pragma unroll
     for (int i = 0; i < NA; ++i)
@@ -154,9 +188,13 @@ void hconv_mfma_kernel(const HconvParams hp) {
     for (int i = 0; i < EPB; ++i) {
       // an octet past the last channel reads nothing (C is a multiple of eight)
       const unsigned voff = (ch * NOCT + b_oct[i] < hp.coct) ? b_voff[i] : kOob;
+      if constexpr (C8I) {
+        rq[i] = __builtin_bit_cast(uquad, __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, voff, ch * CC * p.HW * 2, 0));
+      } else {
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
-        rb[i][u] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_in, voff, (ch * CC + u) * p.HW * 2, 0);
+        for (int u = 0; u < 8; ++u)
+          rb[i][u] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_in, voff, (ch * CC + u) * p.HW * 2, 0);
+      }
     }
   };
   auto store_chunk = [&](int buf) {
@@ -168,34 +206,50 @@ void hconv_mfma_kernel(const HconvParams hp) {
 #pragma unroll
     for (int i = 0; i < EPB; ++i) {
       if (b_oct[i] < NOCT) {
-        uquad v;
+        if constexpr (C8I) {
+          B[b_lds[i]] = rq[i];
+        } else {
+          uquad v;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) v[w] = (unsigned)rb[i][2 * w] | ((unsigned)rb[i][2 * w + 1] << 16);
-        B[b_lds[i]] = v;
+          for (int w = 0; w < 4; ++w) v[w] = (unsigned)rb[i][2 * w] | ((unsigned)rb[i][2 * w + 1] << 16);
+          B[b_lds[i]] = v;
+        }
       }
     }
   };
+  // One chunk out of LDS buffer `buf`.  Operand reads run HCONV_PF steps (a step is one MFMA
+  // depth of one tap) ahead of the MFMAs that use them: the reads of step s+PF are issued, then
+  // the MFMAs of step s, and the scheduler may not move anything across a step boundary, so a
+  // wave's LDS latency hides behind its own MFMAs.  (Measured: two steps ahead 1-5 % over one,
+  // three no better.)
   auto compute_chunk = [&](int buf) {
     const uquad* A = As + buf * abuf;
     const uquad* B = Bs + buf * bbuf;
-#pragma unroll
-    for (int tap = 0; tap < TAPS; ++tap) {
+    constexpr int STEPS = TAPS * NJ;
+    constexpr int PF = HCONV_PF < STEPS ? HCONV_PF : (STEPS > 1 ? STEPS - 1 : 1);   // steps read ahead
+    constexpr int NS = PF + 1;
+    half8 a[NS][MT], b[NS][NT];
+    auto read_step = [&](int s, int slot) {
+      const int tap = s / NJ, jj = s % NJ;
       const int toff = PW ? 0 : (tap / S_) * p.rowst + (tap % S_);
 #pragma unroll
-      for (int jj = 0; jj < NJ; ++jj) {
-        half8 a[MT], b[NT];
+      for (int mt = 0; mt < MT; ++mt)
+        a[slot][mt] = __builtin_bit_cast(half8, A[laneA + mt * 32 * AST + tap * NOCT + 2 * jj]);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          a[mt] = __builtin_bit_cast(half8, A[laneA + mt * 32 * AST + tap * NOCT + 2 * jj]);
+      for (int nt = 0; nt < NT; ++nt)
+        b[slot][nt] = __builtin_bit_cast(half8, B[laneB[nt] + 2 * jj * npos + toff]);
+    };
+#pragma unroll
+    for (int s = 0; s < PF && s < STEPS; ++s) read_step(s, s % NS);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      if (s + PF < STEPS) read_step(s + PF, (s + PF) % NS);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          b[nt] = __builtin_bit_cast(half8, B[laneB[nt] + 2 * jj * npos + toff]);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
-      }
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[s % NS][mt], b[s % NS][nt], acc[mt][nt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -205,6 +259,7 @@ void hconv_mfma_kernel(const HconvParams hp) {
   for (int ch = 0; ch < hp.nch; ++ch) {
     const bool more = ch + 1 < hp.nch;
     if (more) load_chunk(ch + 1);
+    __builtin_amdgcn_sched_barrier(0);   // the loads are in flight before the first operand read
     compute_chunk(ch & 1);
     if (more) store_chunk((ch + 1) & 1);
     __syncthreads();
@@ -212,40 +267,55 @@ void hconv_mfma_kernel(const HconvParams hp) {
 
   // ---- epilogue: bias + optional ReLU, one rounding to fp16, store
   _Float16* const out = reinterpret_cast<_Float16*>(p.out);
+  if constexpr (C8O) {
+    // accumulator registers 4g .. 4g+3 of a lane are four consecutive filters (half an octet)
+    // of one pixel: one 8-byte store; the two lane halves complete the octet, so a wave's
+    // store covers 32 pixels x 16 contiguous bytes.  K is a multiple of eight here.
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
-      if (k < p.K) {
-        const float bv = p.bias ? p.bias[k] : 0.0f;
+      for (int g = 0; g < 4; ++g) {
+        const int k = m0 + (wm * MT + mt) * 32 + g * 8 + gq * 4;
+        if (k < p.K) {
+          float bv[4];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          if (colvalid[nt]) {
-            float v = acc[mt][nt][i] + bv;
-            if (p.relu) v = v > 0.0f ? v : 0.0f;
-            out[outoff[nt] + k * p.PQ] = (_Float16)v;
+          for (int j = 0; j < 4; ++j) bv[j] = p.bias ? p.bias[k + j] : 0.0f;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            if (colvalid[nt]) {
+              half4 h;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                float v = acc[mt][nt][4 * g + j] + bv[j];
+                if (p.relu) v = v > 0.0f ? v : 0.0f;
+                h[j] = (_Float16)v;
+              }
+              *reinterpret_cast<half4*>(out + outoff[nt] + (k - gq * 4) * p.PQ) = h;
+            }
           }
         }
       }
     }
-  }
-}
-
-// filt KCRS (fp16) -> [K][nch][R*S][CC], zeros for channels past C
-__global__ __launch_bounds__(256)
-void hconv_repack_kernel(const _Float16* __restrict__ filt, _Float16* __restrict__ filt2, int K, int C,
-                         int taps, int CC, int nch, long long total) {
-  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-       idx += (long long)gridDim.x * blockDim.x) {
-    const int cc = (int)(idx % CC);
-    long long r = idx / CC;
-    const int tap = (int)(r % taps);
-    r /= taps;
-    const int ch = (int)(r % nch);
-    const int k = (int)(r / nch);
-    const int c = ch * CC + cc;
-    filt2[idx] = c < C ? filt[((long long)k * C + c) * taps + tap] : (_Float16)0.0f;
+  } else {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
+        if (k < p.K) {
+          const float bv = p.bias ? p.bias[k] : 0.0f;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            if (colvalid[nt]) {
+              float v = acc[mt][nt][i] + bv;
+              if (p.relu) v = v > 0.0f ? v : 0.0f;
+              out[outoff[nt] + k * p.PQ] = (_Float16)v;
+            }
+          }
+        }
+      }
+    }
   }
 }
 
@@ -276,16 +346,17 @@ struct HTile {
   X(h16k3_64x64_c32, 3, 3, 2, 2, 1, 1, 32, 4)   \
   X(h16pw_32x128_c64, 1, 1, 1, 4, 1, 1, 64, 4)  \
   X(h16pw_32x64_c64, 1, 1, 1, 2, 1, 1, 64, 4)   \
-  X(h16pw_64x32_c64, 1, 1, 2, 1, 1, 1, 64, 2)
-
-static const HTile kHTiles[] = {
-#define X(name, R, S, WM, WN, MT, NT, CC, EPB) {#name, R, S, WM, WN, MT, NT, CC, EPB},
-    HCONV_TILES(X)
-#undef X
-};
-constexpr int kNumHTiles = (int)(sizeof(kHTiles) / sizeof(kHTiles[0]));
+  X(h16pw_64x32_c64, 1, 1, 2, 1, 1, 1, 64, 2)   \
+  X(h16k3_128x256_c16, 3, 3, 2, 4, 2, 2, 16, 3) \
+  X(h16pw_128x256_c32, 1, 1, 2, 4, 2, 2, 32, 2) \
+  X(h16k5_64x256_c16, 5, 5, 2, 4, 1, 2, 16, 3)
 
 typedef hipError_t (*HLaunchFn)(const HconvParams&, dim3, size_t, hipStream_t);
+// One launch table per layout pair, each held by its own translation unit.
+HLaunchFn hconv_launch_l0(int which);
+HLaunchFn hconv_launch_l1(int which);
+HLaunchFn hconv_launch_l2(int which);
+
 // (dynamic LDS above the default limit must be allowed per kernel and device; the largest
 // request so far is remembered, host threads may race on it harmlessly)
 template <typename KernelT>
@@ -303,18 +374,105 @@ static hipError_t launch_h(KernelT kernel, int nthr, const HconvParams& hp, dim3
   }
   return launch_kernel(kernel, grid, dim3(nthr), lds, st, hp);
 }
+#if HCONV_LAYOUT == 0
+#define HCONV_TABLE hconv_launch_l0
+#define HCONV_C8I false
+#define HCONV_C8O false
+#elif HCONV_LAYOUT == 1
+#define HCONV_TABLE hconv_launch_l1
+#define HCONV_C8I true
+#define HCONV_C8O false
+#else
+#define HCONV_TABLE hconv_launch_l2
+#define HCONV_C8I true
+#define HCONV_C8O true
+#endif
 #define X(name, R, S, WM, WN, MT, NT, CC, EPB)                                                        \
   static hipError_t hlaunch_##name(const HconvParams& hp, dim3 grid, size_t lds, hipStream_t st) {    \
     static std::atomic<size_t> allowed[64];                                                           \
-    return launch_h(hconv_mfma_kernel<R, S, WM, WN, MT, NT, CC, EPB>, WM * WN * 64, hp, grid, lds, st, allowed); \
+    return launch_h(hconv_mfma_kernel<R, S, WM, WN, MT, NT, CC, EPB, HCONV_C8I, HCONV_C8O>, WM * WN * 64, hp, grid, \
+                    lds, st, allowed);                                                                \
   }
 HCONV_TILES(X)
 #undef X
-static const HLaunchFn kHLaunch[] = {
+HLaunchFn HCONV_TABLE(int which) {
+  static const HLaunchFn table[] = {
 #define X(name, R, S, WM, WN, MT, NT, CC, EPB) hlaunch_##name,
+      HCONV_TILES(X)
+#undef X
+  };
+  return table[which];
+}
+
+#if HCONV_LAYOUT == 0
+// filt KCRS (fp16) -> [K][nch][R*S][CC], zeros for channels past C
+__global__ __launch_bounds__(256)
+void hconv_repack_kernel(const _Float16* __restrict__ filt, _Float16* __restrict__ filt2, int K, int C,
+                         int taps, int CC, int nch, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int cc = (int)(idx % CC);
+    long long r = idx / CC;
+    const int tap = (int)(r % taps);
+    r /= taps;
+    const int ch = (int)(r % nch);
+    const int k = (int)(r / nch);
+    const int c = ch * CC + cc;
+    filt2[idx] = c < C ? filt[((long long)k * C + c) * taps + tap] : (_Float16)0.0f;
+  }
+}
+
+// NCHW -> C8: one thread per (image, octet, pixel) gathers eight planes and writes 16 bytes
+__global__ __launch_bounds__(256)
+void f16_nchw_to_c8_kernel(const _Float16* __restrict__ in, uquad* __restrict__ out, int HW, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const long long no = idx / HW;                 // image * C/8 + octet
+    const int hw = (int)(idx - no * HW);
+    const unsigned short* src = reinterpret_cast<const unsigned short*>(in) + no * 8 * HW + hw;
+    uquad v;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      v[w] = (unsigned)src[(size_t)(2 * w) * HW] | ((unsigned)src[(size_t)(2 * w + 1) * HW] << 16);
+    out[idx] = v;
+  }
+}
+
+// C8 -> NCHW
+__global__ __launch_bounds__(256)
+void f16_c8_to_nchw_kernel(const uquad* __restrict__ in, _Float16* __restrict__ out, int HW, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const long long no = idx / HW;
+    const int hw = (int)(idx - no * HW);
+    const uquad v = in[idx];
+    unsigned short* dst = reinterpret_cast<unsigned short*>(out) + no * 8 * HW + hw;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      dst[(size_t)(2 * w) * HW] = (unsigned short)(v[w] & 0xffffu);
+      dst[(size_t)(2 * w + 1) * HW] = (unsigned short)(v[w] >> 16);
+    }
+  }
+}
+
+hipError_t launch_f16_layout(const void* in, void* out, long long n_times_c, int HW, int to_c8, hipStream_t st) {
+  const long long total = n_times_c / 8 * HW;
+  if (total == 0) return hipSuccess;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (to_c8)
+    return launch_kernel(f16_nchw_to_c8_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                         static_cast<const _Float16*>(in), static_cast<uquad*>(out), HW, total);
+  return launch_kernel(f16_c8_to_nchw_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uquad*>(in), static_cast<_Float16*>(out), HW, total);
+}
+
+static const HTile kHTiles[] = {
+#define X(name, R, S, WM, WN, MT, NT, CC, EPB) {#name, R, S, WM, WN, MT, NT, CC, EPB},
     HCONV_TILES(X)
 #undef X
 };
+constexpr int kNumHTiles = (int)(sizeof(kHTiles) / sizeof(kHTiles[0]));
 
 int hconv_num_variants() { return kNumHTiles; }
 const char* hconv_variant_name(int which) { return kHTiles[which].name; }
@@ -398,8 +556,8 @@ size_t hconv_workspace_bytes(int which, const Shape& s) {
 // with a deep software pipeline, so the small tiles win wherever the sweep looked (64x64 for
 // 3x3 and pointwise, 32x128 for 5x5): the workgroups of the busiest compute unit, run
 // `resident` at a time, each costing its tile's work plus a per-workgroup overhead.
-int hconv_select(const Shape& s) {
-  if ((long long)s.N * s.P * s.Q < 1024) return -1;
+int hconv_select(const Shape& s, bool any_size) {
+  if (!any_size && (long long)s.N * s.P * s.Q < 1024) return -1;
   int best = -1;
   double best_cost = 0.0;
   for (int w = 0; w < kNumHTiles; ++w) {
@@ -431,24 +589,30 @@ hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Sh
                        v.R * v.S, v.CC, pl.hp.nch, total);
 }
 
-// The convolution itself on filters that launch_hconv_pack re-laid for the same tile and shape.
+// The convolution itself on filters that launch_hconv_pack re-laid for the same tile and shape;
+// in_c8 / out_c8 say which activations are octet-interleaved (C8 out needs K % 8 == 0; NCHW in
+// with C8 out is not built).
 hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
-                               const Shape& s, int relu, hipStream_t st) {
+                               const Shape& s, int relu, int in_c8, int out_c8, hipStream_t st) {
   HPlan pl;
   if (!plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
+  if (out_c8 && (!in_c8 || s.K % 8 != 0)) return hipErrorInvalidValue;
   pl.hp.g.in = static_cast<const float*>(in);
   pl.hp.g.bias = bias;
   pl.hp.g.out = static_cast<float*>(out);
   pl.hp.g.relu = relu;
   pl.hp.filt2 = static_cast<const _Float16*>(packed);
-  return kHLaunch[which](pl.hp, dim3(pl.gx, pl.gy), pl.lds_bytes, st);
+  const HLaunchFn fn = out_c8 ? hconv_launch_l2(which) : (in_c8 ? hconv_launch_l1(which) : hconv_launch_l0(which));
+  return fn(pl.hp, dim3(pl.gx, pl.gy), pl.lds_bytes, st);
 }
 
 hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
                         const Shape& s, int relu, void* ws, hipStream_t st) {
   hipError_t e = launch_hconv_pack(which, filt, ws, s, st);
   if (e != hipSuccess) return e;
-  return launch_hconv_packed(which, in, ws, bias, out, s, relu, st);
+  return launch_hconv_packed(which, in, ws, bias, out, s, relu, 0, 0, st);
 }
+
+#endif  // HCONV_LAYOUT == 0
 
 }  // namespace bconv

@@ -204,6 +204,79 @@ def main_f16(args, batches, names):
     return 0
 
 
+def sweep_layer_f16_c8(layer, N):
+    """Octet-interleaved activations, filters packed beforehand: every fp16-matrix-core tile that
+    applies, timed through conv_fwd_f16_packed_layout_ex (C8 out where K allows it) and checked
+    against the NCHW path of the same tile, which it must equal bit for bit."""
+    dev = torch.device("cuda:0")
+    x, f, b = workloads.make_layer_inputs(layer, N)
+    xd, fd = torch.from_numpy(x).to(dev).half(), torch.from_numpy(f).to(dev).half()
+    bd = None if b is None else torch.from_numpy(b).to(dev)
+    C, K, H, W = layer.C, layer.K, layer.H, layer.W
+    dims = (N, C, H, W, K, layer.R, layer.S, layer.stride, layer.pad)
+    P, Q = binding.conv_out_dims(H, W, layer.R, layer.S, layer.stride, layer.pad)
+    rows = []
+    if C % 8:
+        return rows
+    c8_out = K % 8 == 0
+    ref = torch.empty((N, K, P, Q), dtype=torch.float16, device=dev)
+    back = torch.empty_like(ref)
+    x8 = torch.empty((N, C // 8, H, W, 8), dtype=torch.float16, device=dev)
+    o8 = torch.empty((N, K // 8, P, Q, 8), dtype=torch.float16, device=dev) if c8_out else back
+    binding.f16_layout_convert(xd, binding.LAYOUT_NCHW, x8, binding.LAYOUT_C8, (N, C, H, W))
+    olay = binding.LAYOUT_C8 if c8_out else binding.LAYOUT_NCHW
+    flops = roofline.conv_flops(*dims)
+    for v in range(1, binding.conv_num_variants()):
+        if not binding.conv_variant_name(v).startswith("h16"):
+            continue
+        nbytes = binding.conv_f16_packed_filter_bytes(*dims, v)
+        if nbytes == 0:
+            continue
+        packed = torch.empty(nbytes // 2, dtype=torch.float16, device=dev)
+        binding.conv_f16_pack_filters(fd, packed, N, H, W, layer.stride, layer.pad, variant=v)
+        binding.conv_fwd_f16_packed_ex(xd, packed, fd.shape, bd, ref, layer.stride, layer.pad, True, variant=v)
+
+        def run():
+            binding.conv_fwd_f16_packed_layout_ex(x8, binding.LAYOUT_C8, packed, fd.shape, bd, o8, olay,
+                                                  (N, C, H, W), layer.stride, layer.pad, True, variant=v)
+        us = graph_time_us(run, best=True)
+        if c8_out:
+            binding.f16_layout_convert(o8, binding.LAYOUT_C8, back, binding.LAYOUT_NCHW, (N, K, P, Q))
+        rows.append({"variant": binding.conv_variant_name(v), "us": round(us, 2),
+                     "tflops": round(flops / us / 1e6, 2), "ok": bool(torch.equal(back, ref))})
+        del packed
+    rows.sort(key=lambda r: r["us"])
+    return rows
+
+
+def main_f16_c8(args, batches, names):
+    """--f16-c8: rows for f16_c8_selection_table.inc, the best tile per (layer, batch)."""
+    layers = [l for l in workloads.ALL_LAYERS + workloads.EXTRA_LAYERS if (l.name in names if names else l in workloads.ALL_LAYERS)]
+    results, table = [], []
+    for layer in layers:
+        for N in batches:
+            rows = sweep_layer_f16_c8(layer, N)
+            good = [r for r in rows if r["ok"]]
+            best = good[0] if good else None
+            results.append({"layer": layer.name, "N": N, "best": best, "all": rows})
+            print("%-18s N=%-3d C8 best %-22s %8.2f us %7.1f TFLOP/s (%d candidates, %d failed)"
+                  % (layer.name, N, best["variant"] if best else "-", best["us"] if best else 0,
+                     best["tflops"] if best else 0, len(rows), len(rows) - len(good)), flush=True)
+            if best:
+                tile, split = best["variant"].split("/s")
+                table.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, "%s", %s},  // %s N=%d: %.1f us'
+                             % (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride,
+                                layer.pad, tile, split, layer.name, N, best["us"]))
+    with open(args.out, "w") as fh:
+        json.dump(results, fh, indent=1)
+    with open(args.table, "w") as fh:
+        fh.write("// Tile choices for half-precision layers on octet-interleaved (C8) activations, written by the\n"
+                 "// offline tuning sweep (paper_1606_00094_amd/tune.py --f16-c8).\n"
+                 "// Row: {N, C, H, W, K, R, S, stride, pad, \"tile\", nsplit},\n")
+        fh.write("\n".join(table) + ("\n" if table else ""))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="tune.json")
@@ -217,6 +290,8 @@ def main():
                     help="sweep the convolution + pooling call instead (rows for pool_selection_table.inc)")
     ap.add_argument("--f16", action="store_true",
                     help="sweep the half-precision entry points' fp16-matrix-core tiles (rows for f16_selection_table.inc)")
+    ap.add_argument("--f16-c8", action="store_true",
+                    help="sweep those tiles on octet-interleaved activations (rows for f16_c8_selection_table.inc)")
     ap.add_argument("--max-split", type=int, default=0, help="largest reduction split to try (0: by batch)")
     ap.add_argument("--only", default="",
                     help="regular expression: sweep only the variants whose name matches, against "
@@ -226,6 +301,8 @@ def main():
     names = [t for t in args.layers.split(",") if t]
     if args.pool:
         return main_pooled(args, batches, names)
+    if args.f16_c8:
+        return main_f16_c8(args, batches, names)
     if args.f16:
         return main_f16(args, batches, names)
     # the square matrix products (batch 1 only) are swept when named, or with --sgemm

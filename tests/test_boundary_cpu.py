@@ -17,7 +17,7 @@ def _declared_functions():
     text = open(os.path.join(ROOT, "include", "bconv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
-    return sorted(set(n for n in names if n.startswith(("conv_", "bconv_", "maxpool_", "sgemm"))))
+    return sorted(set(n for n in names if n.startswith(("conv_", "bconv_", "maxpool_", "sgemm", "f16_"))))
 
 
 def test_library_loads_and_exports_every_declared_symbol():

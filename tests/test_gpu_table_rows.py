@@ -1,4 +1,4 @@
-"""Every row of the two selection tables on the GPU, through variant -1.
+"""Every row of the selection tables on the GPU, through variant -1.
 
 A row names the tile and reduction split measured best for one exact (layer, batch) shape.
 For each row the library must (a) pick exactly that variant when asked to choose and
@@ -92,6 +92,23 @@ def test_f16_selection_table_row(row):
     ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=True)
     got = gpu_conv_f16(x, f, b, stride, pad, True)
     assert_close_f16(got, ref, "%s via %s" % (_row_id(row), chosen))
+
+
+@pytest.mark.parametrize("row", table_rows("f16_c8_selection_table.inc"), ids=_row_id)
+def test_f16_c8_selection_table_row(row):
+    """Rows of the table for octet-interleaved activations: the query returns the row's tile, and
+    that tile on C8 input (C8 output where K allows) gives the oracle's values, every image."""
+    from tests.test_gpu_parity_f16_c8 import gpu_conv_c8
+    dims, tile, nsplit = row[:9], row[9], row[10]
+    N, C, H, W, K, R, S, stride, pad = dims
+    v = binding.conv_fwd_f16_c8_selected_variant(*dims)
+    assert binding.conv_variant_name(v) == "%s/s%d" % (tile, nsplit)
+    layer = _layer_of(dims)
+    x, f, b = workloads.make_layer_inputs(layer, N, seed=workloads.BASE_SEED + 700000 + sum(dims))
+    x, f = x.astype(np.float16), f.astype(np.float16)
+    ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=True)
+    got = gpu_conv_c8(x, f, b, stride, pad, True, v, K % 8 == 0)
+    assert_close_f16(got, ref, "%s via %s on C8" % (_row_id(row), tile))
 
 
 def test_rows_cover_the_batch_points():
