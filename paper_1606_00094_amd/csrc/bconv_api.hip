@@ -633,6 +633,37 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
       }
     }
   }
+  // Filter reads.  A staged item is AV consecutive words of one filter row, at the chunk's
+  // column offset col0 = chunk * KR * S plus the item's column j.  Only the last chunk can
+  // reach past the end of its row (every earlier one ends at or before (nchunks-1)*KR*S <
+  // C*R*S); there a word past the row's end comes from the next filter row, or, in the last
+  // row, from beyond the tensor, where the kernel relies on the buffer range check (which
+  // covers per-lane plus scalar offset) to return zero.  Either way the kernel zeroes the
+  // item in LDS afterwards, which it decides per item from col0 + j >= C*R*S: so every word
+  // past the row's end must belong to an item that starts past it, and the byte offset of a
+  // read beyond the tensor must not wrap around 2^32 back into it.
+  {
+    const int SP = v.S ? v.S : kSmaxGeneric;
+    const int agrp = v.KR * SP / v.AV;
+    const int krs = v.KR * p.S;
+    const long long col0 = (long long)(p.nchunks - 1) * v.KR * p.S;
+    const long long filt_words = (long long)p.K * p.CRS;
+    for (unsigned by = 0; by < pl.gy; ++by) {
+      for (int m = 0; m < BM && (long long)by * BM + m < p.K; ++m) {
+        const long long row = ((long long)by * BM + m) * p.CRS;
+        for (int g = 0; g < agrp; ++g) {
+          const int j = g * v.AV;
+          if (!v.S && j >= krs) continue;
+          for (int u = 0; u < v.AV; ++u) {
+            const long long w = col0 + j + u;
+            if (w < p.CRS) continue;
+            if (col0 + j < p.CRS) ++bad;                                   // straddles the row's end: not zeroed
+            if (row + w >= filt_words && (row + w + 1) * 4 > (1LL << 32)) ++bad;    // would wrap into the tensor
+          }
+        }
+      }
+    }
+  }
   for (unsigned by = 0; by < pl.gy; ++by) {
     int m0 = (int)by * BM;
     if (m0 >= p.K) ++bad;
