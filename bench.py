@@ -235,6 +235,90 @@ def run_stack(N, reps):
             "frac_mfma": round(flops / (ms * 1e-3) / 1e12 / roofline.PEAK_FP32_MFMA_TFLOPS, 4)}
 
 
+class F16Stack:
+    """The five-layer stack with half-precision storage, laid out for the fp16 matrix cores: the
+    first layer (three channels) runs NCHW on the widening kernel and is pooled there; its output
+    is converted once to the octet-interleaved layout, in which the other four layers and the
+    second pooling run, filters packed beforehand.  step() enqueues the whole chain."""
+
+    def __init__(self, N, img, params):
+        import torch
+        import workloads
+        from paper_1606_00094_amd import binding, roofline
+        B = binding
+        dev = torch.device("cuda:0")
+        self.N, self.flops = N, 0
+        half = lambda a: torch.from_numpy(a).to(dev).half()
+        self.x = half(img)
+        self.ops, self.acts = [], []     # acts: (tensor, layout, logical shape) after each conv (+ pool)
+        cur, cur_shape, lay = self.x, tuple(img.shape), B.LAYOUT_NCHW
+        for li, (layer, (f, b)) in enumerate(zip(workloads.STACK, params)):
+            n, c, h, w = cur_shape
+            dims = (n, c, h, w, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+            P, Q = B.conv_out_dims(h, w, layer.R, layer.S, layer.stride, layer.pad)
+            self.flops += roofline.conv_flops(*dims)
+            fd, bd = half(f), torch.from_numpy(b).to(dev)
+            oshape = (n, layer.K, P, Q)
+            if lay == B.LAYOUT_NCHW:     # first layer
+                v = B.conv_fwd_f16_selected_variant(*dims)
+                need = B.conv_fwd_f16_workspace_bytes(*dims, v)
+                ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
+                out = torch.empty(oshape, dtype=torch.float16, device=dev)
+                self.ops.append(lambda cur=cur, fd=fd, bd=bd, out=out, l=layer, ws=ws, v=v:
+                                B.conv_fwd_f16_ex(cur, fd, bd, out, l.stride, l.pad, True, workspace=ws, variant=v))
+            else:
+                v = B.conv_fwd_f16_c8_selected_variant(*dims)
+                pk = torch.empty(B.conv_f16_packed_filter_bytes(*dims, v) // 2, dtype=torch.float16, device=dev)
+                B.conv_f16_pack_filters(fd, pk, n, h, w, layer.stride, layer.pad, variant=v)
+                out = torch.empty((n, layer.K // 8, P, Q, 8), dtype=torch.float16, device=dev)
+                self.ops.append(lambda cur=cur, pk=pk, fs=tuple(fd.shape), bd=bd, out=out, l=layer, v=v,
+                                shp=cur_shape:
+                                B.conv_fwd_f16_packed_layout_ex(cur, B.LAYOUT_C8, pk, fs, bd, out, B.LAYOUT_C8, shp,
+                                                                l.stride, l.pad, True, variant=v))
+            cur, cur_shape = out, oshape
+            if li in workloads.STACK_POOL_AFTER:
+                PP, PQ = B.conv_out_dims(P, Q, 3, 3, 2, 0)
+                pshape = (n, layer.K, PP, PQ)
+                pout = torch.empty(pshape if lay == B.LAYOUT_NCHW else (n, layer.K // 8, PP, PQ, 8),
+                                   dtype=torch.float16, device=dev)
+                self.ops.append(lambda cur=cur, pout=pout, lay=lay, shp=cur_shape:
+                                B.maxpool_fwd_f16(cur, pout, lay, shp, 3, 2))
+                cur, cur_shape = pout, pshape
+            if lay == B.LAYOUT_NCHW:     # into the layout the rest of the chain keeps
+                c8 = torch.empty((cur_shape[0], cur_shape[1] // 8) + cur_shape[2:] + (8,), dtype=torch.float16,
+                                 device=dev)
+                self.ops.append(lambda cur=cur, c8=c8, shp=cur_shape:
+                                B.f16_layout_convert(cur, B.LAYOUT_NCHW, c8, B.LAYOUT_C8, shp))
+                cur, lay = c8, B.LAYOUT_C8
+            self.acts.append((cur, cur_shape))
+        torch.cuda.synchronize()
+
+    def step(self):
+        for op in self.ops:
+            op()
+
+    def activations_nchw(self):
+        """The input and each layer's (pooled) output as NCHW numpy arrays, after step()."""
+        import torch
+        from paper_1606_00094_amd import binding as B
+        outs = [self.x.cpu().numpy()]
+        for t, shape in self.acts:
+            back = torch.empty(shape, dtype=torch.float16, device=t.device)
+            B.f16_layout_convert(t, B.LAYOUT_C8, back, B.LAYOUT_NCHW, shape)
+            torch.cuda.synchronize()
+            outs.append(back.cpu().numpy())
+        return outs
+
+
+def run_stack_f16(N, reps):
+    import workloads
+    from paper_1606_00094_amd import roofline
+    img, params = workloads.make_stack_inputs(N)
+    st = F16Stack(N, img, params)
+    ms = graph_time_us(st.step, launches=reps) * 1e-3
+    return {"N": N, "ms": round(ms, 4), "gflops": round(st.flops / (ms * 1e-3) / 1e9, 1), "kernels": len(st.ops)}
+
+
 def cpu_baseline(layers, N, min_seconds=10.0, max_passes=8):
     """The oracle as it stands, timed on this machine's host cores over whole passes of
     the same layer set at batch N, repeated until about min_seconds of CPU work."""
@@ -397,6 +481,10 @@ def main():
     for row in stack:
         log(json.dumps({"stack": row}))
 
+    stack16 = [] if args.no_layer_table else [run_stack_f16(n, 20) for n in (1, 5, 20, 32)]
+    for row in stack16:
+        log(json.dumps({"stack_f16": row}))
+
     sgemm = [] if args.no_layer_table else [run_sgemm(n) for n in workloads.SGEMM_SIZES]
     for row in sgemm:
         log(json.dumps({"sgemm": row}))
@@ -499,7 +587,7 @@ def main():
                   "frac": round(tf16 / roofline.PEAK_FP16_MFMA_TFLOPS, 4), "layout": lay16,
                   "layer": big["layer"], "N": big["N"], "kernel": kern16, "us_per_launch": us16}
     full = {"layers": table, "layers_batch_%d" % args.big_batch: table_big, "layers_f16_storage": table_f16,
-            "stack": stack, "sgemm": sgemm, "single_launch": single, "measured_peaks": measured}
+            "stack": stack, "stack_f16": stack16, "sgemm": sgemm, "single_launch": single, "measured_peaks": measured}
     log(json.dumps({"tables": full}))
 
     # The one line on stdout: the contract's fields first, the compact per-layer summary, then
@@ -520,6 +608,7 @@ def main():
                               "frac_hbm_b1", "kernel_floor_over_us_b1"],
         "per_layer": per_layer,
         "stack_ms": {str(r["N"]): r["ms"] for r in stack},
+        "stack_f16_ms": {str(r["N"]): r["ms"] for r in stack16},
         "measured_peaks": measured,
         "per_layer_f16_columns": ["us_b%d" % args.batch, "tflops", "us_filters_prepacked", "us_c8_activations"], "per_layer_f16": per_layer_f16,
         "roofline_f16": roof16,

@@ -280,6 +280,13 @@ int bconv_debug_mfma_loop(float* out, int workgroups, int iters, void* hip_strea
 int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz,
                 int stride, void* hip_stream);
 
+/* maxpool_fwd for fp16 activations in `layout` (BCONV_LAYOUT_NCHW, or BCONV_LAYOUT_C8 with
+ * C % 8 == 0 and 16-byte aligned buffers), output in the same layout: what a chain of
+ * half-precision layers pools with between convolutions.  A maximum is one of its inputs:
+ * no rounding. */
+int maxpool_fwd_f16(const void* in, void* out, int layout, int N, int C, int H, int W, int ksz,
+                    int stride, void* hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char* bconv_strerror(int status);
 

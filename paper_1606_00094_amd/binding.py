@@ -46,6 +46,7 @@ EXPORTS = {
     "bconv_debug_model_cost": ([_i] * 10, ctypes.c_double),
     "bconv_debug_mfma_loop": ([_vp, _i, _i, _vp], _i),
     "maxpool_fwd": ([_vp] * 2 + [_i] * 6 + [_vp], _i),
+    "maxpool_fwd_f16": ([_vp, _vp] + [_i] * 7 + [_vp], _i),
     "bconv_strerror": ([_i], ctypes.c_char_p),
 }
 
@@ -390,6 +391,20 @@ def maxpool_fwd(inp, out, ksz, stride, stream=None):
     N, C, H, W = inp.shape
     _check(lib().maxpool_fwd(_dev_ptr(inp, "in"), _dev_ptr(out, "out"), N, C, H, W, ksz, stride,
                              _stream_handle(stream)), "maxpool_fwd")
+    return out
+
+
+def maxpool_fwd_f16(inp, out, layout, shape, ksz, stride, stream=None):
+    """maxpool_fwd_f16 of the C ABI; `shape` = (N, C, H, W) of the logical input; C8 tensors have
+    shape (N, C // 8, height, width, 8)."""
+    N, C, H, W = shape
+    P, Q = (H - ksz) // stride + 1, (W - ksz) // stride + 1
+    want_in = (N, C // 8, H, W, 8) if layout == LAYOUT_C8 else (N, C, H, W)
+    want_out = (N, C // 8, P, Q, 8) if layout == LAYOUT_C8 else (N, C, P, Q)
+    if tuple(inp.shape) != want_in or tuple(out.shape) != want_out:
+        raise ValueError("in / out must have shapes %s / %s" % (want_in, want_out))
+    _check(lib().maxpool_fwd_f16(_dev_ptr(inp, "in", True), _dev_ptr(out, "out", True), int(layout), N, C, H, W,
+                                 ksz, stride, _stream_handle(stream)), "maxpool_fwd_f16")
     return out
 
 

@@ -1119,6 +1119,23 @@ int maxpool_fwd(const float* in, float* out, int N, int C, int H, int W, int ksz
              : BCONV_ELAUNCH;
 }
 
+int maxpool_fwd_f16(const void* in, void* out, int layout, int N, int C, int H, int W, int ksz, int stride,
+                    void* hip_stream) {
+  if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || ksz <= 0 || stride <= 0) return BCONV_EINVAL;
+  if (layout != BCONV_LAYOUT_NCHW && layout != BCONV_LAYOUT_C8) return BCONV_EINVAL;
+  if (layout == BCONV_LAYOUT_C8 && C % 8 != 0) return BCONV_EINVAL;
+  if (H < ksz || W < ksz) return BCONV_ESHAPE;
+  if ((long long)N * C > 0x7fffffffLL || (long long)H * W > 0x7fffffffLL) return BCONV_ESHAPE;
+  if (!in || !out) return BCONV_ENULL;
+  const uintptr_t mask = layout == BCONV_LAYOUT_C8 ? 15u : 1u;
+  if (((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & mask) != 0) return BCONV_EINVAL;
+  const int P = (H - ksz) / stride + 1, Q = (W - ksz) / stride + 1;
+  return launch_maxpool_f16(in, out, (long long)N * C, H, W, ksz, stride, P, Q, layout == BCONV_LAYOUT_C8,
+                            static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
 int bconv_debug_mfma_loop(float* out, int workgroups, int iters, void* hip_stream) {
   if (!out) return BCONV_ENULL;
   if (workgroups <= 0 || workgroups > 65536 || iters <= 0) return BCONV_EINVAL;

@@ -71,6 +71,9 @@ hipError_t launch_hconv_packed(int which, const void* in, const void* packed, co
                                const Shape& s, int relu, int in_c8, int out_c8, hipStream_t st);
 // fp16 activations between NCHW and the octet-interleaved layout [N][C/8][H*W][8]
 // (n_times_c = N * C, a multiple of eight); to_c8 = 1: NCHW -> C8, 0: back.
+// Max pooling of fp16 activations, NCHW (c8 = 0) or octet-interleaved (c8 = 1).
+hipError_t launch_maxpool_f16(const void* in, void* out, long long n_times_c, int H, int W, int ksz, int stride,
+                              int P, int Q, int c8, hipStream_t st);
 hipError_t launch_f16_layout(const void* in, void* out, long long n_times_c, int HW, int to_c8, hipStream_t st);
 
 }  // namespace bconv

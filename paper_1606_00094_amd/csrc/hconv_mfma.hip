@@ -455,6 +455,65 @@ void f16_c8_to_nchw_kernel(const uquad* __restrict__ in, _Float16* __restrict__ 
   }
 }
 
+// Max pooling of fp16 activations (window ksz, step `stride`, no padding, floor extents).
+// C8: one thread per (image, octet, pooled pixel) reads its window as 16-byte octets and keeps
+// the eight running maxima; NCHW: one thread per pooled element.  A maximum of fp16 values is
+// one of them, so there is no rounding.
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(256)
+void maxpool_f16_c8_kernel(const half8v* __restrict__ in, half8v* __restrict__ out, int H, int W, int P, int Q,
+                           int ksz, int stride, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int q = (int)(idx % Q);
+    long long r = idx / Q;
+    const int pp = (int)(r % P);
+    const long long no = r / P;
+    const half8v* src = in + (no * H + (long long)pp * stride) * W + (long long)q * stride;
+    half8v m = src[0];
+    for (int y = 0; y < ksz; ++y)
+      for (int x = 0; x < ksz; ++x) {
+        const half8v v = src[(long long)y * W + x];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m[u] = v[u] > m[u] ? v[u] : m[u];
+      }
+    out[idx] = m;
+  }
+}
+
+__global__ __launch_bounds__(256)
+void maxpool_f16_nchw_kernel(const _Float16* __restrict__ in, _Float16* __restrict__ out, int H, int W, int P,
+                             int Q, int ksz, int stride, long long total) {
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int q = (int)(idx % Q);
+    long long r = idx / Q;
+    const int pp = (int)(r % P);
+    const long long nc = r / P;
+    const _Float16* src = in + (nc * H + (long long)pp * stride) * W + (long long)q * stride;
+    _Float16 m = src[0];
+    for (int y = 0; y < ksz; ++y)
+      for (int x = 0; x < ksz; ++x) {
+        const _Float16 v = src[(long long)y * W + x];
+        m = v > m ? v : m;
+      }
+    out[idx] = m;
+  }
+}
+
+hipError_t launch_maxpool_f16(const void* in, void* out, long long n_times_c, int H, int W, int ksz, int stride,
+                              int P, int Q, int c8, hipStream_t st) {
+  const long long total = (c8 ? n_times_c / 8 : n_times_c) * P * Q;
+  if (total == 0) return hipSuccess;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (c8)
+    return launch_kernel(maxpool_f16_c8_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                         static_cast<const half8v*>(in), static_cast<half8v*>(out), H, W, P, Q, ksz, stride, total);
+  return launch_kernel(maxpool_f16_nchw_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const _Float16*>(in), static_cast<_Float16*>(out), H, W, P, Q, ksz, stride, total);
+}
+
 hipError_t launch_f16_layout(const void* in, void* out, long long n_times_c, int HW, int to_c8, hipStream_t st) {
   const long long total = n_times_c / 8 * HW;
   if (total == 0) return hipSuccess;

@@ -171,6 +171,57 @@ def test_c8_chain_of_two_layers_stays_in_c8():
     assert ref.shape == ref_on_gpu_mid.shape
 
 
+@pytest.mark.parametrize("layout", [NCHW, C8])
+def test_maxpool_f16_both_layouts(layout):
+    """Pooling of fp16 activations: bit for bit the oracle's pooling (a maximum is one of its
+    inputs), windows 3/2, 2/2 and 3/1, negative values, ragged extents."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(workloads.BASE_SEED + 88 + layout)
+    for shape, ksz, stride in (((2, 16, 13, 13), 3, 2), ((1, 96, 55, 55), 3, 2), ((3, 8, 8, 9), 2, 2),
+                               ((2, 24, 7, 5), 3, 1), ((1, 8, 3, 3), 3, 2)):
+        n, c, h, w = shape
+        a = rng.standard_normal(shape).astype(np.float16)
+        ref = oracle.maxpool_fwd(a.astype(np.float32), ksz, stride).astype(np.float16)
+        P, Q = ref.shape[2:]
+        ad = torch.from_numpy(a).to(dev)
+        if layout == C8:
+            a8 = torch.empty((n, c // 8, h, w, 8), dtype=torch.float16, device=dev)
+            binding.f16_layout_convert(ad, NCHW, a8, C8, shape)
+            o8 = torch.full((n, c // 8, P, Q, 8), float("nan"), dtype=torch.float16, device=dev)
+            binding.maxpool_fwd_f16(a8, o8, C8, shape, ksz, stride)
+            out = torch.empty((n, c, P, Q), dtype=torch.float16, device=dev)
+            binding.f16_layout_convert(o8, C8, out, NCHW, (n, c, P, Q))
+        else:
+            out = torch.full((n, c, P, Q), float("nan"), dtype=torch.float16, device=dev)
+            binding.maxpool_fwd_f16(ad, out, NCHW, shape, ksz, stride)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), ref), (shape, ksz, stride)
+    lib = binding.lib()
+    assert lib.maxpool_fwd_f16(ad.data_ptr(), out.data_ptr(), C8, 1, 12, 5, 5, 3, 2, None) == -1
+    assert lib.maxpool_fwd_f16(ad.data_ptr(), out.data_ptr(), NCHW, 1, 8, 2, 2, 3, 2, None) == -3
+    assert lib.maxpool_fwd_f16(None, out.data_ptr(), NCHW, 1, 8, 5, 5, 3, 2, None) == -2
+    assert lib.maxpool_fwd_f16(ad.data_ptr() + 2, out.data_ptr(), C8, 1, 8, 5, 5, 3, 2, None) == -1
+
+
+@pytest.mark.parametrize("N", [1, 5, 32])
+def test_five_layer_stack_in_half_precision_as_the_benchmark_runs_it(N):
+    """The five-layer stack with fp16 storage the way bench.py times it (first layer NCHW, then
+    C8 throughout): every layer against the oracle applied to that layer's actual GPU input,
+    every image, to the half-precision bar."""
+    import bench
+    img, params = workloads.make_stack_inputs(N)
+    st = bench.F16Stack(N, img, params)
+    st.step()
+    torch.cuda.synchronize()
+    acts = st.activations_nchw()
+    for li, (layer, (f, b)) in enumerate(zip(workloads.STACK, params)):
+        ref16 = oracle.conv_fwd_f16(acts[li], f.astype(np.float16), b, stride=layer.stride, pad=layer.pad, relu=True)
+        if li in workloads.STACK_POOL_AFTER:
+            ref16 = oracle.maxpool_fwd(ref16.astype(np.float32), 3, 2).astype(np.float16)
+        assert_close_f16(acts[li + 1], ref16, "f16 stack N=%d %s" % (N, layer.name))
+    assert acts[-1].shape == (N, 256, 13, 13)
+
+
 def test_c8_refusals():
     """C8 output from NCHW input, C8 output with K not a multiple of eight, a misaligned C8
     pointer, an unknown layout: BCONV_EINVAL; a tile that is not an fp16-matrix-core one:
