@@ -237,9 +237,10 @@ def run_stack(N, reps):
 
 class F16Stack:
     """The five-layer stack with half-precision storage, laid out for the fp16 matrix cores: the
-    first layer (three channels) runs NCHW on the widening kernel and is pooled there; its output
-    is converted once to the octet-interleaved layout, in which the other four layers and the
-    second pooling run, filters packed beforehand.  step() enqueues the whole chain."""
+    first layer (three channels, NCHW input) writes the octet-interleaved layout directly when
+    its choice is a first-layer fp16-matrix-core tile (else NCHW, pooled there and converted
+    once); both poolings and the other four layers run in that layout, filters packed beforehand.
+    step() enqueues the whole chain."""
 
     def __init__(self, N, img, params):
         import torch
@@ -259,13 +260,22 @@ class F16Stack:
             self.flops += roofline.conv_flops(*dims)
             fd, bd = half(f), torch.from_numpy(b).to(dev)
             oshape = (n, layer.K, P, Q)
-            if lay == B.LAYOUT_NCHW:     # first layer
+            if lay == B.LAYOUT_NCHW:     # first layer: NCHW in, straight into the layout the chain keeps
                 v = B.conv_fwd_f16_selected_variant(*dims)
                 need = B.conv_fwd_f16_workspace_bytes(*dims, v)
                 ws = torch.zeros(max(1, (need + 3) // 4), dtype=torch.float32, device=dev)
-                out = torch.empty(oshape, dtype=torch.float16, device=dev)
-                self.ops.append(lambda cur=cur, fd=fd, bd=bd, out=out, l=layer, ws=ws, v=v:
-                                B.conv_fwd_f16_ex(cur, fd, bd, out, l.stride, l.pad, True, workspace=ws, variant=v))
+                direct = B.conv_variant_name(v).startswith(("h16k11s4", "h16k7s2")) and layer.K % 8 == 0
+                if direct:
+                    out = torch.empty((n, layer.K // 8, P, Q, 8), dtype=torch.float16, device=dev)
+                    self.ops.append(lambda cur=cur, fd=fd, bd=bd, out=out, l=layer, ws=ws, v=v, shp=cur_shape:
+                                    B.conv_fwd_f16_layout_ex(cur, B.LAYOUT_NCHW, fd, bd, out, B.LAYOUT_C8, shp,
+                                                             l.stride, l.pad, True, ws, variant=v))
+                    lay = B.LAYOUT_C8
+                else:
+                    out = torch.empty(oshape, dtype=torch.float16, device=dev)
+                    self.ops.append(lambda cur=cur, fd=fd, bd=bd, out=out, l=layer, ws=ws, v=v:
+                                    B.conv_fwd_f16_ex(cur, fd, bd, out, l.stride, l.pad, True, workspace=ws,
+                                                      variant=v))
             else:
                 v = B.conv_fwd_f16_c8_selected_variant(*dims)
                 pk = torch.empty(B.conv_f16_packed_filter_bytes(*dims, v) // 2, dtype=torch.float16, device=dev)

@@ -186,6 +186,17 @@ int conv_fwd_f16_c8_selected_variant(int N, int C, int H, int W, int K, int R, i
                                      int pad);
 int f16_layout_convert(const void* in, int in_layout, void* out, int out_layout, int N, int C,
                        int H, int W, void* hip_stream);
+/* conv_fwd_f16_ex with the layouts named per tensor: filters unpacked (re-laid per call into
+ * the workspace, conv_fwd_f16_workspace_bytes(shape, variant_id) bytes, 16-byte aligned).  With
+ * both layouts NCHW it is conv_fwd_f16_ex.  Otherwise the variant must be an fp16-matrix-core
+ * tile (BCONV_EVARIANT if not): C8 input goes to the channel-octet tiles (-1 = the choice of
+ * conv_fwd_f16_c8_selected_variant), NCHW input with C8 output to the first-layer tiles
+ * (C <= 3, 11x11 step 4 or 7x7 step 2: how a chain enters the C8 layout without a conversion
+ * pass; -1 = conv_fwd_f16_selected_variant's choice, which must be such a tile). */
+int conv_fwd_f16_layout_ex(const void* in, int in_layout, const void* filt, const float* bias,
+                           void* out, int out_layout, int N, int C, int H, int W, int K, int R,
+                           int S, int stride, int pad, int relu, void* workspace,
+                           size_t workspace_bytes, void* hip_stream, int variant_id);
 int conv_fwd_f16_packed_layout_ex(const void* in, int in_layout, const void* packed,
                                   const float* bias, void* out, int out_layout, int N, int C,
                                   int H, int W, int K, int R, int S, int stride, int pad, int relu,

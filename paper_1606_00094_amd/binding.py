@@ -30,6 +30,7 @@ EXPORTS = {
     "conv_f16_pack_filters": ([_vp, _vp, _sz] + [_i] * 9 + [_vp, _i], _i),
     "conv_fwd_f16_packed_ex": ([_vp] * 4 + [_i] * 10 + [_vp, _i], _i),
     "conv_fwd_f16_packed_layout_ex": ([_vp, _i, _vp, _vp, _vp, _i] + [_i] * 10 + [_vp, _i], _i),
+    "conv_fwd_f16_layout_ex": ([_vp, _i, _vp, _vp, _vp, _i] + [_i] * 10 + [_vp, _sz, _vp, _i], _i),
     "f16_layout_convert": ([_vp, _i, _vp, _i] + [_i] * 4 + [_vp], _i),
     "conv_fwd_f16_c8_selected_variant": ([_i] * 9, _i),
     "conv_pool_fwd_ex": ([_vp] * 4 + [_i] * 12 + [_vp, _sz, _vp, _i], _i),
@@ -350,6 +351,31 @@ def f16_layout_convert(inp, in_layout, out, out_layout, shape, stream=None):
             raise ValueError("%s must have shape %s" % (nm, want))
     _check(lib().f16_layout_convert(_dev_ptr(inp, "in", True), int(in_layout), _dev_ptr(out, "out", True),
                                     int(out_layout), N, C, H, W, _stream_handle(stream)), "f16_layout_convert")
+    return out
+
+
+def conv_fwd_f16_layout_ex(inp, in_layout, filt, bias, out, out_layout, in_shape, stride, pad, relu, workspace,
+                           stream=None, variant=-1):
+    """conv_fwd_f16_layout_ex of the C ABI; in_shape = (N, C, H, W) of the logical input, `filt`
+    float16 K x C x R x S; C8 tensors have shape (N, channels // 8, height, width, 8)."""
+    N, C, H, W = in_shape
+    K, C2, R, S = filt.shape
+    if C != C2:
+        raise ValueError("in has %d channels, the filters expect %d" % (C, C2))
+    P, Q = conv_out_dims(H, W, R, S, stride, pad)
+    want_in = (N, C // 8, H, W, 8) if in_layout == LAYOUT_C8 else (N, C, H, W)
+    want_out = (N, K // 8, P, Q, 8) if out_layout == LAYOUT_C8 else (N, K, P, Q)
+    if tuple(inp.shape) != want_in:
+        raise ValueError("in must have shape %s" % (want_in,))
+    if tuple(out.shape) != want_out:
+        raise ValueError("out must have shape %s" % (want_out,))
+    _check(lib().conv_fwd_f16_layout_ex(_dev_ptr(inp, "in", True), int(in_layout), _dev_ptr(filt, "filt", True),
+                                        _dev_ptr(bias, "bias"), _dev_ptr(out, "out", True), int(out_layout),
+                                        N, C, H, W, K, R, S, stride, pad, 1 if relu else 0,
+                                        workspace.data_ptr() if workspace is not None else None,
+                                        workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                        _stream_handle(stream), int(variant)),
+           "conv_fwd_f16_layout_ex")
     return out
 
 

@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 def _units():
     units = [("bconv_api.hip", "bconv_api.o", []), ("aux_kernels.hip", "aux_kernels.o", []),
-             ("fma_conv.hip", "fma_conv.o", [])]
+             ("fma_conv.hip", "fma_conv.o", []), ("hconv_first.hip", "hconv_first.o", [])]
     for lay in range(3):   # fp16 matrix-core tiles, one unit per activation-layout pair
         units.append(("hconv_mfma.hip", "hconv_mfma_l%d.o" % lay, ["-DHCONV_LAYOUT=%d" % lay]))
     for g in range(NUM_GROUPS):

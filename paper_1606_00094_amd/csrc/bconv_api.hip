@@ -405,7 +405,7 @@ static int run_conv_launch(const float* in, const float* filt, const float* bias
       return BCONV_EWORKSPACE;
     }
     if (dry) return BCONV_OK;
-    return launch_hconv(h, in, filt, bias, out, s, relu, ws, st) == hipSuccess ? BCONV_OK : BCONV_ELAUNCH;
+    return launch_hconv(h, in, filt, bias, out, s, relu, 0, 0, ws, st) == hipSuccess ? BCONV_OK : BCONV_ELAUNCH;
   }
   if (variant_id == 0) {
     if (dry) return BCONV_OK;
@@ -917,7 +917,7 @@ static int packed_tile(const Shape& s, int variant_id) {
   if (images_per_launch(s) < s.N) return -1;            // one launch only
   const int id = variant_id < 0 ? select_variant_f16(s, true, true) : variant_id;
   const int h = hconv_index(id);
-  return (h >= 0 && hconv_applicable(h, s)) ? h : -1;
+  return (h >= 0 && hconv_packable(h) && hconv_applicable(h, s)) ? h : -1;
 }
 
 int conv_fwd_f16_c8_selected_variant(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
@@ -928,7 +928,8 @@ int conv_fwd_f16_c8_selected_variant(int N, int C, int H, int W, int K, int R, i
   const int listed = f16_rows_lookup(kF16C8Table, s);
   if (listed > 0) return listed;
   const int h = hconv_select(s, true);
-  return h < 0 ? BCONV_EVARIANT : kNumTileVariants + fma_num_variants() + h;
+  // (the first-layer tiles read NCHW only)
+  return (h < 0 || !hconv_packable(h)) ? BCONV_EVARIANT : kNumTileVariants + fma_num_variants() + h;
 }
 
 size_t conv_f16_packed_filter_bytes(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -986,6 +987,40 @@ int conv_fwd_f16_packed_layout_ex(const void* in, int in_layout, const void* pac
   if (h < 0) return BCONV_EVARIANT;
   return launch_hconv_packed(h, in, packed, bias, out, s, relu, in_layout == BCONV_LAYOUT_C8,
                              out_layout == BCONV_LAYOUT_C8, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? BCONV_OK
+             : BCONV_ELAUNCH;
+}
+
+int conv_fwd_f16_layout_ex(const void* in, int in_layout, const void* filt, const float* bias, void* out,
+                           int out_layout, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           int relu, void* workspace, size_t workspace_bytes, void* hip_stream, int variant_id) {
+  if ((in_layout != BCONV_LAYOUT_NCHW && in_layout != BCONV_LAYOUT_C8) ||
+      (out_layout != BCONV_LAYOUT_NCHW && out_layout != BCONV_LAYOUT_C8))
+    return BCONV_EINVAL;
+  if (in_layout == BCONV_LAYOUT_NCHW && out_layout == BCONV_LAYOUT_NCHW)
+    return conv_fwd_f16_ex(in, filt, bias, out, N, C, H, W, K, R, S, stride, pad, relu, workspace, workspace_bytes,
+                           hip_stream, variant_id);
+  Shape s;
+  int rc = check_conv_args(in, filt, out, N, C, H, W, K, R, S, stride, pad, relu, 2, &s);
+  if (rc != BCONV_OK) return rc;
+  if (in_layout == BCONV_LAYOUT_C8 && (C % 8 != 0 || (reinterpret_cast<uintptr_t>(in) & 15u) != 0)) return BCONV_EINVAL;
+  if (out_layout == BCONV_LAYOUT_C8 && (K % 8 != 0 || (reinterpret_cast<uintptr_t>(out) & 15u) != 0)) return BCONV_EINVAL;
+  if (images_per_launch(s) < s.N) return BCONV_EVARIANT;
+  int id = variant_id;
+  if (id < 0) {
+    id = in_layout == BCONV_LAYOUT_C8 ? conv_fwd_f16_c8_selected_variant(N, C, H, W, K, R, S, stride, pad)
+                                      : select_variant_f16(s, true, true);
+    if (id < 0) return BCONV_EVARIANT;
+  }
+  const int h = hconv_index(id);
+  if (h < 0 || !hconv_applicable(h, s)) return BCONV_EVARIANT;
+  // channel-octet tiles write C8 from C8 input only; the first-layer tiles read NCHW only
+  if (hconv_packable(h) ? (in_layout != BCONV_LAYOUT_C8) : (in_layout != BCONV_LAYOUT_NCHW)) return BCONV_EVARIANT;
+  const size_t need = hconv_workspace_bytes(h, s);
+  if (!workspace || workspace_bytes < need) return BCONV_EWORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return BCONV_EINVAL;
+  return launch_hconv(h, in, filt, bias, out, s, relu, in_layout == BCONV_LAYOUT_C8, out_layout == BCONV_LAYOUT_C8,
+                      workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? BCONV_OK
              : BCONV_ELAUNCH;
 }

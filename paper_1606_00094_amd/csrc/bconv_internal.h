@@ -57,6 +57,18 @@ hipError_t launch_fma_conv(int which, const float* in, const float* filt, const 
 // Half-precision convolution on the fp16 matrix cores (hconv_mfma.hip); `which` indexes its
 // catalogue.  fp16 storage only; needs hconv_workspace_bytes of device scratch for the re-laid
 // filters.
+// First-layer kernels on the fp16 matrix cores (hconv_first.hip): C <= 3, 11x11 step 4 or 7x7
+// step 2; `which` indexes their own list, which hconv_* appends to its catalogue.
+int hfl_num_variants();
+const char* hfl_variant_name(int which);
+bool hfl_applicable(int which, const Shape& s);
+size_t hfl_workspace_bytes(int which, const Shape& s);
+long long hfl_tiles(int which, const Shape& s);     // pixel tiles of the launch (0 if not applicable)
+hipError_t launch_hfl(int which, const void* in, const void* filt, const float* bias, void* out, const Shape& s,
+                      int relu, int out_c8, void* ws, hipStream_t st);
+// (false for the first-layer tiles: their filters cannot be packed ahead of the call, they
+// need workspace for the padded input as well)
+bool hconv_packable(int which);
 int hconv_num_variants();
 const char* hconv_variant_name(int which);
 bool hconv_applicable(int which, const Shape& s);
@@ -64,8 +76,10 @@ size_t hconv_workspace_bytes(int which, const Shape& s);
 // (any_size: also for launches too small to fill the chip, where the widening kernel would win
 // on NCHW activations -- the octet-interleaved layout has no other kernel)
 int hconv_select(const Shape& s, bool any_size = false);
+// (in_c8 / out_c8: octet-interleaved activations; the first-layer tiles take NCHW input only,
+// C8 output needs K % 8 == 0 and, for the channel-octet tiles, C8 input)
 hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
-                        const Shape& s, int relu, void* ws, hipStream_t st);
+                        const Shape& s, int relu, int in_c8, int out_c8, void* ws, hipStream_t st);
 hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st);
 hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
                                const Shape& s, int relu, int in_c8, int out_c8, hipStream_t st);

@@ -533,8 +533,13 @@ static const HTile kHTiles[] = {
 };
 constexpr int kNumHTiles = (int)(sizeof(kHTiles) / sizeof(kHTiles[0]));
 
-int hconv_num_variants() { return kNumHTiles; }
-const char* hconv_variant_name(int which) { return kHTiles[which].name; }
+// The catalogue of the fp16-matrix-core kernels: the channel-octet tiles of this file, then the
+// first-layer tiles (hconv_first.hip), which take NCHW activations and unpacked filters only.
+int hconv_num_variants() { return kNumHTiles + hfl_num_variants(); }
+const char* hconv_variant_name(int which) {
+  return which < kNumHTiles ? kHTiles[which].name : hfl_variant_name(which - kNumHTiles);
+}
+bool hconv_packable(int which) { return which >= 0 && which < kNumHTiles; }
 
 struct HPlan {
   HconvParams hp;
@@ -600,11 +605,13 @@ static bool plan_hconv(int which, const Shape& s0, HPlan* pl) {
 }
 
 bool hconv_applicable(int which, const Shape& s) {
+  if (which >= kNumHTiles) return hfl_applicable(which - kNumHTiles, s);
   HPlan pl;
   return plan_hconv(which, s, &pl);
 }
 
 size_t hconv_workspace_bytes(int which, const Shape& s) {
+  if (which >= kNumHTiles) return hfl_workspace_bytes(which - kNumHTiles, s);
   HPlan pl;
   return plan_hconv(which, s, &pl) ? pl.filt2_bytes : 0;
 }
@@ -632,13 +639,24 @@ int hconv_select(const Shape& s, bool any_size) {
     const double cost = per_cu * ((double)v.BM() * v.BN() * (1.0 + 16.0 / v.BM() + 16.0 / v.BN()) + 3000.0) / eff;
     if (best < 0 || cost < best_cost) { best = w; best_cost = cost; }
   }
+  if (best < 0) {
+    // a first layer (measured faster than the widening kernel from batch 1 up): the widest
+    // pixel tile that still gives every compute unit a tile, else the narrowest
+    int narrowest = -1;
+    for (int f = 0; f < hfl_num_variants(); ++f) {
+      if (!hfl_applicable(f, s)) continue;
+      narrowest = f;
+      if (hfl_tiles(f, s) >= 256) return kNumHTiles + f;
+    }
+    if (narrowest >= 0) return kNumHTiles + narrowest;
+  }
   return best;
 }
 
 // The filters re-laid for tile `which` into `packed` (hconv_workspace_bytes bytes).
 hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st) {
   HPlan pl;
-  if (!plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
+  if (!hconv_packable(which) || !plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
   const HTile& v = kHTiles[which];
   const long long total = (long long)(pl.filt2_bytes / 2);
   long long blocks = (total + 255) / 256;
@@ -654,7 +672,7 @@ hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Sh
 hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
                                const Shape& s, int relu, int in_c8, int out_c8, hipStream_t st) {
   HPlan pl;
-  if (!plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
+  if (!hconv_packable(which) || !plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
   if (out_c8 && (!in_c8 || s.K % 8 != 0)) return hipErrorInvalidValue;
   pl.hp.g.in = static_cast<const float*>(in);
   pl.hp.g.bias = bias;
@@ -666,10 +684,14 @@ hipError_t launch_hconv_packed(int which, const void* in, const void* packed, co
 }
 
 hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
-                        const Shape& s, int relu, void* ws, hipStream_t st) {
+                        const Shape& s, int relu, int in_c8, int out_c8, void* ws, hipStream_t st) {
+  if (which >= kNumHTiles) {
+    if (in_c8) return hipErrorInvalidValue;
+    return launch_hfl(which - kNumHTiles, in, filt, bias, out, s, relu, out_c8, ws, st);
+  }
   hipError_t e = launch_hconv_pack(which, filt, ws, s, st);
   if (e != hipSuccess) return e;
-  return launch_hconv_packed(which, in, ws, bias, out, s, relu, 0, 0, st);
+  return launch_hconv_packed(which, in, ws, bias, out, s, relu, in_c8, out_c8, st);
 }
 
 #endif  // HCONV_LAYOUT == 0

@@ -148,9 +148,9 @@ def _family_of(tile):
         return (5, 5, 1)
     if tile.startswith(("pw_", "h16pw_")):
         return (1, 1, 1)
-    if tile.startswith("k11s4_"):
+    if tile.startswith(("k11s4_", "h16k11s4_")):
         return (11, 11, 4)
-    if tile.startswith("k7s2_"):
+    if tile.startswith(("k7s2_", "h16k7s2_")):
         return (7, 7, 2)
     if tile.startswith("pws2_"):
         return (1, 1, 2)

@@ -96,7 +96,9 @@ def test_layout_convert_is_the_transpose_both_ways():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("tile", sorted(t for t in _tile_families() if t.startswith("h16")))
+# (the first-layer tiles h16k11s4 / h16k7s2 take three-channel NCHW input only)
+@pytest.mark.parametrize("tile", sorted(t for t in _tile_families()
+                                        if t.startswith("h16") and not t.startswith(("h16k11s4", "h16k7s2"))))
 def test_c8_every_matrix_core_tile_exact_on_integers(tile):
     """Each fp16-matrix-core tile on C8 input, writing C8 (where K is a multiple of eight) and
     NCHW, on the ragged shapes of its family: bitwise equal to the oracle."""
@@ -251,3 +253,38 @@ def test_c8_refusals():
     assert lib.conv_fwd_f16_c8_selected_variant(4, l1.C, l1.H, l1.W, l1.K, l1.R, l1.S, l1.stride, l1.pad) == -6
     assert lib.conv_fwd_f16_c8_selected_variant(4, 16, 9, 9, 8, 3, 3, 2, 1) == -6
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("N", [1, 5, 32])
+def test_first_layer_tiles_write_c8_directly(N):
+    """conv_fwd_f16_layout_ex, NCHW in -> C8 out, on the first benchmark layer (the first-layer
+    fp16-matrix-core tiles are the half-precision path's choice there at every batch): every
+    image against the oracle, and the same bits as the NCHW output of the same call."""
+    layer = workloads.CONV1
+    dims = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad)
+    v = binding.conv_fwd_f16_selected_variant(*dims)
+    assert binding.conv_variant_name(v).startswith("h16k11s4"), binding.conv_variant_name(v)
+    x, f, b = workloads.make_layer_inputs(layer, N, seed=workloads.BASE_SEED + 620 + N)
+    x, f = x.astype(np.float16), f.astype(np.float16)
+    dev = torch.device("cuda:0")
+    P, Q = binding.conv_out_dims(layer.H, layer.W, layer.R, layer.S, layer.stride, layer.pad)
+    xd, fd, bd = torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev)
+    ws = torch.zeros(binding.conv_fwd_f16_workspace_bytes(*dims, v) // 4 + 1, dtype=torch.float32, device=dev)
+    o8 = torch.full((N, layer.K // 8, P, Q, 8), float("nan"), dtype=torch.float16, device=dev)
+    binding.conv_fwd_f16_layout_ex(xd, NCHW, fd, bd, o8, C8, x.shape, layer.stride, layer.pad, True, ws)
+    got = torch.empty((N, layer.K, P, Q), dtype=torch.float16, device=dev)
+    binding.f16_layout_convert(o8, C8, got, NCHW, (N, layer.K, P, Q))
+    plain = torch.full((N, layer.K, P, Q), float("nan"), dtype=torch.float16, device=dev)
+    binding.conv_fwd_f16_layout_ex(xd, NCHW, fd, bd, plain, NCHW, x.shape, layer.stride, layer.pad, True, ws)
+    torch.cuda.synchronize()
+    ref = oracle.conv_fwd_f16(x, f, b, stride=layer.stride, pad=layer.pad, relu=True)
+    assert_close_f16(got.cpu().numpy(), ref, "conv1 N=%d to C8" % N)
+    assert torch.equal(got, plain)
+    lib = binding.lib()
+    # a first-layer tile cannot read C8; too small a workspace; C8 out with K not a multiple of eight
+    args = (N, layer.C, layer.H, layer.W, layer.K, layer.R, layer.S, layer.stride, layer.pad, 1)
+    assert lib.conv_fwd_f16_layout_ex(xd.data_ptr(), NCHW, fd.data_ptr(), bd.data_ptr(), o8.data_ptr(), C8, *args,
+                                      ws.data_ptr(), 16, None, v) == -4
+    assert lib.conv_fwd_f16_layout_ex(xd.data_ptr(), NCHW, fd.data_ptr(), bd.data_ptr(), o8.data_ptr(), C8,
+                                      N, layer.C, layer.H, layer.W, 92, layer.R, layer.S, layer.stride, layer.pad, 1,
+                                      ws.data_ptr(), ws.numel() * 4, None, v) == -1
