@@ -364,6 +364,8 @@ def main():
                     help="batch of the supplementary per-layer table (0: skip it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer-table", action="store_true")
+    ap.add_argument("--no-stack", action="store_true",
+                    help="skip the five-layer stacks and the matrix products (a profile of single layers)")
     ap.add_argument("--cpu-baseline-batch", type=int, default=32)
     ap.add_argument("--layers", default="", help="comma-separated layer names (default: all ten)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -487,15 +489,15 @@ def main():
             "traffic": recorded_traffic(dom), "kernel": binding.conv_variant_name(dom.variant),
             "layer": dom.layer.name, "N": dom.N, "us_per_launch": round(dom_ms * 1e3, 2)}
 
-    stack = [] if args.no_layer_table else [run_stack(n, 20) for n in (1, 5, 20, 32)]
+    stack = [] if args.no_layer_table or args.no_stack else [run_stack(n, 20) for n in (1, 5, 20, 32)]
     for row in stack:
         log(json.dumps({"stack": row}))
 
-    stack16 = [] if args.no_layer_table else [run_stack_f16(n, 20) for n in (1, 5, 20, 32)]
+    stack16 = [] if args.no_layer_table or args.no_stack else [run_stack_f16(n, 20) for n in (1, 5, 20, 32)]
     for row in stack16:
         log(json.dumps({"stack_f16": row}))
 
-    sgemm = [] if args.no_layer_table else [run_sgemm(n) for n in workloads.SGEMM_SIZES]
+    sgemm = [] if args.no_layer_table or args.no_stack else [run_sgemm(n) for n in workloads.SGEMM_SIZES]
     for row in sgemm:
         log(json.dumps({"sgemm": row}))
 
