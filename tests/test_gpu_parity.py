@@ -120,8 +120,8 @@ FAMILY_SHAPES = {
                 (3, 16, 14, 14, 40, 2)],
     (1, 1, 1): [(3, 37, 7, 7, 50, 0), (2, 20, 14, 14, 130, 0), (1, 9, 28, 28, 64, 0), (5, 8, 6, 6, 33, 0),
                 (2, 132, 7, 7, 40, 0), (2, 72, 14, 14, 130, 0), (3, 40, 7, 7, 50, 0)],
-    (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2)],
-    (7, 7, 2): [(2, 3, 37, 41, 70, 3), (1, 3, 224, 224, 64, 3), (1, 2, 30, 29, 33, 0)],
+    (11, 11, 4): [(2, 3, 67, 71, 100, 0), (1, 3, 227, 227, 96, 0), (1, 2, 51, 47, 30, 2), (1, 3, 35, 39, 160, 1)],
+    (7, 7, 2): [(2, 3, 37, 41, 70, 3), (1, 3, 224, 224, 64, 3), (1, 2, 30, 29, 33, 0), (3, 1, 21, 23, 136, 3)],
     (1, 1, 2): [(2, 20, 14, 14, 70, 0), (1, 36, 28, 27, 130, 0), (3, 8, 7, 9, 33, 1)],
     (3, 3, 2): [(2, 12, 27, 27, 70, 0), (1, 8, 28, 30, 130, 1), (3, 4, 9, 7, 33, 2)],
     (1, 7, 1): [(2, 12, 17, 17, 70, 0), (1, 8, 9, 30, 130, 3), (2, 4, 5, 11, 33, 1)],
