@@ -167,7 +167,10 @@ void hfl_kernel(const HflParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[nt][i] = 0.0f;
 
-    // the 16 bytes of an operand in pieces the alignment allows (8 bytes at stride 4, 4 at 2)
+    // the 16 bytes of an operand in pieces the alignment allows (8 bytes at stride 4, 4 at 2).
+    // Slots past the kernel's width hold input columns that belong to the NEXT pixels' windows;
+    // their filter slots are zero, but 0 x Inf is NaN, so they are cleared here as well and
+    // a non-finite input element reaches exactly the outputs whose window contains it.
     auto read_b = [&](int off) {
       fl_quad v;
       if constexpr (STR_ >= 4) {
@@ -177,6 +180,14 @@ void hfl_kernel(const HflParams p) {
       } else {
 #pragma unroll
         for (int w = 0; w < 4; ++w) v[w] = *reinterpret_cast<const unsigned*>(B + off + 4 * w);
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        // slots 2w, 2w+1 of this lane's octet are columns base + 2w, base + 2w + 1
+        const int lo0 = 2 * w, lo1 = (WIDE ? 8 : 0) + 2 * w;       // first column, lane half 0 / 1
+        const unsigned m0 = lo0 + 1 < S_ ? 0xffffffffu : (lo0 < S_ ? 0x0000ffffu : 0u);
+        const unsigned m1 = lo1 + 1 < S_ ? 0xffffffffu : (lo1 < S_ ? 0x0000ffffu : 0u);
+        if (m0 != 0xffffffffu || m1 != 0xffffffffu) v[w] &= (gq ? m1 : m0);
       }
       return __builtin_bit_cast(fl_half8, v);
     };

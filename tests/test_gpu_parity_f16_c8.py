@@ -288,3 +288,30 @@ def test_first_layer_tiles_write_c8_directly(N):
     assert lib.conv_fwd_f16_layout_ex(xd.data_ptr(), NCHW, fd.data_ptr(), bd.data_ptr(), o8.data_ptr(), C8,
                                       N, layer.C, layer.H, layer.W, 92, layer.R, layer.S, layer.stride, layer.pad, 1,
                                       ws.data_ptr(), ws.numel() * 4, None, v) == -1
+
+
+@pytest.mark.parametrize("tile,shape", [("h16k11s4_p64", (1, 3, 51, 55, 40, 11, 4, 0)),
+                                        ("h16k7s2_p32", (1, 3, 29, 31, 40, 7, 2, 3))])
+def test_first_layer_tiles_keep_an_infinity_inside_its_windows(tile, shape):
+    """One +Inf input element: the outputs whose window contains it are non-finite, every other
+    output is the oracle's finite value (the kernel's reduction slots past the kernel width read
+    neighbouring columns; they must not leak)."""
+    N, C, H, W, K, R, stride, pad = shape
+    v = binding.variant_ids_by_name()[tile + "/s1"]
+    x, f, b = workloads.make_integer_problem(99, N, C, H, W, K, R, R)
+    x, f = x.astype(np.float16), np.abs(f).astype(np.float16) + np.float16(1)
+    x[0, 1, H // 2, W // 2] = np.float16(np.inf)
+    with np.errstate(invalid="ignore"):
+        ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=False)
+    dev = torch.device("cuda:0")
+    P, Q = ref.shape[2:]
+    dims = (N, C, H, W, K, R, R, stride, pad)
+    ws = torch.zeros(binding.conv_fwd_f16_workspace_bytes(*dims, v) // 4 + 1, dtype=torch.float32, device=dev)
+    out = torch.empty((N, K, P, Q), dtype=torch.float16, device=dev)
+    binding.conv_fwd_f16_ex(torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev), torch.from_numpy(b).to(dev), out,
+                            stride, pad, False, workspace=ws, variant=v)
+    got = out.cpu().numpy()
+    finite = np.isfinite(ref)
+    assert 0 < (~finite).sum() < ref.size
+    assert np.array_equal(np.isfinite(got), finite)
+    assert np.array_equal(got[finite], ref[finite])
