@@ -88,8 +88,9 @@ void fma_conv_kernel(const FmaParams p) {
         const float* src = p.in + ((size_t)(n * p.C + c) * p.H + (rowok ? iy : 0)) * p.W;
         for (int i = 0; i < p.NI; ++i) {
           const int x = x0 + i * STR;
-          // (a column past S multiplies a zero filter word; only the image bounds are tested)
-          const float v = (rowok && (unsigned)x < (unsigned)p.W) ? src[x] : 0.0f;
+          // (a column past S multiplies a zero filter word, and must be zero itself: it belongs
+          // to the next pixel's window, and 0 x Inf would be NaN)
+          const float v = (rowok && (unsigned)x < (unsigned)p.W && i * STR + j < p.S) ? src[x] : 0.0f;
 #pragma unroll
           for (int k4 = 0; k4 < KB; k4 += 4) {
             const float4 f = *reinterpret_cast<const float4*>(flp + k4);

@@ -868,3 +868,38 @@ def test_mfma_loop_measurement_aid_runs_and_validates_arguments():
         binding.bconv_debug_mfma_loop(buf, 0, 3)
     with pytest.raises(ValueError):
         binding.bconv_debug_mfma_loop(buf, 9, 3)
+
+
+# ------------------------------------------------------------------ non-finite inputs
+@pytest.mark.parametrize("shape", [(2, 13, 13, 13, 70, 3, 3, 1, 1), (3, 37, 7, 7, 50, 1, 1, 1, 0),
+                                   (2, 6, 27, 27, 40, 5, 5, 1, 2), (2, 3, 67, 71, 100, 11, 11, 4, 0),
+                                   (2, 20, 14, 14, 70, 1, 1, 2, 0)],
+                         ids=lambda s: "C%d_%dx%d_K%d_%dx%d_s%d" % (s[1], s[2], s[3], s[4], s[5], s[6], s[7]))
+def test_an_infinite_input_element_stays_inside_its_windows(shape):
+    """One +Inf input element (positive filters, so no Inf - Inf): exactly the outputs whose
+    window holds it are non-finite, all others equal the oracle's.  The kernels pad their
+    reduction (chunk tails, the next image's planes) with zeros on the filter side; the padded
+    input side must be zero as well, or 0 x Inf would leak NaN into neighbouring outputs.
+    Every applicable tile of the shape's family, unsplit and with its first split."""
+    N, C, H, W, K, R, S, stride, pad = shape
+    x, f, b = workloads.make_integer_problem(7 + sum(shape), N, C, H, W, K, R, S)
+    f = np.abs(f) + 1.0
+    P, Q = binding.conv_out_dims(H, W, R, S, stride, pad)
+    # the centre of the window of output point (P/2, Q/2)
+    x[N - 1, C - 1, (P // 2) * stride - pad + R // 2, (Q // 2) * stride - pad + S // 2] = np.inf
+    ref = oracle.conv_fwd(x, f, b, stride=stride, pad=pad, relu=False)
+    finite = np.isfinite(ref)
+    assert 0 < (~finite).sum() < ref.size
+    ran = 0
+    for tile, ids in sorted(_tile_families().items()):
+        if tile.startswith("h16"):
+            continue
+        for v in ids[:2]:
+            if not binding.conv_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+                continue
+            got = gpu_conv(x, f, b, stride, pad, False, variant=v)
+            name = binding.conv_variant_name(v)
+            assert np.array_equal(np.isfinite(got), finite), name
+            assert np.array_equal(got[finite], ref[finite]), name
+            ran += 1
+    assert ran > 0

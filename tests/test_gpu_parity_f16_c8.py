@@ -315,3 +315,28 @@ def test_first_layer_tiles_keep_an_infinity_inside_its_windows(tile, shape):
     assert 0 < (~finite).sum() < ref.size
     assert np.array_equal(np.isfinite(got), finite)
     assert np.array_equal(got[finite], ref[finite])
+
+
+@pytest.mark.parametrize("fam", [(3, 3, 1), (5, 5, 1), (1, 1, 1)], ids=lambda f: "%dx%d" % f[:2])
+def test_c8_tiles_keep_an_infinity_inside_its_windows(fam):
+    """The channel-octet tiles pad the last chunk's channels with zero filters; the input side of
+    those channels must be zero too (it is: octets past the last channel are not loaded).  One
+    +Inf input element, every applicable tile, C8 in and out."""
+    R, S, stride = fam
+    N, C, H, W, K, pad = C8_SHAPES[fam][0]
+    x, f, b = workloads.make_integer_problem(5 + R, N, C, H, W, K, R, S)
+    x, f = x.astype(np.float16), (np.abs(f) + 1).astype(np.float16)
+    x[N - 1, C - 1, H // 2, W // 2] = np.float16(np.inf)
+    ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=False)
+    finite = np.isfinite(ref)
+    assert 0 < (~finite).sum() < ref.size
+    ran = 0
+    for tile, (v,) in sorted((t, ids) for t, ids in _tile_families().items()
+                             if t.startswith("h16") and _family_of(t) == fam):
+        if not binding.conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+            continue
+        got = gpu_conv_c8(x, f, b, stride, pad, False, v, True)
+        assert np.array_equal(np.isfinite(got), finite), tile
+        assert np.array_equal(got[finite], ref[finite]), tile
+        ran += 1
+    assert ran > 0
