@@ -56,15 +56,23 @@ struct HconvParams {
   int coct;                 // C / 8
 };
 
-template <int R_, int S_, int WM, int WN, int MT, int NT, int CC, int EPB, bool C8I, bool C8O>
+// TR: kernel rows of a chunk's filters staged at a time (R_: the whole chunk in one stage; 1: a
+// stage per kernel row, which cuts the filters' LDS footprint R_-fold -- what lets a 5x5 tile of
+// 64 or 128 filters leave room for several workgroups per compute unit).  The input halo of a
+// chunk is staged once and serves all its stages.
+template <int R_, int S_, int WM, int WN, int MT, int NT, int CC, int EPB, int TR, bool C8I, bool C8O>
 __global__ __launch_bounds__(WM * WN * 64)
 void hconv_mfma_kernel(const HconvParams hp) {
+  static_assert(R_ % TR == 0, "stages are whole kernel rows");
   constexpr int NTHR = WM * WN * 64;
   constexpr int BM = WM * MT * 32, BN = WN * NT * 32;
   constexpr int TAPS = R_ * S_;
+  constexpr int NRS = R_ / TR;            // stages per chunk
+  constexpr int STAPS = TR * S_;          // taps per stage
   constexpr int NOCT = CC / 8;            // octets per position (or tap) and chunk
   constexpr int NJ = CC / 16;             // MFMAs per tap and chunk
-  constexpr int AROW = TAPS * NOCT;       // 16-byte units per filter row and chunk
+  constexpr int FROW = TAPS * NOCT;       // 16-byte units per filter row and chunk (packed filters)
+  constexpr int AROW = STAPS * NOCT;      // ... and stage
   constexpr int AST = AROW | 1;           // LDS row stride (odd: rows spread over the banks)
   constexpr int NA = (BM * AROW + NTHR - 1) / NTHR;
   constexpr bool PW = (R_ == 1 && S_ == 1);
@@ -127,13 +135,13 @@ void hconv_mfma_kernel(const HconvParams hp) {
     const int e = tid + i * NTHR;
     const int m = e / AROW, j = e - m * AROW;
     const bool ok = (e < BM * AROW) && (m0 + m < p.K);
-    a_voff[i] = ok ? (unsigned)((((m0 + m) * hp.nch) * AROW + j) * 16) : kOob;
+    a_voff[i] = ok ? (unsigned)((((m0 + m) * hp.nch) * FROW + j) * 16) : kOob;
     a_lds[i] = (e < BM * AROW) ? m * AST + j : -1;
   }
   const __amdgpu_buffer_rsrc_t rsrc_in = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(p.in), 0, p.N * p.CHW * 2, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_f = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<_Float16*>(hp.filt2), 0, p.K * hp.nch * AROW * 16, 0x00020000);
+      const_cast<_Float16*>(hp.filt2), 0, p.K * hp.nch * FROW * 16, 0x00020000);
 
   // ---- per-lane operand bases (16-byte units)
   const int laneA = (wm * MT * 32 + l32) * AST + gq;
@@ -180,10 +188,15 @@ void hconv_mfma_kernel(const HconvParams hp) {
   uquad ra[NA];
   unsigned short rb[C8I ? 1 : EPB][8];
   uquad rq[C8I ? EPB : 1];
-  auto load_chunk = [&](int ch) {
+  // filters of stage rr of chunk ch
+  auto load_a = [&](int ch, int rr) {
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-      ra[i] = __builtin_bit_cast(uquad, __builtin_amdgcn_raw_buffer_load_b128(rsrc_f, a_voff[i], ch * AROW * 16, 0));
+      ra[i] = __builtin_bit_cast(uquad, __builtin_amdgcn_raw_buffer_load_b128(rsrc_f, a_voff[i],
+                                                                              (ch * FROW + rr * AROW) * 16, 0));
+  };
+  // input halo of chunk ch
+  auto load_b = [&](int ch) {
 #pragma unroll
     for (int i = 0; i < EPB; ++i) {
       // an octet past the last channel reads nothing (C is a multiple of eight)
@@ -197,12 +210,14 @@ void hconv_mfma_kernel(const HconvParams hp) {
       }
     }
   };
-  auto store_chunk = [&](int buf) {
+  auto store_a = [&](int buf) {
     uquad* A = As + buf * abuf;
-    uquad* B = Bs + buf * bbuf;
 #pragma unroll
     for (int i = 0; i < NA; ++i)
       if (a_lds[i] >= 0) A[a_lds[i]] = ra[i];
+  };
+  auto store_b = [&](int buf) {
+    uquad* B = Bs + buf * bbuf;
 #pragma unroll
     for (int i = 0; i < EPB; ++i) {
       if (b_oct[i] < NOCT) {
@@ -217,15 +232,15 @@ void hconv_mfma_kernel(const HconvParams hp) {
       }
     }
   };
-  // One chunk out of LDS buffer `buf`.  Operand reads run HCONV_PF steps (a step is one MFMA
-  // depth of one tap) ahead of the MFMAs that use them: the reads of step s+PF are issued, then
-  // the MFMAs of step s, and the scheduler may not move anything across a step boundary, so a
-  // wave's LDS latency hides behind its own MFMAs.  (Measured: two steps ahead 1-5 % over one,
-  // three no better.)
-  auto compute_chunk = [&](int buf) {
-    const uquad* A = As + buf * abuf;
-    const uquad* B = Bs + buf * bbuf;
-    constexpr int STEPS = TAPS * NJ;
+  // One stage out of filter buffer abuf_i and input buffer bbuf_i.  Operand reads run HCONV_PF
+  // steps (a step is one MFMA depth of one tap) ahead of the MFMAs that use them: the reads of
+  // step s+PF are issued, then the MFMAs of step s, and the scheduler may not move anything
+  // across a step boundary, so a wave's LDS latency hides behind its own MFMAs.  (Measured: two
+  // steps ahead 1-5 % over one, three no better.)
+  auto compute_stage = [&](int abuf_i, int bbuf_i, int rr) {
+    const uquad* A = As + abuf_i * abuf;
+    const uquad* B = Bs + bbuf_i * bbuf + (PW ? 0 : rr * TR * p.rowst);
+    constexpr int STEPS = STAPS * NJ;
     constexpr int PF = HCONV_PF < STEPS ? HCONV_PF : (STEPS > 1 ? STEPS - 1 : 1);   // steps read ahead
     constexpr int NS = PF + 1;
     half8 a[NS][MT], b[NS][NT];
@@ -253,16 +268,31 @@ void hconv_mfma_kernel(const HconvParams hp) {
     }
   };
 
-  load_chunk(0);
-  store_chunk(0);
+  // Stage it = ch * NRS + rr multiplies out of filter buffer it & 1 and input buffer ch & 1 while
+  // the loads of stage it + 1 (its filters; at the first stage of a chunk also the next chunk's
+  // halo) are in flight; they are written to the other buffers afterwards, the halo at the
+  // chunk's last stage.  One barrier per stage.
+  load_a(0, 0);
+  load_b(0);
+  store_a(0);
+  store_b(0);
   __syncthreads();
-  for (int ch = 0; ch < hp.nch; ++ch) {
-    const bool more = ch + 1 < hp.nch;
-    if (more) load_chunk(ch + 1);
-    __builtin_amdgcn_sched_barrier(0);   // the loads are in flight before the first operand read
-    compute_chunk(ch & 1);
-    if (more) store_chunk((ch + 1) & 1);
-    __syncthreads();
+  {
+    int ch = 0, rr = 0;
+    const int nstages = hp.nch * NRS;
+    for (int it = 0; it < nstages; ++it) {
+      const bool more = it + 1 < nstages;
+      const bool last_of_chunk = rr == NRS - 1;
+      const bool more_ch = ch + 1 < hp.nch;
+      if (more) load_a(last_of_chunk ? ch + 1 : ch, last_of_chunk ? 0 : rr + 1);
+      if (rr == 0 && more_ch) load_b(ch + 1);
+      __builtin_amdgcn_sched_barrier(0);   // the loads are in flight before the first operand read
+      compute_stage(it & 1, ch & 1, rr);
+      if (more) store_a((it + 1) & 1);
+      if (last_of_chunk && more_ch) store_b((ch + 1) & 1);
+      __syncthreads();
+      if (last_of_chunk) { rr = 0; ++ch; } else { ++rr; }
+    }
   }
 
   // ---- epilogue: bias + optional ReLU, one rounding to fp16, store
@@ -322,34 +352,38 @@ void hconv_mfma_kernel(const HconvParams hp) {
 // ------------------------------------------------------------------ catalogue and planning
 struct HTile {
   const char* name;
-  int R, S, WM, WN, MT, NT, CC, EPB;
+  int R, S, WM, WN, MT, NT, CC, EPB, TR;
   int BM() const { return WM * MT * 32; }
   int BN() const { return WN * NT * 32; }
   int NTHR() const { return WM * WN * 64; }
 };
-#define HCONV_TILES(X)                         \
-  X(h16k3_128x128_c16, 3, 3, 2, 2, 2, 2, 16, 3) \
-  X(h16k3_64x128_c16, 3, 3, 2, 2, 1, 2, 16, 3)  \
-  X(h16k3_128x64_c16, 3, 3, 2, 2, 2, 1, 16, 2)  \
-  X(h16k3_64x64_c16, 3, 3, 2, 2, 1, 1, 16, 2)   \
-  X(h16k3_64x128_c32, 3, 3, 2, 2, 1, 2, 32, 6)  \
-  X(h16k5_64x128_c16, 5, 5, 2, 2, 1, 2, 16, 4)  \
-  X(h16k5_64x64_c16, 5, 5, 2, 2, 1, 1, 16, 3)   \
-  X(h16k5_32x128_c16, 5, 5, 1, 4, 1, 1, 16, 4)  \
-  X(h16pw_128x128_c32, 1, 1, 2, 2, 2, 2, 32, 2) \
-  X(h16pw_64x128_c32, 1, 1, 2, 2, 1, 2, 32, 2)  \
-  X(h16pw_128x64_c32, 1, 1, 2, 2, 2, 1, 32, 1)  \
-  X(h16pw_64x64_c32, 1, 1, 2, 2, 1, 1, 32, 1)   \
-  X(h16pw_64x64_c64, 1, 1, 2, 2, 1, 1, 64, 2)   \
-  X(h16k3_32x128_c16, 3, 3, 1, 4, 1, 1, 16, 3)  \
-  X(h16k3_32x64_c16, 3, 3, 1, 2, 1, 1, 16, 4)   \
-  X(h16k3_64x64_c32, 3, 3, 2, 2, 1, 1, 32, 4)   \
-  X(h16pw_32x128_c64, 1, 1, 1, 4, 1, 1, 64, 4)  \
-  X(h16pw_32x64_c64, 1, 1, 1, 2, 1, 1, 64, 4)   \
-  X(h16pw_64x32_c64, 1, 1, 2, 1, 1, 1, 64, 2)   \
-  X(h16k3_128x256_c16, 3, 3, 2, 4, 2, 2, 16, 3) \
-  X(h16pw_128x256_c32, 1, 1, 2, 4, 2, 2, 32, 2) \
-  X(h16k5_64x256_c16, 5, 5, 2, 4, 1, 2, 16, 3)
+#define HCONV_TILES(X) \
+  X(h16k3_128x128_c16, 3, 3, 2, 2, 2, 2, 16, 3, 3) \
+  X(h16k3_64x128_c16, 3, 3, 2, 2, 1, 2, 16, 3, 3) \
+  X(h16k3_128x64_c16, 3, 3, 2, 2, 2, 1, 16, 2, 3) \
+  X(h16k3_64x64_c16, 3, 3, 2, 2, 1, 1, 16, 2, 3) \
+  X(h16k3_64x128_c32, 3, 3, 2, 2, 1, 2, 32, 6, 3) \
+  X(h16k5_64x128_c16, 5, 5, 2, 2, 1, 2, 16, 4, 5) \
+  X(h16k5_64x64_c16, 5, 5, 2, 2, 1, 1, 16, 3, 5) \
+  X(h16k5_32x128_c16, 5, 5, 1, 4, 1, 1, 16, 4, 5) \
+  X(h16pw_128x128_c32, 1, 1, 2, 2, 2, 2, 32, 2, 1) \
+  X(h16pw_64x128_c32, 1, 1, 2, 2, 1, 2, 32, 2, 1) \
+  X(h16pw_128x64_c32, 1, 1, 2, 2, 2, 1, 32, 1, 1) \
+  X(h16pw_64x64_c32, 1, 1, 2, 2, 1, 1, 32, 1, 1) \
+  X(h16pw_64x64_c64, 1, 1, 2, 2, 1, 1, 64, 2, 1) \
+  X(h16k3_32x128_c16, 3, 3, 1, 4, 1, 1, 16, 3, 3) \
+  X(h16k3_32x64_c16, 3, 3, 1, 2, 1, 1, 16, 4, 3) \
+  X(h16k3_64x64_c32, 3, 3, 2, 2, 1, 1, 32, 4, 3) \
+  X(h16pw_32x128_c64, 1, 1, 1, 4, 1, 1, 64, 4, 1) \
+  X(h16pw_32x64_c64, 1, 1, 1, 2, 1, 1, 64, 4, 1) \
+  X(h16pw_64x32_c64, 1, 1, 2, 1, 1, 1, 64, 2, 1) \
+  X(h16k3_128x256_c16, 3, 3, 2, 4, 2, 2, 16, 3, 3) \
+  X(h16pw_128x256_c32, 1, 1, 2, 4, 2, 2, 32, 2, 1) \
+  X(h16k5_64x256_c16, 5, 5, 2, 4, 1, 2, 16, 3, 5) \
+  X(h16k5_64x256_c16r1, 5, 5, 2, 4, 1, 2, 16, 3, 1) \
+  X(h16k5_128x256_c16r1, 5, 5, 2, 4, 2, 2, 16, 3, 1) \
+  X(h16k5_64x128_c16r1, 5, 5, 2, 2, 1, 2, 16, 4, 1) \
+  X(h16k5_32x128_c16r1, 5, 5, 1, 4, 1, 1, 16, 4, 1)
 
 typedef hipError_t (*HLaunchFn)(const HconvParams&, dim3, size_t, hipStream_t);
 // One launch table per layout pair, each held by its own translation unit.
@@ -387,17 +421,17 @@ static hipError_t launch_h(KernelT kernel, int nthr, const HconvParams& hp, dim3
 #define HCONV_C8I true
 #define HCONV_C8O true
 #endif
-#define X(name, R, S, WM, WN, MT, NT, CC, EPB)                                                        \
+#define X(name, R, S, WM, WN, MT, NT, CC, EPB, TR)                                                    \
   static hipError_t hlaunch_##name(const HconvParams& hp, dim3 grid, size_t lds, hipStream_t st) {    \
     static std::atomic<size_t> allowed[64];                                                           \
-    return launch_h(hconv_mfma_kernel<R, S, WM, WN, MT, NT, CC, EPB, HCONV_C8I, HCONV_C8O>, WM * WN * 64, hp, grid, \
-                    lds, st, allowed);                                                                \
+    return launch_h(hconv_mfma_kernel<R, S, WM, WN, MT, NT, CC, EPB, TR, HCONV_C8I, HCONV_C8O>, WM * WN * 64, hp,  \
+                    grid, lds, st, allowed);                                                          \
   }
 HCONV_TILES(X)
 #undef X
 HLaunchFn HCONV_TABLE(int which) {
   static const HLaunchFn table[] = {
-#define X(name, R, S, WM, WN, MT, NT, CC, EPB) hlaunch_##name,
+#define X(name, R, S, WM, WN, MT, NT, CC, EPB, TR) hlaunch_##name,
       HCONV_TILES(X)
 #undef X
   };
@@ -527,7 +561,7 @@ hipError_t launch_f16_layout(const void* in, void* out, long long n_times_c, int
 }
 
 static const HTile kHTiles[] = {
-#define X(name, R, S, WM, WN, MT, NT, CC, EPB) {#name, R, S, WM, WN, MT, NT, CC, EPB},
+#define X(name, R, S, WM, WN, MT, NT, CC, EPB, TR) {#name, R, S, WM, WN, MT, NT, CC, EPB, TR},
     HCONV_TILES(X)
 #undef X
 };
@@ -588,7 +622,8 @@ static bool plan_hconv(int which, const Shape& s0, HPlan* pl) {
   }
   const int noct = v.CC / 8;
   if ((long long)noct * npos > (long long)v.EPB * v.NTHR()) return false;
-  const int arow = v.R * v.S * noct, ast = arow | 1;
+  const int arow = v.R * v.S * noct;                 // per chunk (the packed filters)
+  const int ast = (v.TR * v.S * noct) | 1;           // per stage (LDS row stride)
   const size_t lds = (size_t)16 * (2 * (size_t)BM * ast + 2 * (size_t)noct * npos);
   if (lds > kLdsLimitBytes) return false;
   pl->hp.nch = (s.C + v.CC - 1) / v.CC;
