@@ -149,8 +149,11 @@ size_t conv_fwd_f16_workspace_bytes(int N, int C, int H, int W, int K, int R, in
  *     that many bytes), enqueued on hip_stream.
  *   conv_fwd_f16_packed_ex: conv_fwd_f16_ex on a packed copy made for the SAME shape and
  *     variant_id (the layout depends on the tile; a copy made for another tile gives wrong
- *     results without an error); no workspace; bit for bit the result of conv_fwd_f16_ex with
- *     that variant.
+ *     results without an error); no workspace argument; bit for bit the result of
+ *     conv_fwd_f16_ex with that variant.  A variant that splits the reduction (name .../sN,
+ *     N > 1: what small batches get) keeps its partial sums in the library's own per-device
+ *     buffer, as conv_fwd does: grown on first need, shared by the calls on that GPU, which
+ *     must therefore not overlap in time.
  * Errors as conv_fwd_f16_ex; BCONV_EVARIANT where conv_f16_packed_filter_bytes returns 0. */
 size_t conv_f16_packed_filter_bytes(int N, int C, int H, int W, int K, int R, int S, int stride,
                                     int pad, int variant_id);

@@ -61,9 +61,12 @@ hipError_t launch_direct_conv(const float* in, const float* filt, const float* b
 // Filter index of output element e of an N x K x PQ tensor: (e / PQ) % K, the two divisions
 // as multiplies and shifts with constants made by the host (a run-time integer division is
 // ~30 instructions, and these kernels are a handful of loads long).
-__device__ __forceinline__ int filter_of(int e, int K, FastDiv fdPQ, FastDiv fdK) {
+// (octet-interleaved output [N][K/8][PQ][8]: the host passes K/8 and 8*PQ, and the filter is
+// eight times the octet plus the element's position in its octet)
+__device__ __forceinline__ int filter_of(int e, int K, FastDiv fdPQ, FastDiv fdK, int c8 = 0) {
   const int plane = fd_div(e, fdPQ);
-  return plane - fd_div(plane, fdK) * K;
+  const int k = plane - fd_div(plane, fdK) * K;
+  return c8 ? k * 8 + (e & 7) : k;
 }
 
 // out[i] = act(bias[k(i)] + sum_z partial[z][i]), summed in split order.
@@ -71,14 +74,14 @@ template <typename T>
 __global__ __launch_bounds__(256)
 void splitk_reduce_kernel(const float* __restrict__ partial, const float* __restrict__ bias,
                           T* __restrict__ out, int nsplit, int out_elems, int K, int PQ,
-                          int relu, FastDiv fdPQ, FastDiv fdK) {
+                          int relu, FastDiv fdPQ, FastDiv fdK, int c8) {
   // (64-bit counter: i + stride may pass 2^31 when out_elems is close to it)
   for (long long i64 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i64 < out_elems;
        i64 += (long long)gridDim.x * blockDim.x) {
     const int i = (int)i64;
     float v = 0.0f;
     for (int z = 0; z < nsplit; ++z) v += partial[(size_t)z * out_elems + i];
-    if (bias) v += bias[filter_of(i, K, fdPQ, fdK)];
+    if (bias) v += bias[filter_of(i, K, fdPQ, fdK, c8)];
     if (relu) v = v > 0.0f ? v : 0.0f;
     out[i] = (T)v;
   }
@@ -100,7 +103,7 @@ template <typename Q4>
 __global__ __launch_bounds__(256)
 void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __restrict__ bias,
                            Q4* __restrict__ out, int nsplit, int out_quads, int K, int PQ,
-                           int relu, FastDiv fdPQ, FastDiv fdK) {
+                           int relu, FastDiv fdPQ, FastDiv fdK, int c8) {
   for (long long i64 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i64 < out_quads;
        i64 += (long long)gridDim.x * blockDim.x) {
     const int i = (int)i64;
@@ -132,10 +135,10 @@ void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __re
     }
     if (bias) {
       const int e = i * 4;
-      v.x += bias[filter_of(e, K, fdPQ, fdK)];
-      v.y += bias[filter_of(e + 1, K, fdPQ, fdK)];
-      v.z += bias[filter_of(e + 2, K, fdPQ, fdK)];
-      v.w += bias[filter_of(e + 3, K, fdPQ, fdK)];
+      v.x += bias[filter_of(e, K, fdPQ, fdK, c8)];
+      v.y += bias[filter_of(e + 1, K, fdPQ, fdK, c8)];
+      v.z += bias[filter_of(e + 2, K, fdPQ, fdK, c8)];
+      v.w += bias[filter_of(e + 3, K, fdPQ, fdK, c8)];
     }
     if (relu) {
       v.x = v.x > 0.0f ? v.x : 0.0f; v.y = v.y > 0.0f ? v.y : 0.0f;
@@ -146,7 +149,9 @@ void splitk_reduce4_kernel(const float4* __restrict__ partial, const float* __re
 }
 
 hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* out, int nsplit,
-                                int out_elems, int K, int PQ, int relu, bool f16, hipStream_t st) {
+                                int out_elems, int K, int PQ, int relu, bool f16, bool c8, hipStream_t st) {
+  if (c8) { K /= 8; PQ *= 8; }
+  const int c8i = c8 ? 1 : 0;
   const FastDiv fdPQ = make_fastdiv((unsigned)PQ), fdK = make_fastdiv((unsigned)K);
   const uintptr_t out_mask = f16 ? 7 : 15;
   const bool quads = (out_elems % 4 == 0) && ((reinterpret_cast<uintptr_t>(partial) & 15) == 0) &&
@@ -158,17 +163,17 @@ hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* 
     const float4* p4 = reinterpret_cast<const float4*>(partial);
     if (f16)
       return launch_kernel(splitk_reduce4_kernel<Half4>, dim3(blocks), dim3(256), 0, st, p4, bias,
-                           reinterpret_cast<Half4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK);
+                           reinterpret_cast<Half4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK, c8i);
     return launch_kernel(splitk_reduce4_kernel<float4>, dim3(blocks), dim3(256), 0, st, p4, bias,
-                         reinterpret_cast<float4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK);
+                         reinterpret_cast<float4*>(out), nsplit, n4, K, PQ, relu, fdPQ, fdK, c8i);
   }
   int blocks = (out_elems + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   if (f16)
     return launch_kernel(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, st, partial, bias,
-                         reinterpret_cast<_Float16*>(out), nsplit, out_elems, K, PQ, relu, fdPQ, fdK);
+                         reinterpret_cast<_Float16*>(out), nsplit, out_elems, K, PQ, relu, fdPQ, fdK, c8i);
   return launch_kernel(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, st, partial, bias, out,
-                       nsplit, out_elems, K, PQ, relu, fdPQ, fdK);
+                       nsplit, out_elems, K, PQ, relu, fdPQ, fdK, c8i);
 }
 
 // Split reduction with the pooling folded in: one thread per pooled output point takes the

@@ -154,7 +154,7 @@ static int find_variant(const char* tile, int nsplit) {
   for (int f = 0; f < fma_num_variants(); ++f)
     if (nsplit == 1 && std::strcmp(fma_variant_name(f), tile) == 0) return kNumTileVariants + f;
   for (int h = 0; h < hconv_num_variants(); ++h)
-    if (nsplit == 1 && std::strcmp(hconv_variant_name(h), tile) == 0)
+    if (nsplit == hconv_variant_split(h) && std::strcmp(hconv_variant_name(h), tile) == 0)
       return kNumTileVariants + fma_num_variants() + h;
   for (int t = 0; t < kNumTiles; ++t)
     if (std::strcmp(kTiles[t].name, tile) == 0)
@@ -447,7 +447,7 @@ static int run_conv_launch(const float* in, const float* filt, const float* bias
     return BCONV_ELAUNCH;
   if (nsplit > 1) {
     if (launch_splitk_reduce(pl.p.partial, bias, out, nsplit, pl.p.out_elems, s.K, s.P * s.Q, relu,
-                             f16, st) != hipSuccess)
+                             f16, false, st) != hipSuccess)
       return BCONV_ELAUNCH;
   }
   return BCONV_OK;
@@ -932,12 +932,20 @@ int conv_fwd_f16_c8_selected_variant(int N, int C, int H, int W, int K, int R, i
   return (h < 0 || !hconv_packable(h)) ? BCONV_EVARIANT : kNumTileVariants + fma_num_variants() + h;
 }
 
+// The partial sums of a split variant under the packed calls (which take no workspace): the
+// library's own per-device buffer, grown on first need like conv_fwd's.
+static int packed_scratch(int h, const Shape& s, void** scratch) {
+  *scratch = nullptr;
+  const size_t need = hconv_partial_bytes(h, s);
+  return need ? internal_workspace(need, scratch) : BCONV_OK;
+}
+
 size_t conv_f16_packed_filter_bytes(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                                     int variant_id) {
   Shape s;
   if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != BCONV_OK) return 0;
   const int h = packed_tile(s, variant_id);
-  return h < 0 ? 0 : hconv_workspace_bytes(h, s);
+  return h < 0 ? 0 : hconv_packed_bytes(h, s);
 }
 
 int conv_f16_pack_filters(const void* filt, void* packed, size_t packed_bytes, int N, int C, int H, int W,
@@ -949,7 +957,7 @@ int conv_f16_pack_filters(const void* filt, void* packed, size_t packed_bytes, i
   if (((reinterpret_cast<uintptr_t>(filt) & 1u) | (reinterpret_cast<uintptr_t>(packed) & 15u)) != 0) return BCONV_EINVAL;
   const int h = packed_tile(s, variant_id);
   if (h < 0) return BCONV_EVARIANT;
-  if (packed_bytes < hconv_workspace_bytes(h, s)) return BCONV_EWORKSPACE;
+  if (packed_bytes < hconv_packed_bytes(h, s)) return BCONV_EWORKSPACE;
   return launch_hconv_pack(h, filt, packed, s, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? BCONV_OK
                                                                                                   : BCONV_ELAUNCH;
 }
@@ -963,8 +971,11 @@ int conv_fwd_f16_packed_ex(const void* in, const void* packed, const float* bias
   if ((reinterpret_cast<uintptr_t>(packed) & 15u) != 0) return BCONV_EINVAL;
   const int h = packed_tile(s, variant_id);
   if (h < 0) return BCONV_EVARIANT;
-  return launch_hconv_packed(h, in, packed, bias, out, s, relu, 0, 0, static_cast<hipStream_t>(hip_stream)) ==
-                 hipSuccess
+  void* scratch = nullptr;
+  rc = packed_scratch(h, s, &scratch);
+  if (rc != BCONV_OK) return rc;
+  return launch_hconv_packed(h, in, packed, bias, out, s, relu, 0, 0, scratch,
+                             static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? BCONV_OK
              : BCONV_ELAUNCH;
 }
@@ -985,8 +996,11 @@ int conv_fwd_f16_packed_layout_ex(const void* in, int in_layout, const void* pac
   if (out_layout == BCONV_LAYOUT_C8 && (reinterpret_cast<uintptr_t>(out) & 15u) != 0) return BCONV_EINVAL;
   const int h = packed_tile(s, variant_id);
   if (h < 0) return BCONV_EVARIANT;
+  void* scratch = nullptr;
+  rc = packed_scratch(h, s, &scratch);
+  if (rc != BCONV_OK) return rc;
   return launch_hconv_packed(h, in, packed, bias, out, s, relu, in_layout == BCONV_LAYOUT_C8,
-                             out_layout == BCONV_LAYOUT_C8, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+                             out_layout == BCONV_LAYOUT_C8, scratch, static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? BCONV_OK
              : BCONV_ELAUNCH;
 }
@@ -1073,7 +1087,8 @@ int conv_variant_name(int variant_id, char* buf, size_t buflen) {
     return BCONV_OK;
   }
   if (hconv_index(variant_id) >= 0) {
-    std::snprintf(buf, buflen, "%s/s1", hconv_variant_name(hconv_index(variant_id)));
+    std::snprintf(buf, buflen, "%s/s%d", hconv_variant_name(hconv_index(variant_id)),
+                  hconv_variant_split(hconv_index(variant_id)));
     return BCONV_OK;
   }
   int t, nsplit;

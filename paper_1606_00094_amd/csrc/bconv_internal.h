@@ -36,8 +36,9 @@ typedef hipError_t (*TileLaunchFn)(const TconvParams& p, dim3 grid, size_t lds_b
 // f16: in, filt and out address _Float16 elements (bias and partial sums are fp32 always).
 hipError_t launch_direct_conv(const float* in, const float* filt, const float* bias, float* out,
                               const Shape& s, int relu, bool f16, hipStream_t st);
+// (c8: the output is octet-interleaved, [N][K/8][PQ][8]; only the bias index depends on it)
 hipError_t launch_splitk_reduce(const float* partial, const float* bias, float* out, int nsplit,
-                                int out_elems, int K, int PQ, int relu, bool f16, hipStream_t st);
+                                int out_elems, int K, int PQ, int relu, bool f16, bool c8, hipStream_t st);
 hipError_t launch_splitk_reduce_pool(const float* partial, const float* bias, float* out, int nsplit,
                                      int out_elems, int N, int K, int P, int Q, int ksz, int pstride,
                                      int relu, hipStream_t st);
@@ -82,7 +83,10 @@ hipError_t launch_hconv(int which, const void* in, const void* filt, const float
                         const Shape& s, int relu, int in_c8, int out_c8, void* ws, hipStream_t st);
 hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st);
 hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
-                               const Shape& s, int relu, int in_c8, int out_c8, hipStream_t st);
+                               const Shape& s, int relu, int in_c8, int out_c8, void* scratch, hipStream_t st);
+int hconv_variant_split(int which);                       // reduction split of a catalogue entry
+size_t hconv_packed_bytes(int which, const Shape& s);     // re-laid filters alone
+size_t hconv_partial_bytes(int which, const Shape& s);    // partial sums of a split variant (else 0)
 // fp16 activations between NCHW and the octet-interleaved layout [N][C/8][H*W][8]
 // (n_times_c = N * C, a multiple of eight); to_c8 = 1: NCHW -> C8, 0: back.
 // Max pooling of fp16 activations, NCHW (c8 = 0) or octet-interleaved (c8 = 1).

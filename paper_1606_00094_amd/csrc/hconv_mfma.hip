@@ -47,6 +47,7 @@ namespace bconv {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float hacc_t __attribute__((ext_vector_type(16)));
 typedef unsigned uquad __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 struct HconvParams {
   TconvParams g;            // shape and halo geometry; g.in / g.out address _Float16 elements
@@ -54,6 +55,8 @@ struct HconvParams {
   int nch;                  // chunks of CC channels
   int npos;                 // staged positions per octet plane
   int coct;                 // C / 8
+  int nsplit, cps;          // reduction split over the grid's z: chunks [z*cps, z*cps+cps) each
+  float* partial;           // nsplit > 1: fp32 partial sums [nsplit][out_elems], indexed like out
 };
 
 // TR: kernel rows of a chunk's filters staged at a time (R_: the whole chunk in one stage; 1: a
@@ -89,7 +92,10 @@ void hconv_mfma_kernel(const HconvParams hp) {
   const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, gq = lane >> 5;
 
-  const BlockTile bt = xcd_tile(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x, gridDim.y, 1, p.filter_major);
+  const BlockTile bt = xcd_tile(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), gridDim.x,
+                                gridDim.y, gridDim.z, p.filter_major);
+  const int ch_begin = bt.z * hp.cps;
+  const int ch_end = ch_begin + hp.cps < hp.nch ? ch_begin + hp.cps : hp.nch;   // (host: ch_begin < nch)
   const PixTile t = pix_tile(bt.x, BN, p.NPQ, p.Q, p.fdQ);
   const HaloTile ht = PW ? HaloTile{0, 0} : halo_tile(p, t);
   const int m0 = bt.y * BM;
@@ -272,18 +278,18 @@ void hconv_mfma_kernel(const HconvParams hp) {
   // the loads of stage it + 1 (its filters; at the first stage of a chunk also the next chunk's
   // halo) are in flight; they are written to the other buffers afterwards, the halo at the
   // chunk's last stage.  One barrier per stage.
-  load_a(0, 0);
-  load_b(0);
+  load_a(ch_begin, 0);
+  load_b(ch_begin);
   store_a(0);
-  store_b(0);
+  store_b(ch_begin & 1);
   __syncthreads();
   {
-    int ch = 0, rr = 0;
-    const int nstages = hp.nch * NRS;
+    int ch = ch_begin, rr = 0;
+    const int nstages = (ch_end - ch_begin) * NRS;
     for (int it = 0; it < nstages; ++it) {
       const bool more = it + 1 < nstages;
       const bool last_of_chunk = rr == NRS - 1;
-      const bool more_ch = ch + 1 < hp.nch;
+      const bool more_ch = ch + 1 < ch_end;
       if (more) load_a(last_of_chunk ? ch + 1 : ch, last_of_chunk ? 0 : rr + 1);
       if (rr == 0 && more_ch) load_b(ch + 1);
       __builtin_amdgcn_sched_barrier(0);   // the loads are in flight before the first operand read
@@ -293,6 +299,43 @@ void hconv_mfma_kernel(const HconvParams hp) {
       __syncthreads();
       if (last_of_chunk) { rr = 0; ++ch; } else { ++rr; }
     }
+  }
+
+  // ---- a split reduction: this workgroup's fp32 partial sums, in the output's own index order
+  // (the reduction kernel adds the splits, the bias and the ReLU and rounds once)
+  if (hp.nsplit > 1) {
+    float* const part = hp.partial + (size_t)bt.z * p.out_elems;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      if constexpr (C8O) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int k = m0 + (wm * MT + mt) * 32 + g * 8 + gq * 4;
+          if (k < p.K) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+              if (colvalid[nt]) {
+                floatx4 v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = acc[mt][nt][4 * g + j];
+                *reinterpret_cast<floatx4*>(part + outoff[nt] + (k - gq * 4) * p.PQ) = v;
+              }
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int k = m0 + (wm * MT + mt) * 32 + acc_row_32(lane, i);
+          if (k < p.K) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              if (colvalid[nt]) part[outoff[nt] + k * p.PQ] = acc[mt][nt][i];
+          }
+        }
+      }
+    }
+    return;
   }
 
   // ---- epilogue: bias + optional ReLU, one rounding to fp16, store
@@ -567,23 +610,34 @@ static const HTile kHTiles[] = {
 };
 constexpr int kNumHTiles = (int)(sizeof(kHTiles) / sizeof(kHTiles[0]));
 
-// The catalogue of the fp16-matrix-core kernels: the channel-octet tiles of this file, then the
+// The catalogue of the fp16-matrix-core kernels: the channel-octet tiles of this file, each with
+// the reduction splits of kHSplits (index = tile * kNumHSplits + split index), then the
 // first-layer tiles (hconv_first.hip), which take NCHW activations and unpacked filters only.
-int hconv_num_variants() { return kNumHTiles + hfl_num_variants(); }
+static const int kHSplits[] = {1, 2, 3, 4, 6, 8};
+constexpr int kNumHSplits = (int)(sizeof(kHSplits) / sizeof(kHSplits[0]));
+constexpr int kNumOctet = kNumHTiles * kNumHSplits;
+int hconv_num_variants() { return kNumOctet + hfl_num_variants(); }
 const char* hconv_variant_name(int which) {
-  return which < kNumHTiles ? kHTiles[which].name : hfl_variant_name(which - kNumHTiles);
+  return which < kNumOctet ? kHTiles[which / kNumHSplits].name : hfl_variant_name(which - kNumOctet);
 }
-bool hconv_packable(int which) { return which >= 0 && which < kNumHTiles; }
+int hconv_variant_split(int which) { return which < kNumOctet ? kHSplits[which % kNumHSplits] : 1; }
+bool hconv_packable(int which) { return which >= 0 && which < kNumOctet; }
 
 struct HPlan {
   HconvParams hp;
-  unsigned gx, gy;
+  unsigned gx, gy, gz;
   size_t lds_bytes;
   size_t filt2_bytes;
+  size_t partial_bytes;     // 0 for an unsplit variant
 };
 
+static size_t h_align(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// `which` indexes the channel-octet part of the catalogue (tile and reduction split).
 static bool plan_hconv(int which, const Shape& s0, HPlan* pl) {
-  const HTile& v = kHTiles[which];
+  if (which < 0 || which >= kNumOctet) return false;
+  const HTile& v = kHTiles[which / kNumHSplits];
+  const int nsplit = kHSplits[which % kNumHSplits];
   Shape s = s0;
   if (s.R != v.R || s.S != v.S || s.stride != 1 || s.C % 8 != 0) return false;
   const long long i31 = (1LL << 31) - 1;
@@ -633,22 +687,41 @@ static bool plan_hconv(int which, const Shape& s0, HPlan* pl) {
   if ((long long)pl->filt2_bytes > i31) return false;
   const long long gy = (s.K + BM - 1) / BM;
   if (gy > 65535) return false;
+  // every split takes the same number of chunks and none is empty
+  const int cps = (pl->hp.nch + nsplit - 1) / nsplit;
+  if ((nsplit - 1) * cps >= pl->hp.nch) return false;
+  pl->hp.nsplit = nsplit;
+  pl->hp.cps = cps;
+  pl->partial_bytes = nsplit > 1 ? (size_t)nsplit * p.out_elems * 4 : 0;
+  if ((long long)nsplit * p.out_elems > i31) return false;
   pl->gx = (unsigned)ntiles;
   pl->gy = (unsigned)gy;
+  pl->gz = (unsigned)nsplit;
   pl->lds_bytes = lds;
   return true;
 }
 
 bool hconv_applicable(int which, const Shape& s) {
-  if (which >= kNumHTiles) return hfl_applicable(which - kNumHTiles, s);
+  if (which >= kNumOctet) return hfl_applicable(which - kNumOctet, s);
   HPlan pl;
   return plan_hconv(which, s, &pl);
 }
 
+// Device scratch of the per-call path: the re-laid filters, then the partial sums of a split.
 size_t hconv_workspace_bytes(int which, const Shape& s) {
-  if (which >= kNumHTiles) return hfl_workspace_bytes(which - kNumHTiles, s);
+  if (which >= kNumOctet) return hfl_workspace_bytes(which - kNumOctet, s);
+  HPlan pl;
+  if (!plan_hconv(which, s, &pl)) return 0;
+  return pl.partial_bytes ? h_align(pl.filt2_bytes) + pl.partial_bytes : pl.filt2_bytes;
+}
+// ... the two parts on their own (packed calls: the caller keeps the filters, the library the sums)
+size_t hconv_packed_bytes(int which, const Shape& s) {
   HPlan pl;
   return plan_hconv(which, s, &pl) ? pl.filt2_bytes : 0;
+}
+size_t hconv_partial_bytes(int which, const Shape& s) {
+  HPlan pl;
+  return plan_hconv(which, s, &pl) ? pl.partial_bytes : 0;
 }
 
 // The tile the half-precision entry points take for a shape the half-precision table does not
@@ -661,10 +734,10 @@ int hconv_select(const Shape& s, bool any_size) {
   if (!any_size && (long long)s.N * s.P * s.Q < 1024) return -1;
   int best = -1;
   double best_cost = 0.0;
-  for (int w = 0; w < kNumHTiles; ++w) {
+  for (int w = 0; w < kNumOctet; w += kNumHSplits) {      // unsplit variants
     HPlan pl;
     if (!plan_hconv(w, s, &pl)) continue;
-    const HTile& v = kHTiles[w];
+    const HTile& v = kHTiles[w / kNumHSplits];
     const double wgs = (double)pl.gx * pl.gy;
     const double per_cu = (double)(((long long)wgs + 255) / 256);
     int resident = (int)(kLdsLimitBytes / pl.lds_bytes);
@@ -674,6 +747,17 @@ int hconv_select(const Shape& s, bool any_size) {
     const double cost = per_cu * ((double)v.BM() * v.BN() * (1.0 + 16.0 / v.BM() + 16.0 / v.BN()) + 3000.0) / eff;
     if (best < 0 || cost < best_cost) { best = w; best_cost = cost; }
   }
+  if (best >= 0) {
+    // a grid that leaves most of the chip idle: the largest split that still fits it
+    HPlan pl;
+    plan_hconv(best, s, &pl);
+    const long long wgs = (long long)pl.gx * pl.gy;
+    for (int si = kNumHSplits - 1; si > 0; --si) {
+      if (wgs * kHSplits[si] > 384) continue;
+      HPlan ps;
+      if (plan_hconv(best + si, s, &ps)) { best += si; break; }
+    }
+  }
   if (best < 0) {
     // a first layer (measured faster than the widening kernel from batch 1 up): the widest
     // pixel tile that still gives every compute unit a tile, else the narrowest
@@ -681,9 +765,9 @@ int hconv_select(const Shape& s, bool any_size) {
     for (int f = 0; f < hfl_num_variants(); ++f) {
       if (!hfl_applicable(f, s)) continue;
       narrowest = f;
-      if (hfl_tiles(f, s) >= 256) return kNumHTiles + f;
+      if (hfl_tiles(f, s) >= 256) return kNumOctet + f;
     }
-    if (narrowest >= 0) return kNumHTiles + narrowest;
+    if (narrowest >= 0) return kNumOctet + narrowest;
   }
   return best;
 }
@@ -692,7 +776,7 @@ int hconv_select(const Shape& s, bool any_size) {
 hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st) {
   HPlan pl;
   if (!hconv_packable(which) || !plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
-  const HTile& v = kHTiles[which];
+  const HTile& v = kHTiles[which / kNumHSplits];
   const long long total = (long long)(pl.filt2_bytes / 2);
   long long blocks = (total + 255) / 256;
   if (blocks > 8192) blocks = 8192;
@@ -703,30 +787,40 @@ hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Sh
 
 // The convolution itself on filters that launch_hconv_pack re-laid for the same tile and shape;
 // in_c8 / out_c8 say which activations are octet-interleaved (C8 out needs K % 8 == 0; NCHW in
-// with C8 out is not built).
+// with C8 out is not built).  A split variant leaves its partial sums in `scratch`
+// (hconv_partial_bytes, 16-byte aligned) and a reduction kernel finishes the layer.
 hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
-                               const Shape& s, int relu, int in_c8, int out_c8, hipStream_t st) {
+                               const Shape& s, int relu, int in_c8, int out_c8, void* scratch, hipStream_t st) {
   HPlan pl;
   if (!hconv_packable(which) || !plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
   if (out_c8 && (!in_c8 || s.K % 8 != 0)) return hipErrorInvalidValue;
+  if (pl.partial_bytes && !scratch) return hipErrorInvalidValue;
   pl.hp.g.in = static_cast<const float*>(in);
   pl.hp.g.bias = bias;
   pl.hp.g.out = static_cast<float*>(out);
   pl.hp.g.relu = relu;
   pl.hp.filt2 = static_cast<const _Float16*>(packed);
-  const HLaunchFn fn = out_c8 ? hconv_launch_l2(which) : (in_c8 ? hconv_launch_l1(which) : hconv_launch_l0(which));
-  return fn(pl.hp, dim3(pl.gx, pl.gy), pl.lds_bytes, st);
+  pl.hp.partial = static_cast<float*>(scratch);
+  const HLaunchFn fn = out_c8 ? hconv_launch_l2(which / kNumHSplits)
+                              : (in_c8 ? hconv_launch_l1(which / kNumHSplits) : hconv_launch_l0(which / kNumHSplits));
+  hipError_t e = fn(pl.hp, dim3(pl.gx, pl.gy, pl.gz), pl.lds_bytes, st);
+  if (e != hipSuccess || !pl.partial_bytes) return e;
+  return launch_splitk_reduce(pl.hp.partial, bias, static_cast<float*>(out), pl.hp.nsplit, pl.hp.g.out_elems, s.K,
+                              s.P * s.Q, relu, true, out_c8 != 0, st);
 }
 
 hipError_t launch_hconv(int which, const void* in, const void* filt, const float* bias, void* out,
                         const Shape& s, int relu, int in_c8, int out_c8, void* ws, hipStream_t st) {
-  if (which >= kNumHTiles) {
+  if (which >= kNumOctet) {
     if (in_c8) return hipErrorInvalidValue;
-    return launch_hfl(which - kNumHTiles, in, filt, bias, out, s, relu, out_c8, ws, st);
+    return launch_hfl(which - kNumOctet, in, filt, bias, out, s, relu, out_c8, ws, st);
   }
+  HPlan pl;
+  if (!plan_hconv(which, s, &pl)) return hipErrorInvalidValue;
   hipError_t e = launch_hconv_pack(which, filt, ws, s, st);
   if (e != hipSuccess) return e;
-  return launch_hconv_packed(which, in, ws, bias, out, s, relu, in_c8, out_c8, st);
+  void* scratch = pl.partial_bytes ? static_cast<char*>(ws) + h_align(pl.filt2_bytes) : nullptr;
+  return launch_hconv_packed(which, in, ws, bias, out, s, relu, in_c8, out_c8, scratch, st);
 }
 
 #endif  // HCONV_LAYOUT == 0

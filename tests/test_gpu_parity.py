@@ -720,7 +720,8 @@ def test_fuzz_random_variants_exact_on_integers():
     nv = binding.conv_num_variants()
     fam = {"pw": (1, 1, 1), "k3": (3, 3, 1), "k5": (5, 5, 1), "k11s4": (11, 11, 4), "k7s2": (7, 7, 2),
            "pws2": (1, 1, 2), "k3s2": (3, 3, 2), "k1x7": (1, 7, 1), "k7x1": (7, 1, 1),
-           "fmaq4": (11, 11, 4), "fmaq2": (7, 7, 2), "h16k3": (3, 3, 1), "h16k5": (5, 5, 1), "h16pw": (1, 1, 1)}
+           "fmaq4": (11, 11, 4), "fmaq2": (7, 7, 2), "h16k3": (3, 3, 1), "h16k5": (5, 5, 1), "h16pw": (1, 1, 1),
+           "h16k11s4": (11, 11, 4), "h16k7s2": (7, 7, 2)}
     ran = 0
     for it in range(500):
         v = int(rng.integers(1, nv))

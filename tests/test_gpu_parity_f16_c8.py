@@ -103,20 +103,22 @@ def test_c8_every_matrix_core_tile_exact_on_integers(tile):
     """Each fp16-matrix-core tile on C8 input, writing C8 (where K is a multiple of eight) and
     NCHW, on the ragged shapes of its family: bitwise equal to the oracle."""
     fam = _family_of(tile)
-    (v,) = _tile_families()[tile]
     ran = 0
     for shp in FAMILY_SHAPES[fam] + C8_SHAPES[fam]:
         N, C, H, W, K, pad = shp
         R, S, stride = fam
-        if C % 8 or not binding.conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+        if C % 8:
             continue
         x, f, b = workloads.make_integer_problem(len(tile) + sum(shp), N, C, H, W, K, R, S)
         x, f = x.astype(np.float16), f.astype(np.float16)
         ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=False)
-        for c8_out in ((True, False) if K % 8 == 0 else (False,)):
-            got = gpu_conv_c8(x, f, b, stride, pad, False, v, c8_out)
-            assert np.array_equal(got, ref), "%s on %s, C8 out %s" % (tile, shp, c8_out)
-            ran += 1
+        for v in _tile_families()[tile]:          # unsplit and every reduction split that applies
+            if not binding.conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
+                continue
+            for c8_out in ((True, False) if K % 8 == 0 else (False,)):
+                got = gpu_conv_c8(x, f, b, stride, pad, False, v, c8_out)
+                assert np.array_equal(got, ref), "%s on %s, C8 out %s" % (binding.conv_variant_name(v), shp, c8_out)
+                ran += 1
     assert ran > 0
 
 
@@ -331,8 +333,9 @@ def test_c8_tiles_keep_an_infinity_inside_its_windows(fam):
     finite = np.isfinite(ref)
     assert 0 < (~finite).sum() < ref.size
     ran = 0
-    for tile, (v,) in sorted((t, ids) for t, ids in _tile_families().items()
-                             if t.startswith("h16") and _family_of(t) == fam):
+    for tile, ids in sorted((t, ids) for t, ids in _tile_families().items()
+                            if t.startswith("h16") and _family_of(t) == fam):
+        v = ids[0]
         if not binding.conv_fwd_f16_variant_applicable(N, C, H, W, K, R, S, stride, pad, v):
             continue
         got = gpu_conv_c8(x, f, b, stride, pad, False, v, True)
