@@ -583,6 +583,8 @@ def main():
     rows16 = [r for r in table_f16 if r["N"] == args.batch]
     for r in rows16:
         per_layer_f16[r["layer"]] = [r["us"], round(r["gflops"] / 1e3, 1), r.get("us_prepacked"), r.get("us_c8")]
+    # ... and at batch 1 (per-call NCHW path, and C8 activations with packed filters)
+    per_layer_f16_b1 = {r["layer"]: [r["us"], r.get("us_c8")] for r in table_f16 if r["N"] == 1}
     if rows16:
         # the largest layer of the native half-precision configuration (C8 activations, packed
         # filters) against the fp16 matrix peak; NCHW per-call figures where no such tile applies
@@ -623,6 +625,7 @@ def main():
         "stack_f16_ms": {str(r["N"]): r["ms"] for r in stack16},
         "measured_peaks": measured,
         "per_layer_f16_columns": ["us_b%d" % args.batch, "tflops", "us_filters_prepacked", "us_c8_activations"], "per_layer_f16": per_layer_f16,
+        "per_layer_f16_b1_columns": ["us_b1", "us_b1_c8_activations"], "per_layer_f16_b1": per_layer_f16_b1,
         "roofline_f16": roof16,
         "cpu_baseline": cpu, "roofline_batch1": roof1, "roofline": roof,
     }), flush=True)
