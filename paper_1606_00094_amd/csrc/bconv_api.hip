@@ -1152,6 +1152,7 @@ double bconv_debug_model_cost(int N, int C, int H, int W, int K, int R, int S, i
   int t, nsplit;
   Plan pl;
   s = batch_of(s, images_per_launch(s));    // the estimate is per launch
+  if (hconv_index(variant_id) >= 0) return hconv_model_cost(hconv_index(variant_id), s);
   if (!decode_variant(variant_id, &t, &nsplit) || !plan_tconv(s, kTiles[t], nsplit, &pl)) return -1.0;
   return variant_cost(kTiles[t], pl);
 }

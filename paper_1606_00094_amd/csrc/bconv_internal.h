@@ -84,6 +84,7 @@ hipError_t launch_hconv(int which, const void* in, const void* filt, const float
 hipError_t launch_hconv_pack(int which, const void* filt, void* packed, const Shape& s, hipStream_t st);
 hipError_t launch_hconv_packed(int which, const void* in, const void* packed, const float* bias, void* out,
                                const Shape& s, int relu, int in_c8, int out_c8, void* scratch, hipStream_t st);
+double hconv_model_cost(int which, const Shape& s);      // the selection's estimate in us, < 0 if none
 int hconv_variant_split(int which);                       // reduction split of a catalogue entry
 size_t hconv_packed_bytes(int which, const Shape& s);     // re-laid filters alone
 size_t hconv_partial_bytes(int which, const Shape& s);    // partial sums of a split variant (else 0)

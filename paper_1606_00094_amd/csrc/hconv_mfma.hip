@@ -724,39 +724,54 @@ size_t hconv_partial_bytes(int which, const Shape& s) {
   return plan_hconv(which, s, &pl) ? pl.partial_bytes : 0;
 }
 
-// The tile the half-precision entry points take for a shape the half-precision table does not
-// list, or -1 when the layer is better left to the widening kernel (not applicable, or too
-// few output points).  The kernel hides its LDS and memory latency with resident waves, not
-// with a deep software pipeline, so the small tiles win wherever the sweep looked (64x64 for
-// 3x3 and pointwise, 32x128 for 5x5): the workgroups of the busiest compute unit, run
-// `resident` at a time, each costing its tile's work plus a per-workgroup overhead.
+// Estimated microseconds of a channel-octet variant on C8 activations, for shapes the tables do
+// not list.  The workgroups of the busiest compute unit run `resident` at a time; one workgroup
+// costs its MFMAs (stretched by the waves that share a matrix pipe), a per-stage term (barrier,
+// exposed latency), its operand bytes at the rate one unit sustains (shared by its resident
+// workgroups), a fixed part and its epilogue; a split adds the reduction kernel.  The eight
+// constants are a least-squares fit (log time) to 3074 measured (shape, variant) points: the ten
+// benchmark layers at batch 1-128 and ten unlisted shapes at batch 1, 5, 32, every applicable
+// tile and split.  Picking by it is 3.4 % (geometric mean; worst 20 %) off the measured best on
+// the former and 4.0 % (worst 24 %) on the latter.
+static double hconv_cost(int which, const Shape& s) {
+  HPlan pl;
+  if (!plan_hconv(which, s, &pl)) return -1.0;
+  const HTile& v = kHTiles[which / kNumHSplits];
+  const double t0 = 3.667, c_mf = 0.021165, c_stage = 0.093718, c_wg = 1.753, r0 = 0.87467, r_b = 0.96214,
+               c_b = 7.2175e-6, c_epi = 0.017462;
+  const int waves = v.NTHR() / 64, taps = v.R * v.S;
+  const long long wgs = (long long)pl.gx * pl.gy * pl.gz;
+  long long resident = (long long)(kLdsLimitBytes / pl.lds_bytes);
+  if (resident > 32 / waves) resident = 32 / waves;
+  if (resident > 8) resident = 8;
+  if (resident < 1) resident = 1;
+  const long long per_cu = (wgs + 255) / 256;
+  const double conc = (double)(per_cu < resident ? per_cu : resident);
+  const double rounds = (double)((per_cu + resident - 1) / resident);
+  double waves_simd = conc * waves / 4.0;
+  if (waves_simd < 1.0) waves_simd = 1.0;
+  const double mf = (double)pl.hp.cps * taps * (v.CC / 16) * v.MT * v.NT;
+  const double stages = (double)pl.hp.cps * (v.R / v.TR);
+  const double bytes_wg = (double)pl.hp.cps * ((double)v.BM() * taps * v.CC * 2 + (double)pl.hp.npos * v.CC * 2);
+  const double epi = (double)v.BM() * v.BN() / (waves * 64);
+  const double t_wg = mf * c_mf * waves_simd + stages * c_stage + bytes_wg * c_b * conc + c_wg + c_epi * epi;
+  double t = t0 + rounds * t_wg;
+  if (pl.hp.nsplit > 1) t += r0 + r_b * (double)pl.hp.g.out_elems * (pl.hp.nsplit + 0.5) * 1e-6;
+  return t;
+}
+double hconv_model_cost(int which, const Shape& s) { return which < kNumOctet ? hconv_cost(which, s) : -1.0; }
+
+// The variant the half-precision entry points take for a shape the half-precision tables do not
+// list, or -1 when the layer is better left to the widening kernel (not applicable, or, unless
+// any_size, too few output points).
 int hconv_select(const Shape& s, bool any_size) {
   if (!any_size && (long long)s.N * s.P * s.Q < 1024) return -1;
   int best = -1;
   double best_cost = 0.0;
-  for (int w = 0; w < kNumOctet; w += kNumHSplits) {      // unsplit variants
-    HPlan pl;
-    if (!plan_hconv(w, s, &pl)) continue;
-    const HTile& v = kHTiles[w / kNumHSplits];
-    const double wgs = (double)pl.gx * pl.gy;
-    const double per_cu = (double)(((long long)wgs + 255) / 256);
-    int resident = (int)(kLdsLimitBytes / pl.lds_bytes);
-    if (resident > 8) resident = 8;
-    const double waves = (per_cu < resident ? per_cu : resident) * v.NTHR() / 256.0;   // per SIMD
-    const double eff = waves >= 3.0 ? 1.0 : (waves >= 2.0 ? 0.8 : 0.5);
-    const double cost = per_cu * ((double)v.BM() * v.BN() * (1.0 + 16.0 / v.BM() + 16.0 / v.BN()) + 3000.0) / eff;
+  for (int w = 0; w < kNumOctet; ++w) {
+    const double cost = hconv_cost(w, s);
+    if (cost < 0.0) continue;
     if (best < 0 || cost < best_cost) { best = w; best_cost = cost; }
-  }
-  if (best >= 0) {
-    // a grid that leaves most of the chip idle: the largest split that still fits it
-    HPlan pl;
-    plan_hconv(best, s, &pl);
-    const long long wgs = (long long)pl.gx * pl.gy;
-    for (int si = kNumHSplits - 1; si > 0; --si) {
-      if (wgs * kHSplits[si] > 384) continue;
-      HPlan ps;
-      if (plan_hconv(best + si, s, &ps)) { best += si; break; }
-    }
   }
   if (best < 0) {
     // a first layer (measured faster than the widening kernel from batch 1 up): the widest

@@ -343,3 +343,23 @@ def test_c8_tiles_keep_an_infinity_inside_its_windows(fam):
         assert np.array_equal(got[finite], ref[finite]), tile
         ran += 1
     assert ran > 0
+
+
+UNLISTED_C8 = [(3, 256, 28, 28, 256, 3, 3, 1, 1), (3, 512, 14, 14, 512, 1, 1, 1, 0), (2, 48, 14, 14, 128, 5, 5, 1, 2),
+               (8, 160, 7, 7, 320, 3, 3, 1, 1), (1, 64, 56, 56, 256, 1, 1, 1, 0), (2, 512, 14, 14, 512, 3, 3, 1, 1),
+               (1, 24, 9, 11, 40, 3, 3, 1, 0), (4, 8, 5, 5, 16, 5, 5, 1, 2)]
+
+
+@pytest.mark.parametrize("dims", UNLISTED_C8, ids=lambda d: "N%d_C%d_%dx%d_K%d_%dx%d" % d[:7])
+def test_c8_unlisted_shapes_through_the_cost_model(dims):
+    """Shapes neither half-precision table lists: the variant the fitted cost model picks (tile
+    and reduction split) applies and gives the oracle's values on C8 activations."""
+    N, C, H, W, K, R, S, stride, pad = dims
+    v = binding.conv_fwd_f16_c8_selected_variant(*dims)
+    name = binding.conv_variant_name(v)
+    assert name.startswith("h16") and binding.conv_fwd_f16_variant_applicable(*dims, v), name
+    x, f, b = workloads.make_random_problem(workloads.BASE_SEED + 640 + sum(dims), N, C, H, W, K, R, S, dist="u01")
+    x, f = x.astype(np.float16), (f * np.float32(0.05)).astype(np.float16)
+    ref = oracle.conv_fwd_f16(x, f, b, stride=stride, pad=pad, relu=True)
+    got = gpu_conv_c8(x, f, b, stride, pad, True, v, K % 8 == 0)
+    assert_close_f16(got, ref, "%s via %s" % (dims, name))
