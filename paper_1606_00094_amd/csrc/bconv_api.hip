@@ -633,6 +633,12 @@ static long long audit(const Shape& s, const TileDesc& v, const Plan& pl) {
       }
     }
   }
+  // Input reads of the last chunk under flat staging: a thread's own plane offset can carry it up
+  // to one chunk of planes past the last channel -- into the next image, or past the tensor for
+  // the last image, where the range check returns zero; the kernel zeroes those cells in LDS by
+  // the same predicate that would have masked the load.  What the host has to guarantee is that
+  // the byte offset of such a read cannot wrap around 2^32 back into the tensor.
+  if (((long long)in_elems + p.gbias + (long long)planes * p.HW + 4) * 4 > (1LL << 32)) ++bad;
   // Filter reads.  A staged item is AV consecutive words of one filter row, at the chunk's
   // column offset col0 = chunk * KR * S plus the item's column j.  Only the last chunk can
   // reach past the end of its row (every earlier one ends at or before (nchunks-1)*KR*S <
