@@ -229,3 +229,39 @@ def test_batches_beyond_one_launch_are_planned_as_runs_of_images():
     assert binding.conv_variant_name(binding.conv_selected_variant(2, 16, 6000, 6000, 2, 3, 3, 1, 0)) == "direct"
     # small shapes are untouched: an audit over a toy batch counts one launch
     assert binding.bconv_debug_audit(3, 5, 9, 9, 7, 3, 3, 1, 1, binding.conv_selected_variant(3, 5, 9, 9, 7, 3, 3, 1, 1)) == 0
+
+
+def test_half_precision_selection_on_random_shapes_without_a_gpu():
+    """The half-precision queries on seeded random stride-1 shapes: the choice for C8 activations
+    is an applicable fp16-matrix-core variant whose estimate is the smallest among the applicable
+    ones, its workspace covers the packed filters, and shapes those tiles cannot serve have no
+    C8 choice."""
+    import numpy as np
+    rng = np.random.default_rng(20160601)
+    names = {v: binding.conv_variant_name(v) for v in range(binding.conv_num_variants())}
+    h16 = [v for v, n in names.items() if n.startswith("h16") and not n.startswith(("h16k11s4", "h16k7s2"))]
+    lib = binding.lib()
+    checked = 0
+    for _ in range(40):
+        R = int(rng.choice([1, 3, 5]))
+        N, C, K = int(rng.integers(1, 40)), 8 * int(rng.integers(1, 40)), int(rng.integers(1, 300))
+        H, W = int(rng.integers(R, 40)), int(rng.integers(R, 40))
+        pad = 0 if R == 1 else int(rng.integers(0, R // 2 + 1))
+        dims = (N, C, H, W, K, R, R, 1, pad)
+        v = binding.conv_fwd_f16_c8_selected_variant(*dims)
+        assert v in h16 and binding.conv_fwd_f16_variant_applicable(*dims, v), (dims, names[v])
+        costs = {u: binding.bconv_debug_model_cost(*dims, u) for u in h16
+                 if binding.conv_fwd_f16_variant_applicable(*dims, u)}
+        assert all(c > 0 for c in costs.values())
+        assert costs[v] <= min(costs.values()) * (1 + 1e-12) or _listed_c8(dims), (dims, names[v])
+        assert binding.conv_fwd_f16_workspace_bytes(*dims, v) >= binding.conv_f16_packed_filter_bytes(*dims, v) > 0
+        checked += 1
+    assert checked == 40
+    assert lib.conv_fwd_f16_c8_selected_variant(2, 12, 9, 9, 8, 3, 3, 1, 1) == -6      # C % 8 != 0
+    assert lib.conv_fwd_f16_c8_selected_variant(2, 16, 9, 9, 8, 3, 3, 2, 1) == -6      # stride 2
+    assert lib.conv_fwd_f16_c8_selected_variant(2, 16, 9, 9, 8, 7, 7, 1, 3) == -6      # 7x7
+
+
+def _listed_c8(dims):
+    text = open(os.path.join(ROOT, "paper_1606_00094_amd", "csrc", "f16_c8_selection_table.inc")).read()
+    return ("{%d, %d, %d, %d, %d, %d, %d, %d, %d," % dims) in text
